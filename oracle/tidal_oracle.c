@@ -1,0 +1,196 @@
+/*
+ * tidal_oracle.c -- CPU oracle for the template-materialization + LoRA hot path.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Only tests, the smoke check
+ * and the benchmark's "cpu_baseline" leg may load it.  It shares no code,
+ * header, table or helper with the HIP library; it is plain single-threaded
+ * C99, every floating-point step written out in the order the definition
+ * states, with no blocking, fusion or reordering.
+ *
+ * What it follows.  The paper frames a function *template*: pre-initialised
+ * function state kept in GPU memory from which new invocations start (Sec. 1,
+ * "template-start"; Sec. 4.2, the template's re-ordered weight layout), plus
+ * per-request *dynamic initialisation* (LoRA adapters attached to a shared
+ * base model, Sec. 1 and Sec. 5.2 "Adaptive template state reusing"), with
+ * only the dynamic part re-initialised while the function is kept alive
+ * (Sec. 5.2 "Keep-alive of dynamic function").  The paper prints no formula
+ * for any of this; the arithmetic below is the plain definition of
+ *   - slot placement in access order (Sec. 4.2),
+ *   - IEEE-754 narrowing fp32/fp16 -> bfloat16, round-to-nearest-even,
+ *   - the LoRA merge  W' = W + (alpha/r) * B * A  with fp32 accumulation and
+ *     bf16 (or fp32) storage, and swap = unmerge(old) then merge(new).
+ *
+ * Pins (see tests/test_oracle_*.py): conversion is checked against an
+ * independent value-based nearest/ties-to-even search in float64 and against
+ * library conversions; the merge against float64 brute force, the rank-1
+ * closed form, zero-operand identities, merge/unmerge bounds and shape /
+ * transposition / sign / scale mutation cases; placement against the closed
+ * form and the 13B weight footprint of the paper's model-size table.
+ * The adapter-churn replay (a sequence of swaps) has no closed form: it is
+ * pinned only through the single-swap pins and determinism -- the churn
+ * sequence as a whole is "parity unpinned" against the paper.
+ *
+ * Build: gcc -std=c99 -O2 -mfma -ffp-contract=off -fPIC -shared
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+enum { ORC_F32 = 0, ORC_F16 = 1, ORC_BF16 = 2 };
+
+/* ---------------------------------------------------------------------------
+ * Number formats
+ * ------------------------------------------------------------------------- */
+
+static float bits_to_float(uint32_t u) {
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+static uint32_t float_to_bits(float f) {
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return u;
+}
+
+/* IEEE binary16 -> binary32, exact (every binary16 value is a binary32 value).
+ * Written on the bit fields: sign(1) exponent(5, bias 15) fraction(10). */
+uint32_t orc_f16_bits_to_f32_bits(uint16_t h) {
+    uint32_t sign = (uint32_t)(h >> 15) << 31;
+    uint32_t e = (h >> 10) & 0x1Fu;
+    uint32_t f = h & 0x3FFu;
+    if (e == 0x1Fu) {                         /* inf / NaN: keep payload at the top */
+        return sign | 0x7F800000u | (f << 13);
+    }
+    if (e == 0) {
+        if (f == 0) return sign;              /* +-0 */
+        /* subnormal: value = f * 2^-24; normalise into binary32 */
+        int shift = 0;
+        while ((f & 0x400u) == 0) { f <<= 1; ++shift; }
+        f &= 0x3FFu;
+        uint32_t e32 = (uint32_t)(127 - 15 + 1 - shift);
+        return sign | (e32 << 23) | (f << 13);
+    }
+    return sign | ((e + (127 - 15)) << 23) | (f << 13);
+}
+
+/* IEEE binary32 -> bfloat16 (sign 1, exponent 8, fraction 7), round to nearest,
+ * ties to even, no flush of subnormals; overflow rounds to infinity; NaN stays
+ * NaN: sign and upper payload kept, quiet bit forced. */
+uint16_t orc_f32_bits_to_bf16_bits(uint32_t u) {
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) {
+        return (uint16_t)((u >> 16) | 0x0040u);
+    }
+    uint32_t keep_lsb = (u >> 16) & 1u;
+    uint32_t rounded = u + 0x7FFFu + keep_lsb;
+    return (uint16_t)(rounded >> 16);
+}
+
+/* bfloat16 -> binary32, exact */
+static float bf16_to_float(uint16_t b) { return bits_to_float((uint32_t)b << 16); }
+
+static uint16_t float_to_bf16(float f) { return orc_f32_bits_to_bf16_bits(float_to_bits(f)); }
+
+/* Convert n elements of `dtype` at src to bf16 at dst. */
+void orc_convert_to_bf16(const void* src, int dtype, int64_t n, uint16_t* dst) {
+    int64_t i;
+    if (dtype == ORC_F32) {
+        const uint32_t* s = (const uint32_t*)src;
+        for (i = 0; i < n; ++i) dst[i] = orc_f32_bits_to_bf16_bits(s[i]);
+    } else if (dtype == ORC_F16) {
+        const uint16_t* s = (const uint16_t*)src;
+        for (i = 0; i < n; ++i)
+            dst[i] = orc_f32_bits_to_bf16_bits(orc_f16_bits_to_f32_bits(s[i]));
+    } else {
+        const uint16_t* s = (const uint16_t*)src;
+        for (i = 0; i < n; ++i) dst[i] = s[i];
+    }
+}
+
+/* ---------------------------------------------------------------------------
+ * Template slot placement (Sec. 4.2: weights laid out in access order).
+ * offsets has n+1 entries; offsets[n] is the slot area's total size in bytes.
+ * Every slot starts on a 256-byte boundary and holds rows*cols bf16 values,
+ * row-major.
+ * ------------------------------------------------------------------------- */
+int64_t orc_layout(const int64_t* rows, const int64_t* cols, int32_t n, int64_t* offsets) {
+    int64_t off = 0;
+    int32_t i;
+    for (i = 0; i < n; ++i) {
+        offsets[i] = off;
+        off += 2 * rows[i] * cols[i];
+        off = (off + 255) / 256 * 256;
+    }
+    offsets[n] = off;
+    return off;
+}
+
+/* Materialise one tensor into its slot: conversion + placement. */
+void orc_materialize_slot(uint8_t* arena, int64_t slot_offset, const void* src, int dtype,
+                          int64_t rows, int64_t cols) {
+    orc_convert_to_bf16(src, dtype, rows * cols, (uint16_t*)(arena + slot_offset));
+}
+
+/* ---------------------------------------------------------------------------
+ * LoRA merge:  W[i][j] <- round( W[i][j] + sign * (alpha/r) * sum_k B[i][k]*A[k][j] )
+ *   W is out x in, A is r x in, B is out x r, all row-major; A and B are bf16.
+ *   The sum runs k = 0..r-1 in order, each step one fused multiply-add in
+ *   fp32; the scaled sum is added to W with one more fused multiply-add and
+ *   the result rounded once to the storage type.
+ *   r == 0 or alpha == 0 leaves W untouched when short_circuit != 0.
+ * ------------------------------------------------------------------------- */
+
+static float lora_dot(const uint16_t* A, const uint16_t* B, int64_t in, int32_t r,
+                      int64_t i, int64_t j) {
+    float acc = 0.0f;
+    int32_t k;
+    for (k = 0; k < r; ++k) {
+        float b = bf16_to_float(B[i * (int64_t)r + k]);
+        float a = bf16_to_float(A[(int64_t)k * in + j]);
+        acc = fmaf(b, a, acc);
+    }
+    return acc;
+}
+
+void orc_lora_merge_bf16(uint16_t* W, int64_t out, int64_t in, const uint16_t* A,
+                         const uint16_t* B, int32_t r, float alpha, int sign,
+                         int short_circuit) {
+    int64_t i, j;
+    float s;
+    if (short_circuit && (r == 0 || alpha == 0.0f)) return;
+    s = (r == 0) ? 0.0f : alpha / (float)r;
+    if (sign < 0) s = -s;
+    for (i = 0; i < out; ++i) {
+        for (j = 0; j < in; ++j) {
+            float acc = lora_dot(A, B, in, r, i, j);
+            float w = bf16_to_float(W[i * in + j]);
+            W[i * in + j] = float_to_bf16(fmaf(s, acc, w));
+        }
+    }
+}
+
+/* Same update with W stored in fp32 (no narrowing after the final fma). */
+void orc_lora_merge_f32(float* W, int64_t out, int64_t in, const uint16_t* A,
+                        const uint16_t* B, int32_t r, float alpha, int sign,
+                        int short_circuit) {
+    int64_t i, j;
+    float s;
+    if (short_circuit && (r == 0 || alpha == 0.0f)) return;
+    s = (r == 0) ? 0.0f : alpha / (float)r;
+    if (sign < 0) s = -s;
+    for (i = 0; i < out; ++i) {
+        for (j = 0; j < in; ++j) {
+            float acc = lora_dot(A, B, in, r, i, j);
+            W[i * in + j] = fmaf(s, acc, W[i * in + j]);
+        }
+    }
+}
+
+/* Swap = unmerge the old adapter, store, then merge the new one (two roundings). */
+void orc_lora_swap_bf16(uint16_t* W, int64_t out, int64_t in,
+                        const uint16_t* A_old, const uint16_t* B_old, int32_t r_old, float alpha_old,
+                        const uint16_t* A_new, const uint16_t* B_new, int32_t r_new, float alpha_new) {
+    orc_lora_merge_bf16(W, out, in, A_old, B_old, r_old, alpha_old, -1, 1);
+    orc_lora_merge_bf16(W, out, in, A_new, B_new, r_new, alpha_new, +1, 1);
+}
