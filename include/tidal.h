@@ -1,0 +1,230 @@
+/*
+ * tidal.h -- C ABI of libtidal: GPU-side materialisation of an LLM function's state
+ * onto a resident template, and per-invocation LoRA attach / swap, for AMD MI355X
+ * (gfx950).
+ *
+ * Framing (arXiv 2503.06421).  A *template* is pre-initialised function state kept in
+ * GPU memory from which invocations start (Sec. 1; Sec. 2.3 "template-start").  Its
+ * weights are laid out in the traced access order (Sec. 4.2), streamed host->GPU
+ * asynchronously in that order from a pinned host pool (Sec. 5.2 "Efficient overlapping
+ * with correctness ensuring"), with many small tensors merged into fewer copies (Sec. 6
+ * "Tailored memory pool in template server").  Request-specific state -- a LoRA
+ * adapter -- is initialised per invocation on top of the reused static state (Sec. 5.2
+ * "Adaptive template state reusing"), and while a function is kept alive only that
+ * dynamic part is redone (Sec. 5.2 "Keep-alive of dynamic function").
+ *
+ * Conventions.
+ *   - Every pointer is tagged [host] or [device].  No C++ or framework types cross
+ *     the boundary; streams are hipStream_t passed as void* (NULL = the null stream).
+ *   - The caller owns the device arena, the device memory of resident adapters and the
+ *     streams.  The library owns the handle, its pinned bounce buffers and its events.
+ *   - Host source / adapter pointers are borrowed until the stream work of the call
+ *     has completed (tidal_template_sync, or a sync of the streams given).
+ *   - Calls are asynchronous with respect to the host and ordered on the given
+ *     streams.  One thread at a time per template.
+ *   - Every int-returning call returns TIDAL_OK (0) or a negative tidal_status;
+ *     tidal_last_error() then holds a message (thread-local).  Arguments are validated
+ *     before any work is enqueued: a failed call leaves every slot untouched.  Nothing
+ *     throws or aborts across the boundary.
+ *   - There is no CPU fallback: calls that need the GPU return TIDAL_E_HIP without one.
+ *
+ * Template slots hold bf16, row-major, rows = output features, cols = input features.
+ */
+#ifndef TIDAL_H_
+#define TIDAL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tidal_template tidal_template;   /* opaque, freed by tidal_template_destroy */
+typedef struct tidal_adapter tidal_adapter;     /* opaque, freed by tidal_adapter_destroy  */
+
+typedef enum { TIDAL_F32 = 0, TIDAL_F16 = 1, TIDAL_BF16 = 2 } tidal_dtype;
+
+typedef enum {
+    TIDAL_OK = 0,
+    TIDAL_E_INVAL = -1,   /* null / negative / out-of-range argument, unknown dtype, shape mismatch   */
+    TIDAL_E_NOMEM = -2,   /* arena, adapter region or caller buffer too small; host allocation failed */
+    TIDAL_E_STATE = -3,   /* attach while attached, swap/detach with nothing attached, LoRA on a slot
+                             that was never materialised, partial re-materialisation under an adapter */
+    TIDAL_E_HIP = -4      /* a HIP runtime call failed (message in tidal_last_error)                  */
+} tidal_status;
+
+/* One template slot: a rows x cols bf16 matrix (1-D tensors: rows = 1). */
+typedef struct { int64_t rows, cols; } tidal_slot_desc;
+
+/* One tensor to materialise: rows*cols elements of `dtype` at `host`, row-major, dense. */
+typedef struct { int32_t slot; int32_t dtype; const void* host; /* [host] borrowed */ } tidal_src;
+
+/* One LoRA target: slot W (out x in) gets W + (alpha/r) * B * A with A (r x in) and
+ * B (out x r), row-major, dense, both of `dtype`.  r == 0 or alpha == 0 is valid and
+ * leaves W untouched (A and B may then be NULL). */
+typedef struct {
+    int32_t slot;
+    int32_t r;
+    float alpha;
+    int32_t dtype;
+    const void* A;        /* [host] borrowed */
+    const void* B;        /* [host] borrowed */
+} tidal_lora_target;
+
+enum {
+    /* LoRA kernels accumulate sum_k B[i][k]*A[k][j] as one fp32 fused-multiply-add chain in
+     * ascending k on the vector ALUs (bit-reproducible against a sequential definition)
+     * instead of the default matrix-core tiles (fp32 accumulation, unspecified order).      */
+    TIDAL_FLAG_ORDERED_ACCUM = 1,
+    /* tidal_lora_swap runs as two passes over W (unmerge, then merge) instead of one fused
+     * pass.  Results are bit-identical; this exists to demonstrate exactly that.              */
+    TIDAL_FLAG_TWO_PASS_SWAP = 2,
+    /* tidal_materialize records a completion event per slot, for tidal_template_slot_wait.    */
+    TIDAL_FLAG_SLOT_EVENTS = 4
+};
+
+typedef struct {
+    size_t chunk_bytes;        /* source bytes per staged copy unit; 0 = 32 MiB; rounded to 4 KiB;
+                                  must be at least 64 KiB                                        */
+    int32_t max_rank;          /* largest r accepted; 0 = 64; at most 64                         */
+    size_t max_adapter_bytes;  /* size of each of the two in-arena regions that hold the packed
+                                  device copy of adapters given by host pointers; 0 = none (then
+                                  only resident adapters can be attached)                        */
+    int32_t flags;             /* TIDAL_FLAG_*                                                   */
+    size_t coalesce_bytes;     /* host tensors smaller than this are gathered by the CPU into a
+                                  pinned buffer and shipped as one copy; 0 = 64 KiB              */
+} tidal_config;
+
+/* One planned host->device copy unit, as tidal_materialize would issue it (introspection). */
+typedef struct {
+    int32_t chunk;             /* index of the staged chunk this piece belongs to               */
+    int32_t slot;
+    int64_t elem_offset;       /* first element of the slot covered by this piece               */
+    int64_t elems;
+    int64_t src_bytes;         /* bytes read from the host tensor                                */
+    int64_t staging_offset;    /* byte offset inside the staging buffer; -1 = copied straight
+                                  into the slot (bf16 sources need no conversion)                */
+    int32_t gathered;          /* 1 = goes through the CPU-gathered pinned buffer                */
+    int32_t reserved;
+} tidal_copy_piece;
+
+typedef struct {
+    uint64_t h2d_bytes;          /* source bytes sent host->device (tensors and adapters)        */
+    uint64_t h2d_copies;         /* hipMemcpyAsync calls issued                                  */
+    uint64_t chunks;             /* staged chunks processed                                      */
+    uint64_t converted_elems;    /* elements narrowed to bf16 by the convert kernel              */
+    uint64_t gathered_bytes;     /* bytes that went through the CPU-gathered pinned buffer       */
+    uint64_t rmw_elems;          /* W elements read-modified-written by LoRA kernels             */
+    uint64_t lora_launches;      /* LoRA kernel launches                                         */
+} tidal_stats;
+
+/* Fill *cfg with the defaults named above.  Never fails for non-NULL cfg. */
+int tidal_config_default(tidal_config* cfg /* [host] out */);
+
+/* Bytes of device arena tidal_template_create needs: slot area (each slot 256-byte aligned,
+ * in the given order -- the access order of Sec. 4.2) + two staging buffers of chunk_bytes
+ * + two adapter regions of max_adapter_bytes + a launch-descriptor area.  Returns 0 on
+ * invalid arguments. */
+size_t tidal_template_required_bytes(const tidal_slot_desc* slots /* [host] */, int32_t n,
+                                     const tidal_config* cfg /* [host] NULL = defaults */);
+
+/* Create a template over a caller-owned device arena (Sec. 1: the template is function
+ * state cached in GPU memory).  Host-only: touches no device memory and makes no HIP call;
+ * device resources are created on first use.  dev_arena must be 256-byte aligned and at
+ * least tidal_template_required_bytes() long, else TIDAL_E_INVAL / TIDAL_E_NOMEM. */
+int tidal_template_create(const tidal_slot_desc* slots /* [host] copied */, int32_t n,
+                          void* dev_arena /* [device] borrowed for the template's life */,
+                          size_t arena_bytes, const tidal_config* cfg /* [host] NULL = defaults */,
+                          tidal_template** out /* [host] out */);
+
+/* Stream the given host tensors into their slots, in the order given (the load order of
+ * Sec. 5.2), in chunks of chunk_bytes: pinned (or CPU-gathered) host memory ->
+ * hipMemcpyAsync on copy_stream into one of two device staging buffers -> conversion to
+ * bf16 (round to nearest even, subnormals kept, NaN quieted) into the slot on
+ * compute_stream; bf16 sources are copied straight into the slot.  Small tensors are
+ * gathered into one copy (Sec. 6, tensor merging).  On return all work is enqueued;
+ * completion of compute_stream implies completion of the whole call.  If an adapter is
+ * attached, the sources must cover every slot it touches (then the template is pristine
+ * again and nothing is attached), else TIDAL_E_STATE.  A slot may appear at most once. */
+int tidal_materialize(tidal_template* t, const tidal_src* srcs /* [host] */, int32_t n_src,
+                      void* copy_stream, void* compute_stream);
+
+/* The copy plan tidal_materialize would execute for these sources, without executing it
+ * (host-only).  Writes at most cap pieces; returns the number of pieces of the full plan,
+ * or a negative tidal_status.  assume_pinned: 1 = treat sources as pinned host memory,
+ * 0 = as pageable, -1 = ask the HIP runtime (needs a GPU). */
+int32_t tidal_materialize_plan(tidal_template* t, const tidal_src* srcs /* [host] */, int32_t n_src,
+                               int32_t assume_pinned, tidal_copy_piece* out /* [host] out */,
+                               int32_t cap);
+
+/* Dynamic initialisation (Sec. 5.2): upload A and B of every target (converted to bf16 like
+ * any weight), then update every targeted slot in place in one pass,
+ *     W[i][j] <- bf16( f32(W[i][j]) + (alpha/r) * sum_k f32(B[i][k]) * f32(A[k][j]) ),
+ * fp32 accumulation, one rounding.  Slots not named are not written.  TIDAL_E_STATE if an
+ * adapter is already attached or a target slot was never materialised; TIDAL_E_INVAL for
+ * r < 0, r > max_rank, duplicate or out-of-range slots; TIDAL_E_NOMEM if the packed adapter
+ * exceeds max_adapter_bytes. */
+int tidal_lora_attach(tidal_template* t, const tidal_lora_target* targets /* [host] */,
+                      int32_t n_targets, void* stream);
+
+/* Keep-alive path (Sec. 5.2): replace the attached adapter.  Bit-identical to
+ * tidal_lora_detach followed by tidal_lora_attach (two roundings: W is rounded to bf16
+ * after the old delta is subtracted), but a slot targeted by both adapters is read and
+ * written once.  Target sets and ranks of old and new may differ. */
+int tidal_lora_swap(tidal_template* t, const tidal_lora_target* targets_new /* [host] */,
+                    int32_t n_targets, void* stream);
+
+/* Subtract the attached adapter's delta (same packed bf16 copy that was merged). */
+int tidal_lora_detach(tidal_template* t, void* stream);
+
+/* Resident adapters: the packed bf16 device copy lives in caller-owned device memory, so
+ * attach / swap move no host data (multi-tenant pools of adapters kept on the GPU).
+ * tidal_adapter_required_bytes returns 0 on invalid arguments. */
+size_t tidal_adapter_required_bytes(const tidal_template* t, const tidal_lora_target* targets /* [host] */,
+                                    int32_t n_targets);
+int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* targets /* [host] */,
+                         int32_t n_targets, void* dev_mem /* [device] 256-byte aligned, borrowed
+                         until tidal_adapter_destroy */, size_t dev_bytes, void* stream,
+                         tidal_adapter** out /* [host] out */);
+int tidal_adapter_destroy(tidal_adapter* a);   /* must not be attached */
+int tidal_lora_attach_adapter(tidal_template* t, const tidal_adapter* a, void* stream);
+int tidal_lora_swap_adapter(tidal_template* t, const tidal_adapter* a_new, void* stream);
+
+/* Device address and byte length (2*rows*cols) of a slot. */
+int tidal_template_slot_ptr(const tidal_template* t, int32_t slot, void** dev_ptr /* [host] out */,
+                            size_t* bytes /* [host] out, may be NULL */);
+
+/* Make `stream` wait until the last tidal_materialize has filled `slot` (the
+ * synchronisation events of Sec. 5.2).  Needs TIDAL_FLAG_SLOT_EVENTS; a slot that was never
+ * materialised gives TIDAL_E_STATE. */
+int tidal_template_slot_wait(tidal_template* t, int32_t slot, void* stream);
+
+/* Standalone conversion of n device-resident elements of `dtype` to bf16 (the kernel
+ * tidal_materialize runs on each staged chunk).  src and dst 16-byte aligned, not
+ * overlapping. */
+int tidal_convert_device(void* dst_bf16 /* [device] */, const void* src /* [device] */, int32_t dtype,
+                         int64_t n, void* stream);
+
+/* Host->device link rate: best of `reps` timed hipMemcpyAsync of `bytes` from a pinned
+ * host buffer the call allocates, into dev.  Blocks until done. */
+int tidal_h2d_peak(void* dev /* [device] */, size_t bytes, int32_t reps, void* stream,
+                   double* gbytes_per_s /* [host] out */);
+
+int tidal_get_stats(const tidal_template* t, tidal_stats* out /* [host] out */);
+int tidal_reset_stats(tidal_template* t);
+
+/* Block until everything this template enqueued has completed. */
+int tidal_template_sync(tidal_template* t);
+
+/* Waits for enqueued work, then frees the handle, pinned buffers and events.  Resident
+ * adapters and the arena stay with the caller. */
+int tidal_template_destroy(tidal_template* t);
+
+/* Message of the calling thread's last failed call ("" if none).  Never NULL. */
+const char* tidal_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIDAL_H_ */

@@ -1,0 +1,181 @@
+// Narrowing of staged checkpoint data to bf16 template slots, and packing of LoRA
+// factors into the layout the merge kernels read.  gfx950 only.
+//
+// The paper treats dtype changes and host-to-GPU copies as the operators that produce
+// a weight (Sec. 4.1, weight-centric tracing); here the dtype change is one streaming
+// kernel per staged chunk.  It is bound by HBM traffic (4 or 2 bytes in, 2 bytes out per
+// element, no reuse), so every lane moves 16-byte vectors and the arithmetic is integer
+// bit manipulation that reproduces IEEE round-to-nearest-even exactly, including
+// subnormals, infinities and NaN (sign and upper payload kept, quiet bit forced).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tidal_internal.h"
+
+namespace tidal {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// binary32 bits -> bf16 bits, round to nearest even.
+__device__ __forceinline__ uint32_t f32_bits_to_bf16(uint32_t u) {
+    uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    uint32_t nan = (u >> 16) | 0x0040u;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? nan : rounded;
+}
+
+// binary16 bits -> binary32 bits, exact.  Normal numbers are re-biased by an integer add;
+// subnormals are normalised with one exact fp32 subtraction (0.f * 2^-14 = 1.f * 2^-14 - 2^-14).
+__device__ __forceinline__ uint32_t f16_bits_to_f32(uint32_t h) {
+    uint32_t sign = (h & 0x8000u) << 16;
+    uint32_t em = h & 0x7FFFu;
+    uint32_t normal = (em << 13) + 0x38000000u;
+    uint32_t infnan = (em << 13) | 0x7F800000u;
+    float sub = __uint_as_float((em << 13) | 0x38800000u) - __uint_as_float(0x38800000u);
+    uint32_t r = (em >= 0x7C00u) ? infnan : ((em < 0x0400u) ? __float_as_uint(sub) : normal);
+    return sign | r;
+}
+
+__device__ __forceinline__ uint32_t pack2(uint32_t lo_bf16, uint32_t hi_bf16) {
+    return lo_bf16 | (hi_bf16 << 16);
+}
+
+// 8 elements per lane per step.
+__device__ __forceinline__ u32x4 narrow8_f32(u32x4 a, u32x4 b) {
+    u32x4 o;
+    o.x = pack2(f32_bits_to_bf16(a.x), f32_bits_to_bf16(a.y));
+    o.y = pack2(f32_bits_to_bf16(a.z), f32_bits_to_bf16(a.w));
+    o.z = pack2(f32_bits_to_bf16(b.x), f32_bits_to_bf16(b.y));
+    o.w = pack2(f32_bits_to_bf16(b.z), f32_bits_to_bf16(b.w));
+    return o;
+}
+
+__device__ __forceinline__ uint32_t narrow2_f16(uint32_t two) {
+    return pack2(f32_bits_to_bf16(f16_bits_to_f32(two & 0xFFFFu)),
+                 f32_bits_to_bf16(f16_bits_to_f32(two >> 16)));
+}
+
+__device__ __forceinline__ u32x4 narrow8_f16(u32x4 a) {
+    u32x4 o;
+    o.x = narrow2_f16(a.x);
+    o.y = narrow2_f16(a.y);
+    o.z = narrow2_f16(a.z);
+    o.w = narrow2_f16(a.w);
+    return o;
+}
+
+__device__ __forceinline__ uint16_t narrow1(const void* src, int dtype, int64_t i) {
+    if (dtype == TIDAL_F32) return (uint16_t)f32_bits_to_bf16(((const uint32_t*)src)[i]);
+    if (dtype == TIDAL_F16) return (uint16_t)f32_bits_to_bf16(f16_bits_to_f32(((const uint16_t*)src)[i]));
+    return ((const uint16_t*)src)[i];
+}
+
+// One launch converts every segment of a staged chunk: blockIdx.y selects the segment,
+// blockIdx.x strides over its 8-element vectors.  Segment sources are 16-byte aligned
+// inside the staging buffer and destinations are 16-byte aligned inside their slot.
+__global__ __launch_bounds__(256) void convert_segments_kernel(ConvertBatch batch) {
+    const ConvertSegment seg = batch.seg[blockIdx.y];
+    const int64_t nvec = seg.elems >> 3;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    u32x4* __restrict__ dst = (u32x4*)seg.dst;
+    if (seg.dtype == TIDAL_F32) {
+        const u32x4* __restrict__ src = (const u32x4*)seg.src;
+        for (; v < nvec; v += stride) {
+            u32x4 a = __builtin_nontemporal_load(src + 2 * v);
+            u32x4 b = __builtin_nontemporal_load(src + 2 * v + 1);
+            dst[v] = narrow8_f32(a, b);
+        }
+    } else if (seg.dtype == TIDAL_F16) {
+        const u32x4* __restrict__ src = (const u32x4*)seg.src;
+        for (; v < nvec; v += stride) {
+            u32x4 a = __builtin_nontemporal_load(src + v);
+            dst[v] = narrow8_f16(a);
+        }
+    } else {
+        const u32x4* __restrict__ src = (const u32x4*)seg.src;
+        for (; v < nvec; v += stride) dst[v] = __builtin_nontemporal_load(src + v);
+    }
+    // ragged tail (< 8 elements), one block only
+    if (blockIdx.x == 0) {
+        int64_t i = (nvec << 3) + threadIdx.x;
+        if (i < seg.elems) ((uint16_t*)seg.dst)[i] = narrow1(seg.src, seg.dtype, i);
+    }
+}
+
+hipError_t launch_convert(const ConvertBatch& batch, int nseg, hipStream_t stream) {
+    if (nseg <= 0) return hipSuccess;
+    int64_t max_elems = 0;
+    for (int i = 0; i < nseg; ++i) max_elems = batch.seg[i].elems > max_elems ? batch.seg[i].elems : max_elems;
+    // 2 vectors (16 elements) per lane per pass keeps the grid at a few waves per SIMD for a
+    // 32 MiB chunk while tiny segments still get one block.
+    int64_t blocks = (max_elems / 8 + 256 * 2 - 1) / (256 * 2);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    dim3 grid((unsigned)blocks, (unsigned)nseg, 1);
+    hipLaunchKernelGGL(convert_segments_kernel, grid, dim3(256), 0, stream, batch);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Packing of LoRA factors.  Host layout: A is r x in, B is out x r, row-major, any of the
+// three dtypes.  Device layout read by the merge kernels, rp = r rounded up to 16:
+//   At : in  x rp bf16, At[j][k] = bf16(A[k][j]), zero for k >= r   (A transposed)
+//   Bp : out x rp bf16, Bp[i][k] = bf16(B[i][k]), zero for k >= r
+// so that a lane fetches the 8 consecutive k it needs for one column (or row) with a single
+// 16-byte load.  One lane produces one such 16-byte group.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_adapter_kernel(PackBatch batch) {
+    const PackSegment seg = batch.seg[blockIdx.y];
+    const int groups_per_line = seg.rp >> 3;                 // 16-byte groups per packed row
+    const int64_t ngroups = seg.lines * groups_per_line;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < ngroups; g += stride) {
+        // consecutive lanes take consecutive lines so that the strided reads of a transposed
+        // A are coalesced along j
+        const int64_t line = g % seg.lines;
+        const int kg = (int)(g / seg.lines);
+        uint32_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = kg * 8 + e;
+            uint32_t b = 0;
+            if (k < seg.r) {
+                // A: element (k, line) of an r x lines matrix; B: element (line, k) of lines x r
+                const int64_t idx = seg.transposed ? (int64_t)k * seg.lines + line : line * seg.r + k;
+                b = narrow1(seg.src, seg.dtype, idx);
+            }
+            v[e] = b;
+        }
+        u32x4 o;
+        o.x = pack2(v[0], v[1]);
+        o.y = pack2(v[2], v[3]);
+        o.z = pack2(v[4], v[5]);
+        o.w = pack2(v[6], v[7]);
+        ((u32x4*)seg.dst)[line * groups_per_line + kg] = o;
+    }
+}
+
+hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream) {
+    if (nseg <= 0) return hipSuccess;
+    int64_t max_groups = 0;
+    for (int i = 0; i < nseg; ++i) {
+        int64_t g = batch.seg[i].lines * (batch.seg[i].rp >> 3);
+        max_groups = g > max_groups ? g : max_groups;
+    }
+    int64_t blocks = (max_groups + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 1024) blocks = 1024;
+    dim3 grid((unsigned)blocks, (unsigned)nseg, 1);
+    hipLaunchKernelGGL(pack_adapter_kernel, grid, dim3(256), 0, stream, batch);
+    return hipGetLastError();
+}
+
+// h2d peak probe and template set-up use no kernel; a trivial fill kernel clears the
+// descriptor area without recording a memset node.
+__global__ void fill_zero_kernel(uint32_t* p, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+}  // namespace tidal

@@ -1,0 +1,418 @@
+// In-place LoRA merge / unmerge / fused swap on template slots.  gfx950 only.
+//
+// The paper leaves the per-request (dynamic) part of initialisation -- attaching a LoRA
+// adapter to the shared base weights -- to user code (Sec. 5.2, "Adaptive template state
+// reusing"), and re-does only that part while a function is kept alive (Sec. 5.2,
+// "Keep-alive of dynamic function").  Here that part is one streaming pass over every
+// targeted W:
+//     W[i][j] <- bf16( f32(W[i][j]) + s * sum_k f32(B[i][k]) * f32(A[k][j]) ),   s = +-alpha/r
+// and a swap applies the old adapter with -s_old, rounds to bf16 in registers, then applies
+// the new one with +s_new: one read and one write of W, bit-identical to two passes.
+//
+// The pass is bound by HBM traffic (4 bytes per W element), not by arithmetic, as long as
+// the rank-r products do not run on the vector ALUs: at r = 16 the chain of fp32 FMAs alone
+// needs about two thirds of the chip's (unpacked) fp32 rate at 70 % of HBM bandwidth, at
+// r = 64 it needs 2.6x more than exists.  So two kernels:
+//
+//  * lora_mfma_kernel (default): each wave owns a column strip of W and walks down its rows
+//    in 32-row blocks.  The 32 x (32*NT) tile of sum_k B A is produced by NT
+//    v_mfma_f32_32x32x16_bf16 per 16 ranks straight into registers -- there is no separate
+//    GEMM and the delta never exists in memory.  The strip of A stays in registers for the
+//    whole walk (column-strip stationary), the 32 rows of B are one 16-byte load per lane,
+//    and the MFMA output layout is matched to memory by choosing which column feeds which
+//    MFMA column index: lane n of tile T owns column NT*n + T, so a lane holds NT adjacent
+//    columns of a row and a wave-wide access covers two full rows of 64*NT contiguous bytes.
+//    fp32 accumulation order inside the MFMA is the hardware's.
+//
+//  * lora_ordered_kernel (TIDAL_FLAG_ORDERED_ACCUM): 64 x 256 tiles, A and B rank tiles
+//    staged in LDS as fp32, 128-bit accesses to W, and the sum taken as one fused
+//    multiply-add chain in ascending k per element -- reproducible bit for bit against a
+//    sequential definition; VALU-bound from r = 16 up.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "tidal_internal.h"
+
+namespace tidal {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t round_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    uint32_t nan = (u >> 16) | 0x0040u;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? nan : rounded;
+}
+
+// Two adjacent bf16 of W (one 32-bit word, low half = lower column) += s * (d_lo, d_hi).
+__device__ __forceinline__ uint32_t rmw2(uint32_t w2, float d_lo, float d_hi, float s) {
+    float w_lo = __uint_as_float(w2 << 16);
+    float w_hi = __uint_as_float(w2 & 0xFFFF0000u);
+    uint32_t r_lo = round_bf16(__builtin_fmaf(s, d_lo, w_lo));
+    uint32_t r_hi = round_bf16(__builtin_fmaf(s, d_hi, w_hi));
+    return r_lo | (r_hi << 16);
+}
+
+// ---------------------------------------------------------------------------------------
+// Matrix-core kernel
+// ---------------------------------------------------------------------------------------
+
+template <int NT> struct RowVec;     // the NT adjacent bf16 a lane owns in one row
+template <> struct RowVec<2> { typedef uint32_t type; };
+template <> struct RowVec<4> { typedef u32x2 type; };
+template <> struct RowVec<8> { typedef u32x4 type; };
+
+template <int NT>
+__device__ __forceinline__ void unpack_words(const typename RowVec<NT>::type& v, uint32_t (&w)[NT / 2]) {
+    if constexpr (NT == 2) { w[0] = v; }
+    else if constexpr (NT == 4) { w[0] = v.x; w[1] = v.y; }
+    else { w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w; }
+}
+
+template <int NT>
+__device__ __forceinline__ typename RowVec<NT>::type pack_words(const uint32_t (&w)[NT / 2]) {
+    typename RowVec<NT>::type v;
+    if constexpr (NT == 2) { v = w[0]; }
+    else if constexpr (NT == 4) { v.x = w[0]; v.y = w[1]; }
+    else { v.x = w[0]; v.y = w[1]; v.z = w[2]; v.w = w[3]; }
+    return v;
+}
+
+// Columns of A (= rows of At) for the lane's NT columns: MFMA B operand, K x N with
+// N index n = lane % 32 and k = 16*ks + 8*(lane / 32) + 0..7.
+template <int NT, int KS>
+__device__ __forceinline__ void load_strip(const uint16_t* __restrict__ At, int in, int j0, int lane,
+                                           bf16x8 (&bop)[NT][KS ? KS : 1]) {
+    if constexpr (KS > 0) {
+        const int n = lane & 31, kg = lane >> 5;
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            int j = j0 + NT * n + T;
+            j = j < in ? j : in - 1;                       // ragged strip: clamp, masked at the store
+            const uint16_t* p = At + (int64_t)j * (16 * KS) + 8 * kg;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bop[T][ks] = *(const bf16x8*)(p + 16 * ks);
+        }
+    }
+}
+
+// delta tile for one adapter: acc[T][v] = sum_k B[i0 + row(v)][k] * A[k][j0 + NT*n + T]
+template <int NT, int KS>
+__device__ __forceinline__ void delta_tile(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
+                                           const bf16x8 (&bop)[NT][KS ? KS : 1], f32x16 (&acc)[NT]) {
+    if constexpr (KS > 0) {
+        int m = i0 + (lane & 31);
+        m = m < out ? m : out - 1;
+        const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
+        bf16x8 aop[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) aop[ks] = *(const bf16x8*)(p + 16 * ks);
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            f32x16 c = {0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], bop[T][ks], c, 0, 0, 0);
+            acc[T] = c;
+        }
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void apply_tile(uint32_t (&w)[16][NT / 2], const f32x16 (&acc)[NT], float s) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+#pragma unroll
+        for (int p = 0; p < NT / 2; ++p) w[v][p] = rmw2(w[v][p], acc[2 * p][v], acc[2 * p + 1][v], s);
+}
+
+template <int NT, int KS0, int KS1>
+__global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __restrict__ table,
+                                                        int out, int in, int strips, int rowblocks,
+                                                        int rc, int blocks_per_target, int total_blocks) {
+    typedef typename RowVec<NT>::type vec_t;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // Workgroups are dealt round-robin to the 8 XCDs; undo that so that each XCD walks a
+    // contiguous range of (target, row chunk, strip) and its L2 sees each A strip and each
+    // B row block once.  gridDim.x is a multiple of 8.
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= total_blocks) return;
+    const int target = L / blocks_per_target;
+    const int item = (L - target * blocks_per_target) * 4 + wave;
+    const int rowchunks = (rowblocks + rc - 1) / rc;
+    if (item >= strips * rowchunks) return;
+    const int rowchunk = item / strips;
+    const int strip = item - rowchunk * strips;
+    const int j0 = strip * (32 * NT);
+
+    const LoraTargetDev d = table[target];
+    uint16_t* __restrict__ W = d.W;
+
+    bf16x8 bop0[NT][KS0 ? KS0 : 1];
+    bf16x8 bop1[NT][KS1 ? KS1 : 1];
+    load_strip<NT, KS0>(d.At_old, in, j0, lane, bop0);
+    load_strip<NT, KS1>(d.At_new, in, j0, lane, bop1);
+
+    const int n = lane & 31, h = lane >> 5;
+    const int jl = j0 + NT * n;                              // lane's first column
+    const bool strip_full = (j0 + 32 * NT <= in) && (in % NT == 0);
+    const int rb_end = (rowchunk + 1) * rc < rowblocks ? (rowchunk + 1) * rc : rowblocks;
+
+    for (int rb = rowchunk * rc; rb < rb_end; ++rb) {
+        const int i0 = rb * 32;
+        const bool full = strip_full && (i0 + 32 <= out);
+        uint32_t w[16][NT / 2];
+        // lane's rows: 8*(v/4) + 4*h + v%4
+        if (full) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                vec_t x = *(const vec_t*)(W + (int64_t)row * in + jl);
+                unpack_words<NT>(x, w[v]);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+#pragma unroll
+                for (int p = 0; p < NT / 2; ++p) {
+                    uint32_t lo = 0, hi = 0;
+                    if (row < out && jl + 2 * p < in) lo = W[(int64_t)row * in + jl + 2 * p];
+                    if (row < out && jl + 2 * p + 1 < in) hi = W[(int64_t)row * in + jl + 2 * p + 1];
+                    w[v][p] = lo | (hi << 16);
+                }
+            }
+        }
+        f32x16 acc[NT];
+        if constexpr (KS0 > 0) {
+            delta_tile<NT, KS0>(d.Bp_old, out, i0, lane, bop0, acc);
+            apply_tile<NT>(w, acc, d.s_old);
+        }
+        if constexpr (KS1 > 0) {
+            delta_tile<NT, KS1>(d.Bp_new, out, i0, lane, bop1, acc);
+            apply_tile<NT>(w, acc, d.s_new);
+        }
+        if (full) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                *(vec_t*)(W + (int64_t)row * in + jl) = pack_words<NT>(w[v]);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+#pragma unroll
+                for (int p = 0; p < NT / 2; ++p) {
+                    if (row < out && jl + 2 * p < in) W[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[v][p] & 0xFFFFu);
+                    if (row < out && jl + 2 * p + 1 < in) W[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[v][p] >> 16);
+                }
+            }
+        }
+    }
+}
+
+template <int NT, int KS0, int KS1>
+static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
+    const int strips = (g.in + 32 * NT - 1) / (32 * NT);
+    const int rowblocks = (g.out + 31) / 32;
+    // Rows per wave: long walks amortise the A strip, but small jobs need every CU busy.
+    const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
+    int rc = (int)(tiles / 16384);
+    rc = rc < 1 ? 1 : (rc > 16 ? 16 : rc);
+    const int rowchunks = (rowblocks + rc - 1) / rc;
+    const int blocks_per_target = (strips * rowchunks + 3) / 4;
+    const int64_t total = (int64_t)blocks_per_target * g.n_targets;
+    if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((total + 7) / 8 * 8);
+    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, g.table, g.out,
+                       g.in, strips, rowblocks, rc, blocks_per_target, (int)total);
+    return hipGetLastError();
+}
+
+template <int NT, int KS0>
+static hipError_t launch_mfma_new(const LoraGroup& g, hipStream_t stream) {
+    switch (g.rp_new) {
+        case 0: if constexpr (KS0 > 0) return launch_mfma_inst<NT, KS0, 0>(g, stream); else return hipSuccess;
+        case 16: return launch_mfma_inst<NT, KS0, 1>(g, stream);
+        case 32: return launch_mfma_inst<NT, KS0, 2>(g, stream);
+        case 64: return launch_mfma_inst<NT, KS0, 4>(g, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int NT>
+static hipError_t launch_mfma_old(const LoraGroup& g, hipStream_t stream) {
+    switch (g.rp_old) {
+        case 0: return launch_mfma_new<NT, 0>(g, stream);
+        case 16: return launch_mfma_new<NT, 1>(g, stream);
+        case 32: return launch_mfma_new<NT, 2>(g, stream);
+        case 64: return launch_mfma_new<NT, 4>(g, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+static int g_mfma_nt = 0;   // 0 = choose by rank; set from TIDAL_MFMA_NT for tuning runs
+
+hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream) {
+    if (g.n_targets <= 0 || g.out <= 0 || g.in <= 0) return hipSuccess;
+    static const int env_nt = [] {
+        const char* e = getenv("TIDAL_MFMA_NT");
+        return e ? atoi(e) : 0;
+    }();
+    int nt = env_nt ? env_nt : g_mfma_nt;
+    if (nt != 2 && nt != 4 && nt != 8) {
+        // register budget: the A strips of both adapters stay resident (4*NT VGPRs per 16 ranks)
+        nt = (g.rp_old + g.rp_new <= 64) ? 4 : 2;
+    }
+    if (nt == 8) return launch_mfma_old<8>(g, stream);
+    if (nt == 4) return launch_mfma_old<4>(g, stream);
+    return launch_mfma_old<2>(g, stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// Ordered-accumulation kernel (vector ALUs, LDS-staged rank tiles)
+// ---------------------------------------------------------------------------------------
+constexpr int kOrdRows = 64, kOrdCols = 256, kOrdK = 16;
+
+// Stage ranks [k0, k0+16) of the A strip (as Atile[k][col]) and of the B rows (as
+// Btile[k][row]) into LDS as fp32.  The packed layouts are zero padded to a multiple of 16
+// ranks, so no k bound is needed here.
+__device__ __forceinline__ void stage_rank_tiles(const uint16_t* __restrict__ At, const uint16_t* __restrict__ Bp,
+                                                 int rp, int out, int in, int i0, int j0, int k0,
+                                                 float* Atile, float* Btile) {
+    const int tid = threadIdx.x;
+    {   // 256 columns x 16 ranks: one column per thread, two 16-byte loads
+        int j = j0 + tid;
+        j = j < in ? j : in - 1;
+        const u32x4* p = (const u32x4*)(At + (int64_t)j * rp + k0);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            u32x4 x = p[q];
+            const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                Atile[(8 * q + 2 * e) * kOrdCols + tid] = __uint_as_float(wds[e] << 16);
+                Atile[(8 * q + 2 * e + 1) * kOrdCols + tid] = __uint_as_float(wds[e] & 0xFFFF0000u);
+            }
+        }
+    }
+    if (tid < 128) {   // 64 rows x 16 ranks: one 16-byte load per thread
+        const int row = tid & 63, q = tid >> 6;
+        int i = i0 + row;
+        i = i < out ? i : out - 1;
+        u32x4 x = *(const u32x4*)(Bp + (int64_t)i * rp + k0 + 8 * q);
+        const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            Btile[(8 * q + 2 * e) * kOrdRows + row] = __uint_as_float(wds[e] << 16);
+            Btile[(8 * q + 2 * e + 1) * kOrdRows + row] = __uint_as_float(wds[e] & 0xFFFF0000u);
+        }
+    }
+}
+
+__device__ __forceinline__ void ordered_phase(const uint16_t* __restrict__ At, const uint16_t* __restrict__ Bp,
+                                              int r, int rp, float s, int out, int in, int i0, int j0,
+                                              float* Atile, float* Btile, uint32_t (&w)[8][4]) {
+    const int cg = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    float acc[8][8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
+    for (int k0 = 0; k0 < r; k0 += kOrdK) {
+        __syncthreads();
+        stage_rank_tiles(At, Bp, rp, out, in, i0, j0, k0, Atile, Btile);
+        __syncthreads();
+        const int kend = (r - k0) < kOrdK ? (r - k0) : kOrdK;
+        for (int k = 0; k < kend; ++k) {
+            const f32x4 a_lo = *(const f32x4*)(Atile + k * kOrdCols + 8 * cg);
+            const f32x4 a_hi = *(const f32x4*)(Atile + k * kOrdCols + 8 * cg + 4);
+            const f32x4 b_lo = *(const f32x4*)(Btile + k * kOrdRows + 8 * rg);
+            const f32x4 b_hi = *(const f32x4*)(Btile + k * kOrdRows + 8 * rg + 4);
+            const float a8[8] = {a_lo.x, a_lo.y, a_lo.z, a_lo.w, a_hi.x, a_hi.y, a_hi.z, a_hi.w};
+            const float b8[8] = {b_lo.x, b_lo.y, b_lo.z, b_lo.w, b_hi.x, b_hi.y, b_hi.z, b_hi.w};
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+                for (int cc = 0; cc < 8; ++cc) acc[rr][cc] = __builtin_fmaf(b8[rr], a8[cc], acc[rr][cc]);
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) w[rr][p] = rmw2(w[rr][p], acc[rr][2 * p], acc[rr][2 * p + 1], s);
+}
+
+__global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraTargetDev* __restrict__ table, int out,
+                                                           int in, int r_old, int rp_old, int r_new,
+                                                           int rp_new, int col_tiles, int tiles_per_target) {
+    __shared__ __attribute__((aligned(16))) float Atile[kOrdK * kOrdCols];
+    __shared__ __attribute__((aligned(16))) float Btile[kOrdK * kOrdRows];
+    const int target = blockIdx.x / tiles_per_target;
+    const int tile = blockIdx.x - target * tiles_per_target;
+    const int i0 = (tile / col_tiles) * kOrdRows;
+    const int j0 = (tile % col_tiles) * kOrdCols;
+    const LoraTargetDev d = table[target];
+    uint16_t* __restrict__ W = d.W;
+    const int cg = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int jl = j0 + 8 * cg;
+    const bool vec_ok = (in % 8 == 0) && (jl + 8 <= in);
+
+    uint32_t w[8][4];
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+        const int row = i0 + 8 * rg + rr;
+        if (vec_ok && row < out) {
+            u32x4 x = *(const u32x4*)(W + (int64_t)row * in + jl);
+            w[rr][0] = x.x; w[rr][1] = x.y; w[rr][2] = x.z; w[rr][3] = x.w;
+        } else {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint32_t lo = 0, hi = 0;
+                if (row < out && jl + 2 * p < in) lo = W[(int64_t)row * in + jl + 2 * p];
+                if (row < out && jl + 2 * p + 1 < in) hi = W[(int64_t)row * in + jl + 2 * p + 1];
+                w[rr][p] = lo | (hi << 16);
+            }
+        }
+    }
+    if (rp_old > 0) ordered_phase(d.At_old, d.Bp_old, r_old, rp_old, d.s_old, out, in, i0, j0, Atile, Btile, w);
+    if (rp_new > 0) ordered_phase(d.At_new, d.Bp_new, r_new, rp_new, d.s_new, out, in, i0, j0, Atile, Btile, w);
+#pragma unroll
+    for (int rr = 0; rr < 8; ++rr) {
+        const int row = i0 + 8 * rg + rr;
+        if (vec_ok && row < out) {
+            u32x4 x;
+            x.x = w[rr][0]; x.y = w[rr][1]; x.z = w[rr][2]; x.w = w[rr][3];
+            *(u32x4*)(W + (int64_t)row * in + jl) = x;
+        } else {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                if (row < out && jl + 2 * p < in) W[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[rr][p] & 0xFFFFu);
+                if (row < out && jl + 2 * p + 1 < in) W[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[rr][p] >> 16);
+            }
+        }
+    }
+}
+
+hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream) {
+    if (g.n_targets <= 0 || g.out <= 0 || g.in <= 0) return hipSuccess;
+    if (g.rp_old == 0 && g.rp_new == 0) return hipSuccess;
+    const int col_tiles = (g.in + kOrdCols - 1) / kOrdCols;
+    const int row_tiles = (g.out + kOrdRows - 1) / kOrdRows;
+    const int64_t tiles_per_target = (int64_t)col_tiles * row_tiles;
+    const int64_t total = tiles_per_target * g.n_targets;
+    if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(lora_ordered_kernel, dim3((unsigned)total), dim3(256), 0, stream, g.table, g.out, g.in,
+                       g.r_old, g.rp_old, g.r_new, g.rp_new, col_tiles, (int)tiles_per_target);
+    return hipGetLastError();
+}
+
+}  // namespace tidal

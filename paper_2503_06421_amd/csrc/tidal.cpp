@@ -1,0 +1,883 @@
+// libtidal host side: the C ABI, argument validation, the attach/swap state machine and
+// the two-stream staging pipeline.  All arithmetic on tensor data happens in the kernels
+// (convert_kernels.hip, lora_kernels.hip); this file only moves bytes and launches.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <map>
+#include <new>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "plan.h"
+#include "tidal_internal.h"
+
+using namespace tidal;
+
+// ---------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return fail(TIDAL_E_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------
+// handles
+// ---------------------------------------------------------------------------------------
+namespace {
+
+struct PackedTarget {
+    int32_t slot;
+    int32_t r, rp;
+    float alpha;
+    size_t at_off, bp_off;   // byte offsets of At (in x rp) and Bp (out x rp) in the adapter memory
+    bool active() const { return r > 0 && alpha != 0.0f; }
+};
+
+struct AdapterRec {
+    std::vector<PackedTarget> targets;   // sorted by slot
+    char* dev = nullptr;
+    size_t bytes = 0;
+};
+
+struct SlotState {
+    int64_t rows = 0, cols = 0, elems = 0;
+    bool materialised = false;
+    hipEvent_t ready = nullptr;
+    bool ready_recorded = false;
+};
+
+constexpr int kDescRing = 4;
+
+}  // namespace
+
+struct tidal_adapter {
+    tidal_template* owner;
+    AdapterRec rec;
+    bool attached;
+};
+
+struct tidal_template {
+    tidal_config cfg;
+    ArenaLayout lay;
+    char* arena = nullptr;
+    std::vector<SlotState> slots;
+
+    // device-side resources, created on first use
+    bool dev_ready = false;
+    hipEvent_t staged_ready[2] = {nullptr, nullptr};   // copy stream: chunk is in staging[b]
+    hipEvent_t staging_free[2] = {nullptr, nullptr};   // consumer: staging[b] may be overwritten
+    hipEvent_t bounce_free[2] = {nullptr, nullptr};    // copy stream: pinned buffer b has been read
+    hipEvent_t ev_start = nullptr, ev_copy_done = nullptr;
+    hipEvent_t ev_last_compute = nullptr, ev_last_lora = nullptr;
+    bool last_compute_rec = false, last_lora_rec = false;
+    char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
+    bool bounce_used[2] = {false, false};
+    char* desc_host = nullptr;                         // pinned host, kDescRing * kDescBytes
+    hipEvent_t desc_free[kDescRing] = {};
+    bool desc_rec[kDescRing] = {};
+    int desc_next = 0;
+
+    // attach state
+    bool attached = false;
+    AdapterRec cur;                  // record of the attached adapter (device copy stays valid)
+    tidal_adapter* cur_resident = nullptr;
+    int cur_region = -1;             // in-arena region holding it, or -1
+
+    tidal_stats stats = {};
+};
+
+// ---------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------
+static int ensure_device(tidal_template* t) {
+    if (t->dev_ready) return TIDAL_OK;
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return fail(TIDAL_E_HIP, "no HIP device available (%s)", hipGetErrorString(e));
+    }
+    const unsigned flags = hipEventDisableTiming;
+    for (int b = 0; b < 2; ++b) {
+        HIP_TRY(hipEventCreateWithFlags(&t->staged_ready[b], flags));
+        HIP_TRY(hipEventCreateWithFlags(&t->staging_free[b], flags));
+        HIP_TRY(hipEventCreateWithFlags(&t->bounce_free[b], flags));
+    }
+    HIP_TRY(hipEventCreateWithFlags(&t->ev_start, flags));
+    HIP_TRY(hipEventCreateWithFlags(&t->ev_copy_done, flags));
+    HIP_TRY(hipEventCreateWithFlags(&t->ev_last_compute, flags));
+    HIP_TRY(hipEventCreateWithFlags(&t->ev_last_lora, flags));
+    for (int i = 0; i < kDescRing; ++i) HIP_TRY(hipEventCreateWithFlags(&t->desc_free[i], flags));
+    HIP_TRY(hipHostMalloc((void**)&t->desc_host, kDescRing * kDescBytes, hipHostMallocDefault));
+    t->dev_ready = true;
+    return TIDAL_OK;
+}
+
+static int ensure_bounce(tidal_template* t, int b) {
+    if (!t->bounce[b]) HIP_TRY(hipHostMalloc((void**)&t->bounce[b], t->cfg.chunk_bytes, hipHostMallocDefault));
+    return TIDAL_OK;
+}
+
+static bool host_is_pinned(const void* p) {
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();   // plain malloc'ed memory is reported as an error, not a type
+        return false;
+    }
+    return attr.type == hipMemoryTypeHost;
+}
+
+static inline char* slot_ptr(const tidal_template* t, int32_t slot) { return t->arena + t->lay.slot_offset[slot]; }
+
+// ---------------------------------------------------------------------------------------
+// configuration, creation
+// ---------------------------------------------------------------------------------------
+extern "C" int tidal_config_default(tidal_config* cfg) {
+    if (!cfg) return fail(TIDAL_E_INVAL, "cfg is NULL");
+    const char* msg = "";
+    normalise_config(nullptr, cfg, &msg);
+    return TIDAL_OK;
+}
+
+extern "C" size_t tidal_template_required_bytes(const tidal_slot_desc* slots, int32_t n, const tidal_config* cfg) {
+    if ((!slots && n > 0) || n < 0) return 0;
+    tidal_config c;
+    const char* msg = "";
+    if (!normalise_config(cfg, &c, &msg)) return 0;
+    ArenaLayout lay;
+    if (!layout_arena(slots, n, c, &lay)) return 0;
+    return lay.total;
+}
+
+extern "C" int tidal_template_create(const tidal_slot_desc* slots, int32_t n, void* dev_arena, size_t arena_bytes,
+                                     const tidal_config* cfg, tidal_template** out) {
+    if (!out) return fail(TIDAL_E_INVAL, "out is NULL");
+    *out = nullptr;
+    if (n < 0 || (!slots && n > 0)) return fail(TIDAL_E_INVAL, "bad slot list (n=%d)", n);
+    if (!dev_arena) return fail(TIDAL_E_INVAL, "dev_arena is NULL");
+    if ((uintptr_t)dev_arena % kSlotAlign) return fail(TIDAL_E_INVAL, "dev_arena is not 256-byte aligned");
+    tidal_config c;
+    const char* msg = "";
+    if (!normalise_config(cfg, &c, &msg)) return fail(TIDAL_E_INVAL, "config: %s", msg);
+    tidal_template* t = new (std::nothrow) tidal_template();
+    if (!t) return fail(TIDAL_E_NOMEM, "out of host memory");
+    t->cfg = c;
+    if (!layout_arena(slots, n, c, &t->lay)) {
+        delete t;
+        return fail(TIDAL_E_INVAL, "slot with negative or oversized shape");
+    }
+    if (t->lay.total > arena_bytes) {
+        size_t need = t->lay.total;
+        delete t;
+        return fail(TIDAL_E_NOMEM, "arena too small: need %zu bytes, got %zu", need, arena_bytes);
+    }
+    t->arena = (char*)dev_arena;
+    t->slots.resize((size_t)n);
+    for (int32_t i = 0; i < n; ++i) {
+        t->slots[i].rows = slots[i].rows;
+        t->slots[i].cols = slots[i].cols;
+        t->slots[i].elems = slots[i].rows * slots[i].cols;
+    }
+    *out = t;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_template_slot_ptr(const tidal_template* t, int32_t slot, void** dev_ptr, size_t* bytes) {
+    if (!t || !dev_ptr) return fail(TIDAL_E_INVAL, "NULL argument");
+    if (slot < 0 || slot >= (int32_t)t->slots.size()) return fail(TIDAL_E_INVAL, "slot %d out of range", slot);
+    *dev_ptr = slot_ptr(t, slot);
+    if (bytes) *bytes = 2 * (size_t)t->slots[slot].elems;
+    return TIDAL_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// materialisation
+// ---------------------------------------------------------------------------------------
+static int gather_sources(const tidal_template* t, const tidal_src* srcs, int32_t n_src, int32_t assume_pinned,
+                          std::vector<SourceInfo>* out) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    if (n_src < 0 || (!srcs && n_src > 0)) return fail(TIDAL_E_INVAL, "bad source list (n=%d)", n_src);
+    std::vector<char> seen(t->slots.size(), 0);
+    out->clear();
+    out->reserve((size_t)n_src);
+    for (int32_t i = 0; i < n_src; ++i) {
+        const tidal_src& s = srcs[i];
+        if (s.slot < 0 || s.slot >= (int32_t)t->slots.size())
+            return fail(TIDAL_E_INVAL, "source %d: slot %d out of range", i, s.slot);
+        if (!dtype_ok(s.dtype)) return fail(TIDAL_E_INVAL, "source %d: unknown dtype %d", i, s.dtype);
+        if (seen[s.slot]) return fail(TIDAL_E_INVAL, "source %d: slot %d given twice", i, s.slot);
+        seen[s.slot] = 1;
+        const int64_t elems = t->slots[s.slot].elems;
+        if (!s.host && elems > 0) return fail(TIDAL_E_INVAL, "source %d: host pointer is NULL", i);
+        bool pinned = assume_pinned > 0;
+        if (assume_pinned < 0) pinned = elems > 0 && host_is_pinned(s.host);
+        out->push_back(SourceInfo{s.slot, s.dtype, (const char*)s.host, elems, pinned});
+    }
+    return TIDAL_OK;
+}
+
+// With an adapter attached, re-materialising is allowed only if it restores every merged slot.
+static int check_rematerialise(const tidal_template* t, const std::vector<SourceInfo>& srcs, bool* clears) {
+    *clears = false;
+    if (!t->attached) return TIDAL_OK;
+    std::vector<char> covered(t->slots.size(), 0);
+    for (const SourceInfo& s : srcs) covered[s.slot] = 1;
+    int hit = 0, total = 0;
+    for (const PackedTarget& p : t->cur.targets) {
+        if (!p.active()) continue;
+        ++total;
+        hit += covered[p.slot];
+    }
+    if (hit == 0) return TIDAL_OK;
+    if (hit != total)
+        return fail(TIDAL_E_STATE, "materialize covers %d of the %d slots the attached adapter is merged into", hit, total);
+    *clears = true;
+    return TIDAL_OK;
+}
+
+extern "C" int32_t tidal_materialize_plan(tidal_template* t, const tidal_src* srcs, int32_t n_src,
+                                          int32_t assume_pinned, tidal_copy_piece* out, int32_t cap) {
+    std::vector<SourceInfo> infos;
+    int rc = gather_sources(t, srcs, n_src, assume_pinned, &infos);
+    if (rc) return rc;
+    if (cap < 0 || (!out && cap > 0)) return fail(TIDAL_E_INVAL, "bad output buffer");
+    std::vector<Piece> plan;
+    plan_copies(infos, t->cfg, kMaxConvertSeg, &plan);
+    for (size_t i = 0; i < plan.size() && (int32_t)i < cap; ++i) {
+        const Piece& p = plan[i];
+        out[i].chunk = p.chunk;
+        out[i].slot = p.slot;
+        out[i].elem_offset = p.elem_offset;
+        out[i].elems = p.elems;
+        out[i].src_bytes = p.src_bytes;
+        out[i].staging_offset = p.staged ? p.buf_offset : -1;
+        out[i].gathered = p.gathered ? 1 : 0;
+        out[i].reserved = 0;
+    }
+    return (int32_t)plan.size();
+}
+
+namespace {
+
+// Issues the copies of a plan and hands every staged chunk to a consumer.  Used by
+// tidal_materialize (two streams, consumer = convert kernel) and by the adapter upload
+// (one stream, consumer = pack kernel).
+struct Pipeline {
+    tidal_template* t;
+    hipStream_t copy, compute;
+
+    // pending CPU-gathered run that will go out as one DMA
+    bool run = false;
+    char* run_dst = nullptr;
+    const char* run_src = nullptr;
+    size_t run_len = 0;
+
+    int flush() {
+        if (!run) return TIDAL_OK;
+        run = false;
+        HIP_TRY(hipMemcpyAsync(run_dst, run_src, run_len, hipMemcpyHostToDevice, copy));
+        t->stats.h2d_copies++;
+        return TIDAL_OK;
+    }
+
+    // Copy one piece of `bytes` host bytes to device address dst; gathered pieces pass through
+    // pinned buffer b at buf_off first.
+    int put(bool gathered, int b, int64_t buf_off, const char* host, size_t bytes, char* dst) {
+        t->stats.h2d_bytes += bytes;
+        if (!gathered) {
+            int rc = flush();
+            if (rc) return rc;
+            HIP_TRY(hipMemcpyAsync(dst, host, bytes, hipMemcpyHostToDevice, copy));
+            t->stats.h2d_copies++;
+            return TIDAL_OK;
+        }
+        char* stage = t->bounce[b] + buf_off;
+        memcpy(stage, host, bytes);
+        t->stats.gathered_bytes += bytes;
+        // extend the run when source and destination advance by the same amount (alignment
+        // gaps are copied along; they only ever land in padding)
+        if (run && stage >= run_src && (size_t)(stage - run_src) == (size_t)(dst - run_dst) &&
+            (size_t)(stage - run_src) >= run_len && (size_t)(stage - run_src) - run_len < kSlotAlign) {
+            run_len = (size_t)(stage - run_src) + bytes;
+            return TIDAL_OK;
+        }
+        int rc = flush();
+        if (rc) return rc;
+        run = true;
+        run_dst = dst;
+        run_src = stage;
+        run_len = bytes;
+        return TIDAL_OK;
+    }
+
+    // Before the first use of the buffers of chunk parity b.
+    int acquire(int b, bool need_bounce, bool need_staging) {
+        if (need_bounce) {
+            int rc = ensure_bounce(t, b);
+            if (rc) return rc;
+            if (t->bounce_used[b]) HIP_TRY(hipEventSynchronize(t->bounce_free[b]));
+        }
+        if (need_staging) HIP_TRY(hipStreamWaitEvent(copy, t->staging_free[b], 0));
+        return TIDAL_OK;
+    }
+
+    // After the last copy of a chunk has been issued.
+    int copies_done(int b, bool used_bounce, bool used_staging) {
+        int rc = flush();
+        if (rc) return rc;
+        if (used_bounce) {
+            HIP_TRY(hipEventRecord(t->bounce_free[b], copy));
+            t->bounce_used[b] = true;
+        }
+        if (used_staging && copy != compute) {
+            HIP_TRY(hipEventRecord(t->staged_ready[b], copy));
+            HIP_TRY(hipStreamWaitEvent(compute, t->staged_ready[b], 0));
+        }
+        return TIDAL_OK;
+    }
+
+    // After the consumer kernel of a chunk has been launched.
+    int consumed(int b) {
+        HIP_TRY(hipEventRecord(t->staging_free[b], compute));
+        t->stats.chunks++;
+        return TIDAL_OK;
+    }
+};
+
+}  // namespace
+
+extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32_t n_src, void* copy_stream,
+                                 void* compute_stream) {
+    std::vector<SourceInfo> infos;
+    int rc = gather_sources(t, srcs, n_src, 0, &infos);
+    if (rc) return rc;
+    bool clears = false;
+    rc = check_rematerialise(t, infos, &clears);
+    if (rc) return rc;
+    if (infos.empty()) return TIDAL_OK;
+    rc = ensure_device(t);
+    if (rc) return rc;
+    for (SourceInfo& s : infos) s.pinned = s.elems > 0 && host_is_pinned(s.host);
+
+    std::vector<Piece> plan;
+    plan_copies(infos, t->cfg, kMaxConvertSeg, &plan);
+
+    Pipeline pl{t, (hipStream_t)copy_stream, (hipStream_t)compute_stream};
+    // copies may write slots that earlier work on the compute stream still reads
+    if (pl.copy != pl.compute) {
+        HIP_TRY(hipEventRecord(t->ev_start, pl.compute));
+        HIP_TRY(hipStreamWaitEvent(pl.copy, t->ev_start, 0));
+    }
+    const bool slot_events = (t->cfg.flags & TIDAL_FLAG_SLOT_EVENTS) != 0;
+
+    size_t i = 0;
+    while (i < plan.size()) {
+        const int32_t chunk = plan[i].chunk;
+        const int b = chunk & 1;
+        size_t j = i;
+        bool need_bounce = false, need_staging = false;
+        while (j < plan.size() && plan[j].chunk == chunk) {
+            need_bounce |= plan[j].gathered;
+            need_staging |= plan[j].staged;
+            ++j;
+        }
+        rc = pl.acquire(b, need_bounce, need_staging);
+        if (rc) return rc;
+        ConvertBatch batch;
+        int nseg = 0;
+        for (size_t k = i; k < j; ++k) {
+            const Piece& p = plan[k];
+            char* slot_dst = slot_ptr(t, p.slot) + 2 * p.elem_offset;
+            char* dst = p.staged ? t->arena + t->lay.staging[b] + p.buf_offset : slot_dst;
+            rc = pl.put(p.gathered, b, p.buf_offset, p.host, (size_t)p.src_bytes, dst);
+            if (rc) return rc;
+            if (p.staged) {
+                batch.seg[nseg++] = ConvertSegment{dst, slot_dst, p.elems, p.dtype, 0};
+                t->stats.converted_elems += (uint64_t)p.elems;
+            }
+        }
+        rc = pl.copies_done(b, need_bounce, need_staging);
+        if (rc) return rc;
+        if (need_staging) {
+            HIP_TRY(launch_convert(batch, nseg, pl.compute));
+            rc = pl.consumed(b);
+            if (rc) return rc;
+        }
+        if (slot_events) {
+            // a slot is complete when the chunk holding its last piece is done
+            for (size_t k = i; k < j; ++k) {
+                const Piece& p = plan[k];
+                if (p.elem_offset + p.elems != t->slots[p.slot].elems) continue;
+                SlotState& s = t->slots[p.slot];
+                if (!s.ready) HIP_TRY(hipEventCreateWithFlags(&s.ready, hipEventDisableTiming));
+                HIP_TRY(hipEventRecord(s.ready, p.staged ? pl.compute : pl.copy));
+                s.ready_recorded = true;
+            }
+        }
+        i = j;
+    }
+    // completion of the compute stream implies completion of the call
+    if (pl.copy != pl.compute) {
+        HIP_TRY(hipEventRecord(t->ev_copy_done, pl.copy));
+        HIP_TRY(hipStreamWaitEvent(pl.compute, t->ev_copy_done, 0));
+    }
+    HIP_TRY(hipEventRecord(t->ev_last_compute, pl.compute));
+    t->last_compute_rec = true;
+    for (const SourceInfo& s : infos) t->slots[s.slot].materialised = true;
+    if (clears) {
+        if (t->cur_resident) t->cur_resident->attached = false;
+        t->attached = false;
+        t->cur_resident = nullptr;
+        t->cur_region = -1;
+        t->cur.targets.clear();
+    }
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_template_slot_wait(tidal_template* t, int32_t slot, void* stream) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    if (slot < 0 || slot >= (int32_t)t->slots.size()) return fail(TIDAL_E_INVAL, "slot %d out of range", slot);
+    if (!(t->cfg.flags & TIDAL_FLAG_SLOT_EVENTS)) return fail(TIDAL_E_STATE, "template was created without TIDAL_FLAG_SLOT_EVENTS");
+    SlotState& s = t->slots[slot];
+    if (s.elems == 0) return TIDAL_OK;
+    if (!s.ready_recorded) return fail(TIDAL_E_STATE, "slot %d was never materialised", slot);
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, s.ready, 0));
+    return TIDAL_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// adapters: validation, packed layout, upload
+// ---------------------------------------------------------------------------------------
+static int validate_targets(const tidal_template* t, const tidal_lora_target* tg, int32_t n, bool need_host,
+                            AdapterRec* rec) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    if (n < 0 || (!tg && n > 0)) return fail(TIDAL_E_INVAL, "bad target list (n=%d)", n);
+    rec->targets.clear();
+    std::vector<char> seen(t->slots.size(), 0);
+    size_t off = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        const tidal_lora_target& g = tg[i];
+        if (g.slot < 0 || g.slot >= (int32_t)t->slots.size())
+            return fail(TIDAL_E_INVAL, "target %d: slot %d out of range", i, g.slot);
+        if (seen[g.slot]) return fail(TIDAL_E_INVAL, "target %d: slot %d given twice", i, g.slot);
+        seen[g.slot] = 1;
+        if (g.r < 0 || g.r > t->cfg.max_rank)
+            return fail(TIDAL_E_INVAL, "target %d: rank %d outside 0..%d", i, g.r, t->cfg.max_rank);
+        if (!(g.alpha == g.alpha) || g.alpha - g.alpha != 0.0f)
+            return fail(TIDAL_E_INVAL, "target %d: alpha is not finite", i);
+        const SlotState& s = t->slots[g.slot];
+        if (s.rows > 0x7FFFFFFF || s.cols > 0x7FFFFFFF)
+            return fail(TIDAL_E_INVAL, "target %d: slot %d is too large for a LoRA target", i, g.slot);
+        PackedTarget p;
+        p.slot = g.slot;
+        p.r = g.r;
+        p.rp = padded_rank(g.r);
+        p.alpha = g.alpha;
+        p.at_off = p.bp_off = 0;
+        if (p.active() && s.elems > 0) {
+            if (!dtype_ok(g.dtype)) return fail(TIDAL_E_INVAL, "target %d: unknown dtype %d", i, g.dtype);
+            if (need_host && (!g.A || !g.B)) return fail(TIDAL_E_INVAL, "target %d: A or B is NULL", i);
+            p.at_off = off;
+            off = align_up(off + 2 * (size_t)s.cols * p.rp, kSlotAlign);
+            p.bp_off = off;
+            off = align_up(off + 2 * (size_t)s.rows * p.rp, kSlotAlign);
+        }
+        rec->targets.push_back(p);
+    }
+    rec->bytes = off;
+    return TIDAL_OK;
+}
+
+static int check_materialised(const tidal_template* t, const AdapterRec& rec) {
+    for (const PackedTarget& p : rec.targets)
+        if (!t->slots[p.slot].materialised && t->slots[p.slot].elems > 0)
+            return fail(TIDAL_E_STATE, "LoRA target slot %d was never materialised", p.slot);
+    return TIDAL_OK;
+}
+
+extern "C" size_t tidal_adapter_required_bytes(const tidal_template* t, const tidal_lora_target* targets,
+                                               int32_t n_targets) {
+    AdapterRec rec;
+    if (validate_targets(t, targets, n_targets, false, &rec)) return 0;
+    return rec.bytes ? rec.bytes : kSlotAlign;
+}
+
+// Stage A and B of every active target through the staging buffers and pack them into
+// rec.dev on `stream`.
+static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t stream) {
+    struct Job { const char* host; size_t bytes; PackSegment seg; bool pinned; };
+    std::vector<Job> jobs;
+    for (size_t i = 0; i < rec.targets.size(); ++i) {
+        const PackedTarget& p = rec.targets[i];
+        const SlotState& s = t->slots[p.slot];
+        if (!p.active() || s.elems == 0) continue;
+        const size_t isz = dtype_size(tg[i].dtype);
+        Job a{(const char*)tg[i].A, (size_t)p.r * (size_t)s.cols * isz,
+              PackSegment{nullptr, rec.dev + p.at_off, s.cols, p.r, p.rp, tg[i].dtype, 1}, false};
+        Job b{(const char*)tg[i].B, (size_t)p.r * (size_t)s.rows * isz,
+              PackSegment{nullptr, rec.dev + p.bp_off, s.rows, p.r, p.rp, tg[i].dtype, 0}, false};
+        if (a.bytes > t->cfg.chunk_bytes || b.bytes > t->cfg.chunk_bytes)
+            return fail(TIDAL_E_INVAL, "target %zu: a LoRA factor is larger than chunk_bytes", i);
+        jobs.push_back(a);
+        jobs.push_back(b);
+    }
+    if (jobs.empty()) return TIDAL_OK;
+    for (Job& j : jobs) j.pinned = host_is_pinned(j.host);
+
+    Pipeline pl{t, stream, stream};
+    size_t i = 0;
+    int chunk = 0;
+    while (i < jobs.size()) {
+        const int b = chunk & 1;
+        // fill one staging buffer with whole factors
+        size_t fill = 0, j = i;
+        bool need_bounce = false;
+        std::vector<size_t> offs;
+        while (j < jobs.size() && (int)(j - i) < kMaxPackSeg) {
+            size_t off = align_up(fill, kSlotAlign);
+            if (off + jobs[j].bytes > t->cfg.chunk_bytes) break;
+            offs.push_back(off);
+            fill = off + jobs[j].bytes;
+            need_bounce |= !jobs[j].pinned || jobs[j].bytes < t->cfg.coalesce_bytes;
+            ++j;
+        }
+        int rc = pl.acquire(b, need_bounce, true);
+        if (rc) return rc;
+        PackBatch batch;
+        int nseg = 0;
+        for (size_t k = i; k < j; ++k) {
+            Job& job = jobs[k];
+            const bool gathered = !job.pinned || job.bytes < t->cfg.coalesce_bytes;
+            char* dst = t->arena + t->lay.staging[b] + offs[k - i];
+            rc = pl.put(gathered, b, (int64_t)offs[k - i], job.host, job.bytes, dst);
+            if (rc) return rc;
+            job.seg.src = dst;
+            batch.seg[nseg++] = job.seg;
+        }
+        rc = pl.copies_done(b, need_bounce, true);
+        if (rc) return rc;
+        HIP_TRY(launch_pack(batch, nseg, stream));
+        rc = pl.consumed(b);
+        if (rc) return rc;
+        i = j;
+        ++chunk;
+    }
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* targets, int32_t n_targets,
+                                    void* dev_mem, size_t dev_bytes, void* stream, tidal_adapter** out) {
+    if (!out) return fail(TIDAL_E_INVAL, "out is NULL");
+    *out = nullptr;
+    AdapterRec rec;
+    int rc = validate_targets(t, targets, n_targets, true, &rec);
+    if (rc) return rc;
+    if (!dev_mem) return fail(TIDAL_E_INVAL, "dev_mem is NULL");
+    if ((uintptr_t)dev_mem % kSlotAlign) return fail(TIDAL_E_INVAL, "dev_mem is not 256-byte aligned");
+    if (rec.bytes > dev_bytes) return fail(TIDAL_E_NOMEM, "adapter needs %zu bytes, got %zu", rec.bytes, dev_bytes);
+    rc = ensure_device(t);
+    if (rc) return rc;
+    rec.dev = (char*)dev_mem;
+    rc = upload_adapter(t, targets, rec, (hipStream_t)stream);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(t->ev_last_lora, (hipStream_t)stream));
+    t->last_lora_rec = true;
+    tidal_adapter* a = new (std::nothrow) tidal_adapter();
+    if (!a) return fail(TIDAL_E_NOMEM, "out of host memory");
+    a->owner = t;
+    a->rec = rec;
+    a->attached = false;
+    *out = a;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_adapter_destroy(tidal_adapter* a) {
+    if (!a) return TIDAL_OK;
+    if (a->attached) return fail(TIDAL_E_STATE, "adapter is attached; detach or swap it out first");
+    delete a;
+    return TIDAL_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// LoRA launches
+// ---------------------------------------------------------------------------------------
+// One pass over the union of the slots of `older` (subtracted) and `newer` (added); either
+// may be NULL.  Slots are grouped by (shape, padded ranks) and each group is one launch.
+static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterRec* newer, hipStream_t stream) {
+    struct Side { const PackedTarget* p; const AdapterRec* rec; };
+    std::map<int32_t, std::pair<Side, Side>> by_slot;
+    if (older)
+        for (const PackedTarget& p : older->targets)
+            if (p.active() && t->slots[p.slot].elems > 0) by_slot[p.slot].first = Side{&p, older};
+    if (newer)
+        for (const PackedTarget& p : newer->targets)
+            if (p.active() && t->slots[p.slot].elems > 0) by_slot[p.slot].second = Side{&p, newer};
+    if (by_slot.empty()) return TIDAL_OK;
+
+    typedef std::tuple<int64_t, int64_t, int, int, int, int> Key;   // out, in, rp_old, rp_new, r_old, r_new
+    std::map<Key, std::vector<LoraTargetDev>> groups;
+    for (auto& kv : by_slot) {
+        const SlotState& s = t->slots[kv.first];
+        const Side& o = kv.second.first;
+        const Side& n = kv.second.second;
+        LoraTargetDev d;
+        memset(&d, 0, sizeof d);
+        d.W = (uint16_t*)slot_ptr(t, kv.first);
+        int rp_old = 0, rp_new = 0, r_old = 0, r_new = 0;
+        if (o.p) {
+            d.At_old = (const uint16_t*)(o.rec->dev + o.p->at_off);
+            d.Bp_old = (const uint16_t*)(o.rec->dev + o.p->bp_off);
+            d.s_old = -(o.p->alpha / (float)o.p->r);
+            rp_old = o.p->rp;
+            r_old = o.p->r;
+        }
+        if (n.p) {
+            d.At_new = (const uint16_t*)(n.rec->dev + n.p->at_off);
+            d.Bp_new = (const uint16_t*)(n.rec->dev + n.p->bp_off);
+            d.s_new = n.p->alpha / (float)n.p->r;
+            rp_new = n.p->rp;
+            r_new = n.p->r;
+        }
+        groups[Key(s.rows, s.cols, rp_old, rp_new, r_old, r_new)].push_back(d);
+        t->stats.rmw_elems += (uint64_t)s.elems;
+    }
+    size_t total = 0;
+    for (auto& g : groups) total += g.second.size();
+    if (total * sizeof(LoraTargetDev) > kDescBytes)
+        return fail(TIDAL_E_INVAL, "too many LoRA targets in one call (%zu)", total);
+
+    // descriptor table: pinned host ring -> descriptor area of the arena, on the caller's stream
+    const int ring = t->desc_next;
+    t->desc_next = (ring + 1) % kDescRing;
+    if (t->desc_rec[ring]) HIP_TRY(hipEventSynchronize(t->desc_free[ring]));
+    LoraTargetDev* host_tab = (LoraTargetDev*)(t->desc_host + (size_t)ring * kDescBytes);
+    LoraTargetDev* dev_tab = (LoraTargetDev*)(t->arena + t->lay.desc);
+    size_t at = 0;
+    for (auto& g : groups) {
+        memcpy(host_tab + at, g.second.data(), g.second.size() * sizeof(LoraTargetDev));
+        at += g.second.size();
+    }
+    HIP_TRY(hipMemcpyAsync(dev_tab, host_tab, total * sizeof(LoraTargetDev), hipMemcpyHostToDevice, stream));
+    HIP_TRY(hipEventRecord(t->desc_free[ring], stream));
+    t->desc_rec[ring] = true;
+
+    const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
+    at = 0;
+    for (auto& g : groups) {
+        LoraGroup lg;
+        lg.table = dev_tab + at;
+        lg.n_targets = (int32_t)g.second.size();
+        lg.out = (int32_t)std::get<0>(g.first);
+        lg.in = (int32_t)std::get<1>(g.first);
+        lg.rp_old = std::get<2>(g.first);
+        lg.rp_new = std::get<3>(g.first);
+        lg.r_old = std::get<4>(g.first);
+        lg.r_new = std::get<5>(g.first);
+        HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, stream));
+        t->stats.lora_launches++;
+        at += g.second.size();
+    }
+    HIP_TRY(hipEventRecord(t->ev_last_lora, stream));
+    t->last_lora_rec = true;
+    return TIDAL_OK;
+}
+
+static int do_swap_launch(tidal_template* t, const AdapterRec* older, const AdapterRec* newer, hipStream_t stream) {
+    if ((t->cfg.flags & TIDAL_FLAG_TWO_PASS_SWAP) && older && newer) {
+        int rc = launch_rmw(t, older, nullptr, stream);
+        if (rc) return rc;
+        return launch_rmw(t, nullptr, newer, stream);
+    }
+    return launch_rmw(t, older, newer, stream);
+}
+
+static void set_attached(tidal_template* t, const AdapterRec& rec, tidal_adapter* resident, int region) {
+    if (t->cur_resident) t->cur_resident->attached = false;
+    t->attached = true;
+    t->cur = rec;
+    t->cur_resident = resident;
+    t->cur_region = region;
+    if (resident) resident->attached = true;
+}
+
+// attach (swap = false) or swap (swap = true) an adapter given by host pointers
+static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n, void* stream, bool swap) {
+    AdapterRec rec;
+    int rc = validate_targets(t, tg, n, true, &rec);
+    if (rc) return rc;
+    if (!swap && t->attached) return fail(TIDAL_E_STATE, "an adapter is already attached");
+    if (swap && !t->attached) return fail(TIDAL_E_STATE, "no adapter is attached");
+    rc = check_materialised(t, rec);
+    if (rc) return rc;
+    if (rec.bytes > t->cfg.max_adapter_bytes)
+        return fail(TIDAL_E_NOMEM, "packed adapter needs %zu bytes, max_adapter_bytes is %zu", rec.bytes,
+                    t->cfg.max_adapter_bytes);
+    rc = ensure_device(t);
+    if (rc) return rc;
+    const int region = (t->cur_region == 0) ? 1 : 0;
+    rec.dev = t->arena + t->lay.adapter_region[region];
+    rc = upload_adapter(t, tg, rec, (hipStream_t)stream);
+    if (rc) return rc;
+    AdapterRec old = t->cur;
+    rc = do_swap_launch(t, swap ? &old : nullptr, &rec, (hipStream_t)stream);
+    if (rc) return rc;
+    set_attached(t, rec, nullptr, region);
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_lora_attach(tidal_template* t, const tidal_lora_target* targets, int32_t n_targets, void* stream) {
+    return attach_host(t, targets, n_targets, stream, false);
+}
+
+extern "C" int tidal_lora_swap(tidal_template* t, const tidal_lora_target* targets_new, int32_t n_targets, void* stream) {
+    return attach_host(t, targets_new, n_targets, stream, true);
+}
+
+static int attach_resident(tidal_template* t, const tidal_adapter* a_c, void* stream, bool swap) {
+    if (!t || !a_c) return fail(TIDAL_E_INVAL, "NULL argument");
+    tidal_adapter* a = const_cast<tidal_adapter*>(a_c);
+    if (a->owner != t) return fail(TIDAL_E_INVAL, "adapter belongs to another template");
+    if (!swap && t->attached) return fail(TIDAL_E_STATE, "an adapter is already attached");
+    if (swap && !t->attached) return fail(TIDAL_E_STATE, "no adapter is attached");
+    int rc = check_materialised(t, a->rec);
+    if (rc) return rc;
+    rc = ensure_device(t);
+    if (rc) return rc;
+    AdapterRec old = t->cur;
+    rc = do_swap_launch(t, swap ? &old : nullptr, &a->rec, (hipStream_t)stream);
+    if (rc) return rc;
+    set_attached(t, a->rec, a, -1);
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_lora_attach_adapter(tidal_template* t, const tidal_adapter* a, void* stream) {
+    return attach_resident(t, a, stream, false);
+}
+
+extern "C" int tidal_lora_swap_adapter(tidal_template* t, const tidal_adapter* a_new, void* stream) {
+    return attach_resident(t, a_new, stream, true);
+}
+
+extern "C" int tidal_lora_detach(tidal_template* t, void* stream) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    if (!t->attached) return fail(TIDAL_E_STATE, "no adapter is attached");
+    int rc = ensure_device(t);
+    if (rc) return rc;
+    AdapterRec old = t->cur;
+    rc = launch_rmw(t, &old, nullptr, (hipStream_t)stream);
+    if (rc) return rc;
+    if (t->cur_resident) t->cur_resident->attached = false;
+    t->attached = false;
+    t->cur_resident = nullptr;
+    // cur_region keeps its value: the next host-pointer attach then uses the other region,
+    // so a still-running detach kernel never has its factors overwritten
+    t->cur.targets.clear();
+    return TIDAL_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// utilities
+// ---------------------------------------------------------------------------------------
+extern "C" int tidal_convert_device(void* dst_bf16, const void* src, int32_t dtype, int64_t n, void* stream) {
+    if (n < 0) return fail(TIDAL_E_INVAL, "n is negative");
+    if (n == 0) return TIDAL_OK;
+    if (!dst_bf16 || !src) return fail(TIDAL_E_INVAL, "NULL argument");
+    if (!dtype_ok(dtype)) return fail(TIDAL_E_INVAL, "unknown dtype %d", dtype);
+    if ((uintptr_t)dst_bf16 % 16 || (uintptr_t)src % 16) return fail(TIDAL_E_INVAL, "pointers must be 16-byte aligned");
+    ConvertBatch batch;
+    batch.seg[0] = ConvertSegment{src, dst_bf16, n, dtype, 0};
+    HIP_TRY(launch_convert(batch, 1, (hipStream_t)stream));
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_h2d_peak(void* dev, size_t bytes, int32_t reps, void* stream, double* gbytes_per_s) {
+    if (!dev || !gbytes_per_s || bytes == 0 || reps <= 0) return fail(TIDAL_E_INVAL, "bad argument");
+    char* host = nullptr;
+    HIP_TRY(hipHostMalloc((void**)&host, bytes, hipHostMallocDefault));
+    memset(host, 1, bytes);
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    double best = 0.0;
+    hipStream_t s = (hipStream_t)stream;
+    for (int i = 0; i < reps + 1 && e == hipSuccess; ++i) {     // first pass is a warm-up
+        e = hipEventRecord(a, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipEventRecord(b, s);
+        if (e == hipSuccess) e = hipEventSynchronize(b);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+        if (e == hipSuccess && i > 0 && ms > 0.f) best = std::max(best, (double)bytes / (ms * 1e-3) / 1e9);
+    }
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+    (void)hipHostFree(host);
+    if (e != hipSuccess) return fail(TIDAL_E_HIP, "h2d probe failed: %s", hipGetErrorString(e));
+    *gbytes_per_s = best;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_get_stats(const tidal_template* t, tidal_stats* out) {
+    if (!t || !out) return fail(TIDAL_E_INVAL, "NULL argument");
+    *out = t->stats;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_reset_stats(tidal_template* t) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    memset(&t->stats, 0, sizeof t->stats);
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_template_sync(tidal_template* t) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    if (!t->dev_ready) return TIDAL_OK;
+    if (t->last_compute_rec) HIP_TRY(hipEventSynchronize(t->ev_last_compute));
+    if (t->last_lora_rec) HIP_TRY(hipEventSynchronize(t->ev_last_lora));
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_template_destroy(tidal_template* t) {
+    if (!t) return TIDAL_OK;
+    int rc = tidal_template_sync(t);
+    if (t->dev_ready) {
+        for (int b = 0; b < 2; ++b) {
+            if (t->bounce_used[b]) (void)hipEventSynchronize(t->bounce_free[b]);
+            (void)hipEventDestroy(t->staged_ready[b]);
+            (void)hipEventDestroy(t->staging_free[b]);
+            (void)hipEventDestroy(t->bounce_free[b]);
+            if (t->bounce[b]) (void)hipHostFree(t->bounce[b]);
+        }
+        (void)hipEventDestroy(t->ev_start);
+        (void)hipEventDestroy(t->ev_copy_done);
+        (void)hipEventDestroy(t->ev_last_compute);
+        (void)hipEventDestroy(t->ev_last_lora);
+        for (int i = 0; i < kDescRing; ++i) (void)hipEventDestroy(t->desc_free[i]);
+        if (t->desc_host) (void)hipHostFree(t->desc_host);
+        for (SlotState& s : t->slots)
+            if (s.ready) (void)hipEventDestroy(s.ready);
+    }
+    if (t->cur_resident) t->cur_resident->attached = false;
+    delete t;
+    return rc;
+}
+
+extern "C" const char* tidal_last_error(void) { return g_err; }

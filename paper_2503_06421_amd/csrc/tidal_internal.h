@@ -1,0 +1,66 @@
+// Internal declarations shared by the host code and the kernels of libtidal.
+// Nothing here is part of the C ABI.
+#ifndef TIDAL_INTERNAL_H_
+#define TIDAL_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tidal.h"
+
+namespace tidal {
+
+// ---- conversion of a staged chunk -----------------------------------------------------
+struct ConvertSegment {
+    const void* src;   // device, 16-byte aligned (inside a staging buffer)
+    void* dst;         // device, 16-byte aligned (inside a slot)
+    int64_t elems;
+    int32_t dtype;
+    int32_t pad_;
+};
+constexpr int kMaxConvertSeg = 32;
+struct ConvertBatch { ConvertSegment seg[kMaxConvertSeg]; };
+
+hipError_t launch_convert(const ConvertBatch& batch, int nseg, hipStream_t stream);
+
+// ---- packing of LoRA factors ------------------------------------------------------------
+struct PackSegment {
+    const void* src;     // device staging: A (r x lines, transposed = 1) or B (lines x r)
+    void* dst;           // device: lines x rp bf16
+    int64_t lines;       // in (for A) or out (for B)
+    int32_t r, rp, dtype, transposed;
+};
+constexpr int kMaxPackSeg = 32;
+struct PackBatch { PackSegment seg[kMaxPackSeg]; };
+
+hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream);
+
+// ---- LoRA read-modify-write ---------------------------------------------------------------
+// One entry per targeted slot of a launch group.  All slots of a group share out, in and the
+// padded ranks of the old and new adapter.  A side that is absent has a null At/Bp.
+struct LoraTargetDev {
+    uint16_t* W;             // out x in bf16
+    const uint16_t* At_old;  // in x rp_old bf16 (A transposed, zero padded)
+    const uint16_t* Bp_old;  // out x rp_old bf16
+    const uint16_t* At_new;
+    const uint16_t* Bp_new;
+    float s_old;             // already negated: W - (alpha/r) * delta_old
+    float s_new;
+};
+
+struct LoraGroup {
+    const LoraTargetDev* table;  // device
+    int32_t n_targets;
+    int32_t out, in;
+    int32_t r_old, r_new;        // true ranks (ordered-accumulation kernel)
+    int32_t rp_old, rp_new;      // padded ranks: 0, 16, 32 or 64
+};
+
+// Matrix-core path (default) and ordered-accumulation vector path.
+hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream);
+hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream);
+
+inline int padded_rank(int r) { return r <= 0 ? 0 : (r <= 16 ? 16 : (r <= 32 ? 32 : 64)); }
+
+}  // namespace tidal
+#endif

@@ -1,0 +1,297 @@
+"""GPU parity, LoRA attach / detach / swap against the CPU oracle, through the C ABI.
+
+Two kernels are checked.  With TIDAL_FLAG_ORDERED_ACCUM the sum over k is one fp32 FMA chain
+in ascending k, the same order the oracle uses, so the result must be bit-exact.  The default
+matrix-core kernel accumulates in fp32 in the hardware's order; it must agree with the oracle
+within max|W_gpu - W_orc| <= 2^-7 * max|W_orc| per tensor, and in practice differs from it in a
+tiny fraction of elements by one bf16 ulp (checked too).  Fused swap must equal two passes bit
+for bit in both modes."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2503_06421_amd import binding as tb            # noqa: E402
+from paper_2503_06421_amd import workloads as wl_mod      # noqa: E402
+
+ORDERED = tb.TIDAL_FLAG_ORDERED_ACCUM
+TOL = 2.0 ** -7
+
+
+@pytest.fixture(scope="module")
+def G():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from tests import gpu_util
+    return gpu_util
+
+
+def f32(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def check_against_oracle(got, want, exact, what=""):
+    if exact:
+        assert np.array_equal(got, want), "%s: %d elements differ" % (what, int(np.sum(got != want)))
+        return
+    g, w = f32(got).astype(np.float64), f32(want).astype(np.float64)
+    assert np.max(np.abs(g - w)) <= TOL * np.max(np.abs(w)), what
+    # stronger, empirical: almost everything is identical, the rest is one rounding step away
+    frac = np.mean(got != want)
+    assert frac < 2e-3, "%s: %.3g of elements differ" % (what, frac)
+    ulp = np.maximum(np.abs(w), 2.0 ** -120) * 2.0 ** -7
+    assert np.all(np.abs(g - w) <= ulp + 2.0 ** -20 * np.max(np.abs(w))), what
+
+
+def oracle_adapter(orc, A, B):
+    return orc.convert_to_bf16(A), orc.convert_to_bf16(B)
+
+
+def make_problem(seed, out, inn, r, dtype=np.float32, wscale=0.02, ascale=0.01):
+    rng = np.random.default_rng(seed)
+    W = rng.uniform(-wscale, wscale, (out, inn)).astype(dtype)
+    A = rng.normal(0, ascale, (r, inn)).astype(dtype)
+    B = rng.normal(0, ascale, (out, r)).astype(dtype)
+    return W, A, B
+
+
+SHAPES = [(100, 130, 3), (64, 256, 8), (33, 1000, 16), (200, 520, 33), (257, 129, 64), (32, 128, 16),
+          (1, 5, 1), (96, 384, 48)]
+
+
+@pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
+@pytest.mark.parametrize("out,inn,r", SHAPES)
+def test_attach_detach_swap_vs_oracle(orc, G, flags, out, inn, r):
+    exact = flags == ORDERED
+    W, A0, B0 = make_problem(out * 7 + r, out, inn, r, wscale=0.05, ascale=0.05)
+    r1 = max(1, (r * 2) % 65)
+    _, A1, B1 = make_problem(out * 11 + r, out, inn, r1, wscale=0.05, ascale=0.05)
+    alpha0, alpha1 = 2.0 * r, 1.5 * r1
+    with G.Template([(out, inn)], max_adapter_bytes=1 << 20, flags=flags) as T:
+        T.materialize({0: W})
+        Wo = orc.convert_to_bf16(W)
+        assert np.array_equal(T.slot(0), Wo)
+        a0, b0 = oracle_adapter(orc, A0, B0)
+        a1, b1 = oracle_adapter(orc, A1, B1)
+        # attach
+        T.attach([(0, alpha0, A0, B0)])
+        orc.lora_merge(Wo, a0, b0, alpha0, +1)
+        got = T.slot(0)
+        check_against_oracle(got, Wo, exact, "attach")
+        # swap (fused): continue the oracle from the GPU state so that one-ulp differences of the
+        # matrix-core path do not compound across steps
+        Wo = got.copy()
+        T.swap([(0, alpha1, A1, B1)])
+        orc.lora_swap(Wo, a0, b0, alpha0, a1, b1, alpha1)
+        got = T.slot(0)
+        check_against_oracle(got, Wo, exact, "swap")
+        # detach
+        Wo = got.copy()
+        T.detach()
+        orc.lora_merge(Wo, a1, b1, alpha1, -1)
+        check_against_oracle(T.slot(0), Wo, exact, "detach")
+
+
+@pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
+def test_fused_swap_equals_two_passes_bitwise(G, flags):
+    W, A0, B0 = make_problem(1, 300, 700, 16, wscale=0.05, ascale=0.05)
+    _, A1, B1 = make_problem(2, 300, 700, 64, wscale=0.05, ascale=0.05)
+    res = []
+    for extra in (0, tb.TIDAL_FLAG_TWO_PASS_SWAP):
+        with G.Template([(300, 700)], max_adapter_bytes=1 << 20, flags=flags | extra) as T:
+            T.materialize({0: W})
+            T.attach([(0, 32.0, A0, B0)])
+            T.swap([(0, 128.0, A1, B1)])
+            launches = tb.tidal_get_stats(T.h)["lora_launches"]
+            res.append((T.slot(0), launches))
+    assert np.array_equal(res[0][0], res[1][0])
+    assert res[0][1] == 2 and res[1][1] == 3            # fused: one launch for the swap
+
+
+@pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
+def test_swap_equals_detach_then_attach(G, flags):
+    W, A0, B0 = make_problem(3, 129, 260, 8, wscale=0.05, ascale=0.05)
+    _, A1, B1 = make_problem(4, 129, 260, 32, wscale=0.05, ascale=0.05)
+    out = []
+    for fused in (True, False):
+        with G.Template([(129, 260)], max_adapter_bytes=1 << 20, flags=flags) as T:
+            T.materialize({0: W})
+            T.attach([(0, 16.0, A0, B0)])
+            if fused:
+                T.swap([(0, 64.0, A1, B1)])
+            else:
+                T.detach()
+                T.attach([(0, 64.0, A1, B1)])
+            out.append(T.slot(0))
+    assert np.array_equal(out[0], out[1])
+
+
+@pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
+@pytest.mark.parametrize("dtype", [wl_mod.F32, wl_mod.F16, wl_mod.BF16])
+def test_stack_untargeted_slots_untouched_and_dtypes(orc, G, flags, dtype):
+    """Tiny llama-shaped stack; adapters arrive in the base's host dtype; targets of the old and the
+    new adapter overlap only partly (q,v -> v,o); everything else stays bit-identical."""
+    exact = flags == ORDERED
+    w = wl_mod.tiny_stack(host_dtype=dtype, layers=2, hidden=192, ffn=520, vocab=500, lora_on=("q", "v"), rank=16)
+    w2 = wl_mod.tiny_stack(host_dtype=dtype, layers=2, hidden=192, ffn=520, vocab=500, lora_on=("v", "o", "down"), rank=8)
+    arrays = {i: wl_mod.draw_tensor(w, i) for i in range(len(w.tensors))}
+    ad0 = [(s, 32.0) + wl_mod.draw_adapter(w, 0, s) for s in w.lora_slots]
+    ad1 = [(s, 16.0) + wl_mod.draw_adapter(w2, 1, s) for s in w2.lora_slots]
+    with G.Template(w.shapes, max_adapter_bytes=4 << 20, flags=flags, chunk_bytes=256 << 10) as T:
+        T.materialize(arrays)
+        base = [T.slot(i) for i in range(len(w.shapes))]
+        T.attach(ad0)
+        state = [b.copy() for b in base]
+        for s, al, A, B in ad0:
+            orc.lora_merge(state[s], *oracle_adapter(orc, A, B), al, +1)
+        for i in range(len(w.shapes)):
+            check_against_oracle(T.slot(i), state[i], exact or i not in w.lora_slots, "attach slot %d" % i)
+        state = [T.slot(i) for i in range(len(w.shapes))]
+        T.swap(ad1)
+        for s, al, A, B in ad0:
+            orc.lora_merge(state[s], *oracle_adapter(orc, A, B), al, -1)
+        for s, al, A, B in ad1:
+            orc.lora_merge(state[s], *oracle_adapter(orc, A, B), al, +1)
+        touched = set(w.lora_slots) | set(w2.lora_slots)
+        for i in range(len(w.shapes)):
+            check_against_oracle(T.slot(i), state[i], exact or i not in touched, "swap slot %d" % i)
+        for i in set(range(len(w.shapes))) - touched:
+            assert np.array_equal(T.slot(i), base[i])
+
+
+def test_identity_cases_bitwise(G):
+    """r = 0 and alpha = 0 leave W untouched bit for bit, including -0, inf and NaN payloads."""
+    W, A, B = make_problem(5, 64, 128, 8)
+    Wb = W.view(np.uint32).copy()
+    Wb[0, :4] = [0x80000000, 0x7F800000, 0x7FA10000, 0xFF800000]
+    W = Wb.view(np.float32)
+    for flags in (ORDERED, 0):
+        with G.Template([(64, 128), (64, 128)], max_adapter_bytes=1 << 20, flags=flags) as T:
+            T.materialize({0: W, 1: W})
+            before = T.slot(0)
+            T.attach([(0, 0.0, A, B), (1, 16.0, A[:0], B[:, :0])])
+            assert np.array_equal(T.slot(0), before) and np.array_equal(T.slot(1), before)
+            assert tb.tidal_get_stats(T.h)["lora_launches"] == 0
+            T.swap([(0, 16.0, A, B)])                     # swap from a no-op adapter = plain merge
+            assert np.any(T.slot(0) != before) and np.array_equal(T.slot(1), before)
+            T.detach()
+
+
+def test_special_values_in_w(orc, G):
+    """inf stays inf, NaN stays NaN, and their neighbours are unaffected (ordered mode: bit-exact
+    for everything that is not NaN)."""
+    W, A, B = make_problem(6, 64, 256, 16, wscale=0.05, ascale=0.05)
+    Wb = W.view(np.uint32).copy()
+    Wb[3, 5], Wb[10, 200], Wb[63, 255], Wb[0, 0] = 0x7F800000, 0xFF800000, 0x7FC00000, 0x80000000
+    W = Wb.view(np.float32)
+    for flags in (ORDERED, 0):
+        with G.Template([(64, 256)], max_adapter_bytes=1 << 20, flags=flags) as T:
+            T.materialize({0: W})
+            Wo = T.slot(0)
+            T.attach([(0, 32.0, A, B)])
+            orc.lora_merge(Wo, *oracle_adapter(orc, A, B), 32.0, +1)
+            got = T.slot(0)
+            nan = np.isnan(f32(Wo))
+            assert nan.sum() == 1 and np.array_equal(np.isnan(f32(got)), nan)
+            assert got[3, 5] == 0x7F80 and got[10, 200] == 0xFF80
+            if flags == ORDERED:
+                assert np.array_equal(got[~nan], Wo[~nan])
+
+
+def test_state_machine(G):
+    W, A, B = make_problem(7, 32, 64, 4)
+    tgt = [(0, 8.0, A, B)]
+    with G.Template([(32, 64), (32, 64)], max_adapter_bytes=1 << 16) as T:
+        def expect(code, fn, *a):
+            with pytest.raises(tb.TidalError) as e:
+                fn(*a)
+            assert e.value.code == code, str(e.value)
+        expect(tb.TIDAL_E_STATE, T.attach, tgt)                      # slot 0 not materialised
+        T.materialize({0: W})
+        expect(tb.TIDAL_E_STATE, T.swap, tgt)
+        expect(tb.TIDAL_E_STATE, T.detach)
+        expect(tb.TIDAL_E_STATE, T.attach, [(1, 8.0, A, B)])         # slot 1 not materialised
+        T.attach(tgt)
+        expect(tb.TIDAL_E_STATE, T.attach, tgt)
+        merged = T.slot(0)
+        expect(tb.TIDAL_E_INVAL, T.swap, [(0, 8.0, A, B), (0, 8.0, A, B)])
+        assert np.array_equal(T.slot(0), merged)                     # failed call left W alone
+        # re-materialising every merged slot resets the template: nothing is attached any more
+        T.materialize({0: W})
+        expect(tb.TIDAL_E_STATE, T.detach)
+        T.attach(tgt)
+        T.materialize({1: W})                                        # other slots: fine, still attached
+        T.detach()
+    # adapter larger than its region
+    with G.Template([(32, 64)], max_adapter_bytes=256) as T:
+        T.materialize({0: W})
+        with pytest.raises(tb.TidalError) as e:
+            T.attach(tgt)
+        assert e.value.code == tb.TIDAL_E_NOMEM
+
+
+@pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
+def test_resident_adapter_churn(orc, G, flags):
+    """Scaled-down multi-tenant churn: pool of resident adapters with ranks from {8,16,32,64},
+    alpha = 2r, Zipf schedule; step 0 attaches, every later step swaps.  The oracle replays the
+    sequence literally; in ordered mode the final state must match bit for bit."""
+    exact = flags == ORDERED
+    base = wl_mod.tiny_stack(host_dtype=wl_mod.F16, layers=2, hidden=128, ffn=344, vocab=300,
+                             lora_on=("q", "k", "v", "o"))
+    ch = wl_mod.adapter_churn(base=base, pool=6, steps=12, seed=44)
+    arrays = {i: wl_mod.draw_tensor(base, i) for i in range(len(base.tensors))}
+    pool = []
+    for a, r in enumerate(ch.ranks):
+        pool.append([(s, ch.alphas[a]) + wl_mod.draw_adapter(base, a, s, rank=r) for s in base.lora_slots])
+    with G.Template(base.shapes, chunk_bytes=256 << 10, flags=flags) as T:
+        T.materialize(arrays)
+        handles = [T.upload_adapter(items) for items in pool]
+        state = {s: T.slot(s) for s in base.lora_slots}
+        cur = None
+        for step, a in enumerate(ch.schedule):
+            if step == 0:
+                T.attach_adapter(handles[a])
+            else:
+                T.swap_adapter(handles[a])
+            for s, al, A, B in (pool[cur] if cur is not None else []):
+                orc.lora_merge(state[s], *oracle_adapter(orc, A, B), al, -1)
+            for s, al, A, B in pool[a]:
+                orc.lora_merge(state[s], *oracle_adapter(orc, A, B), al, +1)
+            cur = a
+            if not exact:                                   # compare per step, then resynchronise
+                for s in base.lora_slots:
+                    got = T.slot(s)
+                    check_against_oracle(got, state[s], False, "step %d slot %d" % (step, s))
+                    state[s] = got
+        for s in base.lora_slots:
+            check_against_oracle(T.slot(s), state[s], exact, "final slot %d" % s)
+        with pytest.raises(tb.TidalError):
+            tb.tidal_adapter_destroy(handles[cur])          # still attached
+        T.detach()
+
+
+@pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
+def test_single_linear_full_size_attach_then_swap(orc, G, flags):
+    """Configuration 1 at full size: 4096 x 4096 fp32 base, r = 8, alpha = 16, attach then swap."""
+    exact = flags == ORDERED
+    w = wl_mod.single_linear()
+    x = wl_mod.draw_tensor(w, 0)
+    A0, B0 = wl_mod.draw_adapter(w, 0, 0)
+    A1, B1 = wl_mod.draw_adapter(w, 1, 0)
+    with G.Template(w.shapes, max_adapter_bytes=1 << 20, flags=flags) as T:
+        T.materialize({0: x})
+        Wo = orc.convert_to_bf16(x)
+        T.attach([(0, w.alpha, A0, B0)])
+        orc.lora_merge(Wo, *oracle_adapter(orc, A0, B0), w.alpha, +1)
+        got = T.slot(0)
+        check_against_oracle(got, Wo, exact, "attach")
+        Wo = got.copy()
+        T.swap([(0, w.alpha, A1, B1)])
+        orc.lora_swap(Wo, *oracle_adapter(orc, A0, B0), w.alpha, *oracle_adapter(orc, A1, B1), w.alpha)
+        check_against_oracle(T.slot(0), Wo, exact, "swap")
+        # merge -> unmerge restores W within the bf16 bound
+        T.detach()
+        back = f32(T.slot(0)).astype(np.float64)
+        w0 = f32(orc.convert_to_bf16(x)).astype(np.float64)
+        assert np.max(np.abs(back - w0)) <= 2.0 ** -7 * np.max(np.abs(w0))

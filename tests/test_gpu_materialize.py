@@ -1,0 +1,146 @@
+"""GPU parity, materialisation: conversion and slot placement must be bit-exact against the
+CPU oracle.  Everything goes through the C ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2503_06421_amd import binding as tb            # noqa: E402
+from paper_2503_06421_amd import workloads as wl_mod      # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def G():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from tests import gpu_util
+    return gpu_util
+
+
+def _oracle_slots(orc, shapes, arrays):
+    arena, off = orc.materialize(shapes, arrays)
+    return arena, off
+
+
+def _compare_all_slots(orc, T, shapes, arrays):
+    arena, off = _oracle_slots(orc, shapes, arrays)
+    for i in range(len(shapes)):
+        want = orc.slot_view(arena, off, shapes, i)
+        got = T.slot(i)
+        assert np.array_equal(got, want), "slot %d differs" % i
+
+
+@pytest.mark.parametrize("dtype", [wl_mod.F32, wl_mod.F16, wl_mod.BF16])
+@pytest.mark.parametrize("pinned", [True, False])
+def test_tiny_stack_bit_exact(orc, G, dtype, pinned):
+    """Several chunks (64 KiB each), ragged tails, tiny norm vectors gathered by the CPU."""
+    w = wl_mod.tiny_stack(host_dtype=dtype, with_norms=True, hidden=200, ffn=536, vocab=1003)
+    arrays = {i: wl_mod.draw_tensor(w, i) for i in range(len(w.tensors))}
+    with G.Template(w.shapes, chunk_bytes=64 << 10, coalesce_bytes=4096) as T:
+        T.materialize(arrays, pinned=pinned)
+        _compare_all_slots(orc, T, w.shapes, arrays)
+        st = tb.tidal_get_stats(T.h)
+        assert st["h2d_bytes"] == w.source_bytes
+        if dtype != wl_mod.BF16:
+            assert st["converted_elems"] == sum(t.numel for t in w.tensors)
+            assert st["chunks"] >= w.source_bytes // (64 << 10)
+        if pinned:
+            assert 0 < st["gathered_bytes"] < w.source_bytes // 10       # only the norm vectors
+        else:
+            assert st["gathered_bytes"] == w.source_bytes
+
+
+def test_load_order_is_the_order_given(orc, G):
+    """Sources given in reverse still land in their own slots."""
+    w = wl_mod.tiny_stack(host_dtype=wl_mod.F16)
+    arrays = {i: wl_mod.draw_tensor(w, i) for i in reversed(range(len(w.tensors)))}
+    with G.Template(w.shapes, chunk_bytes=128 << 10) as T:
+        T.materialize(arrays)
+        _compare_all_slots(orc, T, w.shapes, arrays)
+
+
+def test_all_fp16_patterns(orc, G):
+    h = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16).view(np.float16).reshape(256, 256)
+    with G.Template([(256, 256)]) as T:
+        T.materialize({0: h})
+        assert np.array_equal(T.slot(0), orc.convert_to_bf16(h))
+
+
+def test_fp32_every_upper_half_times_tie_neighbourhood(orc, G):
+    lows = np.array([0, 1, 0x7FFF, 0x8000, 0x8001, 0xFFFF, 0x1234, 0xC000], dtype=np.uint32)
+    u = ((np.arange(1 << 16, dtype=np.uint32) << 16)[None, :] | lows[:, None]).reshape(8 * 256, 256)
+    x = u.view(np.float32)
+    with G.Template([x.shape]) as T:
+        T.materialize({0: x})
+        assert np.array_equal(T.slot(0), orc.convert_to_bf16(x))
+
+
+def test_fp32_random_bit_patterns_multi_chunk(orc, G):
+    rng = np.random.default_rng(5)
+    u = rng.integers(0, 1 << 32, size=(1531, 1023), dtype=np.uint64).astype(np.uint32)
+    x = u.view(np.float32)
+    with G.Template([x.shape], chunk_bytes=1 << 20) as T:
+        T.materialize({0: x})
+        assert np.array_equal(T.slot(0), orc.convert_to_bf16(x))
+
+
+def test_empty_and_degenerate(orc, G):
+    shapes = [(0, 5), (1, 1), (3, 0), (1, 7)]
+    arrays = {1: np.array([[1.5]], np.float32), 3: np.arange(7, dtype=np.float16).reshape(1, 7),
+              0: np.zeros((0, 5), np.float32)}
+    with G.Template(shapes) as T:
+        tb.tidal_materialize(T.h, [], T.copy_stream, T.compute_stream)       # nothing to do
+        T.materialize(arrays)
+        assert np.array_equal(T.slot(1), orc.convert_to_bf16(arrays[1]))
+        assert np.array_equal(T.slot(3), orc.convert_to_bf16(arrays[3]))
+
+
+def test_single_linear_full_size(orc, G):
+    """Configuration 1: 4096 x 4096 fp32 U[-0.02, 0.02] -> bf16."""
+    w = wl_mod.single_linear()
+    x = wl_mod.draw_tensor(w, 0)
+    with G.Template(w.shapes) as T:
+        T.materialize({0: x})
+        assert np.array_equal(T.slot(0), orc.convert_to_bf16(x))
+        assert tb.tidal_get_stats(T.h)["chunks"] == 2
+
+
+def test_slot_events(orc, G):
+    w = wl_mod.tiny_stack(host_dtype=wl_mod.F32)
+    arrays = {i: wl_mod.draw_tensor(w, i) for i in range(len(w.tensors))}
+    with G.Template(w.shapes, chunk_bytes=64 << 10, flags=tb.TIDAL_FLAG_SLOT_EVENTS) as T:
+        with pytest.raises(tb.TidalError):
+            tb.tidal_template_slot_wait(T.h, 0, None)
+        T.materialize(arrays, sync=False)
+        side = torch.cuda.Stream()
+        for i in range(len(w.shapes)):
+            tb.tidal_template_slot_wait(T.h, i, side)
+        side.synchronize()
+        # the side stream waited for every slot, so without any other sync the data is there
+        arena, off = orc.materialize(w.shapes, arrays)
+        for i in range(len(w.shapes)):
+            assert np.array_equal(T.slot(i), orc.slot_view(arena, off, w.shapes, i))
+        T.sync()
+
+
+def test_convert_device_standalone(orc, G):
+    rng = np.random.default_rng(2)
+    for dt, n in [(np.float32, 100003), (np.float16, 65536 + 5), (np.float32, 7), (np.float16, 8)]:
+        x = rng.normal(0, 1, n).astype(dt)
+        src = torch.from_numpy(x.view(np.uint8).copy()).cuda()
+        dst = torch.zeros(n, dtype=torch.int16, device="cuda")
+        tb.tidal_convert_device(dst, src, tb.dtype_code(x), n, None)
+        torch.cuda.synchronize()
+        got = dst.cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, orc.convert_to_bf16(x))
+
+
+def test_rematerialise_twice_and_stats(orc, G):
+    w = wl_mod.tiny_stack(host_dtype=wl_mod.F16)
+    a1 = {i: wl_mod.draw_tensor(w, i) for i in range(len(w.tensors))}
+    with G.Template(w.shapes, chunk_bytes=64 << 10) as T:
+        T.materialize(a1)
+        a2 = {i: (a1[i] * np.float16(0.5)) for i in a1}
+        T.materialize(a2)
+        _compare_all_slots(orc, T, w.shapes, a2)
