@@ -81,7 +81,10 @@ enum {
      * pass.  Results are bit-identical; this exists to demonstrate exactly that.              */
     TIDAL_FLAG_TWO_PASS_SWAP = 2,
     /* tidal_materialize records a completion event per slot, for tidal_template_slot_wait.    */
-    TIDAL_FLAG_SLOT_EVENTS = 4
+    TIDAL_FLAG_SLOT_EVENTS = 4,
+    /* Bracket every convert and LoRA kernel launch with timing events on its stream and add
+     * the elapsed times to tidal_stats (tidal_get_stats then waits for those kernels).          */
+    TIDAL_FLAG_KERNEL_TIMING = 8
 };
 
 typedef struct {
@@ -117,6 +120,8 @@ typedef struct {
     uint64_t gathered_bytes;     /* bytes that went through the CPU-gathered pinned buffer       */
     uint64_t rmw_elems;          /* W elements read-modified-written by LoRA kernels             */
     uint64_t lora_launches;      /* LoRA kernel launches                                         */
+    double lora_kernel_ms;       /* sum of LoRA kernel durations (TIDAL_FLAG_KERNEL_TIMING)      */
+    double convert_kernel_ms;    /* sum of convert kernel durations (TIDAL_FLAG_KERNEL_TIMING)   */
 } tidal_stats;
 
 /* Fill *cfg with the defaults named above.  Never fails for non-NULL cfg. */
@@ -211,7 +216,7 @@ int tidal_convert_device(void* dst_bf16 /* [device] */, const void* src /* [devi
 int tidal_h2d_peak(void* dev /* [device] */, size_t bytes, int32_t reps, void* stream,
                    double* gbytes_per_s /* [host] out */);
 
-int tidal_get_stats(const tidal_template* t, tidal_stats* out /* [host] out */);
+int tidal_get_stats(tidal_template* t, tidal_stats* out /* [host] out */);
 int tidal_reset_stats(tidal_template* t);
 
 /* Block until everything this template enqueued has completed. */

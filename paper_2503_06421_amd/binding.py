@@ -2,8 +2,9 @@
 marshalling only.  Every step of the path runs in the library's HIP kernels; there is no
 fallback of any kind: if the library is not built, or no GPU is present, calls raise.
 
-PyTorch appears only in `device_ptr` / `stream_ptr` helpers for callers that keep device
-memory and streams in torch; nothing here imports torch at module load.
+PyTorch appears only as plumbing: `device_ptr` / `stream_ptr` accept torch tensors and streams,
+and `lib()` imports torch (when installed) before loading the library so that both share one
+HIP runtime.
 """
 from __future__ import annotations
 
@@ -19,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libtidal.so")
 
 TIDAL_F32, TIDAL_F16, TIDAL_BF16 = 0, 1, 2
 TIDAL_OK, TIDAL_E_INVAL, TIDAL_E_NOMEM, TIDAL_E_STATE, TIDAL_E_HIP = 0, -1, -2, -3, -4
-TIDAL_FLAG_ORDERED_ACCUM, TIDAL_FLAG_TWO_PASS_SWAP, TIDAL_FLAG_SLOT_EVENTS = 1, 2, 4
+TIDAL_FLAG_ORDERED_ACCUM, TIDAL_FLAG_TWO_PASS_SWAP, TIDAL_FLAG_SLOT_EVENTS, TIDAL_FLAG_KERNEL_TIMING = 1, 2, 4, 8
 
 EXPORTS = [
     "tidal_config_default", "tidal_template_required_bytes", "tidal_template_create", "tidal_materialize",
@@ -58,7 +59,7 @@ class tidal_copy_piece(Structure):
 class tidal_stats(Structure):
     _fields_ = [("h2d_bytes", c_uint64), ("h2d_copies", c_uint64), ("chunks", c_uint64),
                 ("converted_elems", c_uint64), ("gathered_bytes", c_uint64), ("rmw_elems", c_uint64),
-                ("lora_launches", c_uint64)]
+                ("lora_launches", c_uint64), ("lora_kernel_ms", c_double), ("convert_kernel_ms", c_double)]
 
 
 class TidalError(RuntimeError):
@@ -79,6 +80,14 @@ def lib() -> ctypes.CDLL:
         raise FileNotFoundError(
             "%s is missing: build it with `python -m paper_2503_06421_amd.build` "
             "(there is no fallback path)" % LIB_PATH)
+    # One HIP runtime per process: the caller's device memory and streams come from PyTorch,
+    # whose wheel bundles its own libamdhip64 under the same soname as the system one.  Loading
+    # torch first makes libtidal bind to that copy; loading libtidal first would bring in a
+    # second runtime that does not see torch's device state.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(LIB_PATH)
     vp = c_void_p
     L.tidal_config_default.argtypes = [POINTER(tidal_config)]
@@ -300,7 +309,7 @@ def tidal_h2d_peak(dev, nbytes: int, reps: int = 5, stream=None) -> float:
 def tidal_get_stats(t) -> dict:
     s = tidal_stats()
     _check(lib().tidal_get_stats(t, byref(s)))
-    return {k: int(getattr(s, k)) for k, _ in tidal_stats._fields_}
+    return {k: (int if ty is c_uint64 else float)(getattr(s, k)) for k, ty in tidal_stats._fields_}
 
 
 def tidal_reset_stats(t) -> None:

@@ -23,7 +23,8 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
     if (c.chunk_bytes > ((size_t)1 << 32)) { *msg = "chunk_bytes above 4 GiB"; return false; }
     if (c.max_rank < 0 || c.max_rank > 64) { *msg = "max_rank outside 1..64"; return false; }
     if (c.coalesce_bytes > c.chunk_bytes) { *msg = "coalesce_bytes above chunk_bytes"; return false; }
-    const int32_t known = TIDAL_FLAG_ORDERED_ACCUM | TIDAL_FLAG_TWO_PASS_SWAP | TIDAL_FLAG_SLOT_EVENTS;
+    const int32_t known = TIDAL_FLAG_ORDERED_ACCUM | TIDAL_FLAG_TWO_PASS_SWAP | TIDAL_FLAG_SLOT_EVENTS |
+                          TIDAL_FLAG_KERNEL_TIMING;
     if (c.flags & ~known) { *msg = "unknown flag bits"; return false; }
     *out = c;
     return true;

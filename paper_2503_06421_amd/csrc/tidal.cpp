@@ -101,6 +101,11 @@ struct tidal_template {
     int cur_region = -1;             // in-arena region holding it, or -1
 
     tidal_stats stats = {};
+
+    // TIDAL_FLAG_KERNEL_TIMING: (start, stop) pairs not yet folded into stats, and a free list
+    struct TimedLaunch { hipEvent_t start, stop; bool lora; };
+    std::vector<TimedLaunch> timed;
+    std::vector<hipEvent_t> timing_pool;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -132,6 +137,47 @@ static int ensure_device(tidal_template* t) {
 
 static int ensure_bounce(tidal_template* t, int b) {
     if (!t->bounce[b]) HIP_TRY(hipHostMalloc((void**)&t->bounce[b], t->cfg.chunk_bytes, hipHostMallocDefault));
+    return TIDAL_OK;
+}
+
+// Kernel timing: begin returns the start event (already recorded), end records the stop event.
+static int timing_begin(tidal_template* t, hipStream_t s, hipEvent_t* start) {
+    *start = nullptr;
+    if (!(t->cfg.flags & TIDAL_FLAG_KERNEL_TIMING)) return TIDAL_OK;
+    if (t->timing_pool.empty()) {
+        HIP_TRY(hipEventCreate(start));
+    } else {
+        *start = t->timing_pool.back();
+        t->timing_pool.pop_back();
+    }
+    HIP_TRY(hipEventRecord(*start, s));
+    return TIDAL_OK;
+}
+
+static int timing_end(tidal_template* t, hipStream_t s, hipEvent_t start, bool lora) {
+    if (!start) return TIDAL_OK;
+    hipEvent_t stop = nullptr;
+    if (t->timing_pool.empty()) {
+        HIP_TRY(hipEventCreate(&stop));
+    } else {
+        stop = t->timing_pool.back();
+        t->timing_pool.pop_back();
+    }
+    HIP_TRY(hipEventRecord(stop, s));
+    t->timed.push_back(tidal_template::TimedLaunch{start, stop, lora});
+    return TIDAL_OK;
+}
+
+static int timing_drain(tidal_template* t) {
+    for (auto& tl : t->timed) {
+        HIP_TRY(hipEventSynchronize(tl.stop));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, tl.start, tl.stop));
+        (tl.lora ? t->stats.lora_kernel_ms : t->stats.convert_kernel_ms) += (double)ms;
+        t->timing_pool.push_back(tl.start);
+        t->timing_pool.push_back(tl.stop);
+    }
+    t->timed.clear();
     return TIDAL_OK;
 }
 
@@ -417,7 +463,12 @@ extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32
         rc = pl.copies_done(b, need_bounce, need_staging);
         if (rc) return rc;
         if (need_staging) {
+            hipEvent_t t0;
+            rc = timing_begin(t, pl.compute, &t0);
+            if (rc) return rc;
             HIP_TRY(launch_convert(batch, nseg, pl.compute));
+            rc = timing_end(t, pl.compute, t0, false);
+            if (rc) return rc;
             rc = pl.consumed(b);
             if (rc) return rc;
         }
@@ -691,7 +742,12 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
         lg.rp_new = std::get<3>(g.first);
         lg.r_old = std::get<4>(g.first);
         lg.r_new = std::get<5>(g.first);
+        hipEvent_t t0;
+        int trc = timing_begin(t, stream, &t0);
+        if (trc) return trc;
         HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, stream));
+        trc = timing_end(t, stream, t0, true);
+        if (trc) return trc;
         t->stats.lora_launches++;
         at += g.second.size();
     }
@@ -835,14 +891,18 @@ extern "C" int tidal_h2d_peak(void* dev, size_t bytes, int32_t reps, void* strea
     return TIDAL_OK;
 }
 
-extern "C" int tidal_get_stats(const tidal_template* t, tidal_stats* out) {
+extern "C" int tidal_get_stats(tidal_template* t, tidal_stats* out) {
     if (!t || !out) return fail(TIDAL_E_INVAL, "NULL argument");
+    int rc = timing_drain(t);
+    if (rc) return rc;
     *out = t->stats;
     return TIDAL_OK;
 }
 
 extern "C" int tidal_reset_stats(tidal_template* t) {
     if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    int rc = timing_drain(t);
+    if (rc) return rc;
     memset(&t->stats, 0, sizeof t->stats);
     return TIDAL_OK;
 }
@@ -874,6 +934,8 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
         if (t->desc_host) (void)hipHostFree(t->desc_host);
         for (SlotState& s : t->slots)
             if (s.ready) (void)hipEventDestroy(s.ready);
+        (void)timing_drain(t);
+        for (hipEvent_t e : t->timing_pool) (void)hipEventDestroy(e);
     }
     if (t->cur_resident) t->cur_resident->attached = false;
     delete t;
