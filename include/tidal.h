@@ -84,11 +84,17 @@ enum {
     TIDAL_FLAG_SLOT_EVENTS = 4,
     /* Bracket every convert and LoRA kernel launch with timing events on its stream and add
      * the elapsed times to tidal_stats (tidal_get_stats then waits for those kernels).          */
-    TIDAL_FLAG_KERNEL_TIMING = 8
+    TIDAL_FLAG_KERNEL_TIMING = 8,
+    /* tidal_materialize enqueues every chunk without waiting.  By default the calling thread
+     * stays at most two chunks ahead of the GPU (it blocks inside the call for most of the
+     * transfer, like a template-server thread would), because a deep queue of cross-stream
+     * waits makes every copy slower; with this flag the call returns as soon as everything is
+     * enqueued, at a lower transfer rate for large jobs.                                      */
+    TIDAL_FLAG_ASYNC_ENQUEUE = 16
 };
 
 typedef struct {
-    size_t chunk_bytes;        /* source bytes per staged copy unit; 0 = 32 MiB; rounded to 4 KiB;
+    size_t chunk_bytes;        /* source bytes per staged copy unit; 0 = 64 MiB; rounded to 4 KiB;
                                   must be at least 64 KiB                                        */
     int32_t max_rank;          /* largest r accepted; 0 = 64; at most 64                         */
     size_t max_adapter_bytes;  /* size of each of the two in-arena regions that hold the packed
@@ -148,8 +154,9 @@ int tidal_template_create(const tidal_slot_desc* slots /* [host] copied */, int3
  * hipMemcpyAsync on copy_stream into one of two device staging buffers -> conversion to
  * bf16 (round to nearest even, subnormals kept, NaN quieted) into the slot on
  * compute_stream; bf16 sources are copied straight into the slot.  Small tensors are
- * gathered into one copy (Sec. 6, tensor merging).  On return all work is enqueued;
- * completion of compute_stream implies completion of the whole call.  If an adapter is
+ * gathered into one copy (Sec. 6, tensor merging).  On return all work is enqueued (the
+ * call itself paces the enqueue, see TIDAL_FLAG_ASYNC_ENQUEUE); completion of
+ * compute_stream implies completion of the whole call.  If an adapter is
  * attached, the sources must cover every slot it touches (then the template is pristine
  * again and nothing is attached), else TIDAL_E_STATE.  A slot may appear at most once. */
 int tidal_materialize(tidal_template* t, const tidal_src* srcs /* [host] */, int32_t n_src,

@@ -42,20 +42,19 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint32_t round_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    uint32_t nan = (u >> 16) | 0x0040u;
-    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? nan : rounded;
-}
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // Two adjacent bf16 of W (one 32-bit word, low half = lower column) += s * (d_lo, d_hi).
+// The narrowing is v_cvt_pk_bf16_f32: round to nearest even, subnormals kept, NaN quieted with
+// sign and upper payload kept -- bit-identical to the integer formula
+// (u + 0x7FFF + ((u >> 16) & 1)) >> 16 for every one of the 2^32 inputs (checked on gfx950).
 __device__ __forceinline__ uint32_t rmw2(uint32_t w2, float d_lo, float d_hi, float s) {
-    float w_lo = __uint_as_float(w2 << 16);
-    float w_hi = __uint_as_float(w2 & 0xFFFF0000u);
-    uint32_t r_lo = round_bf16(__builtin_fmaf(s, d_lo, w_lo));
-    uint32_t r_hi = round_bf16(__builtin_fmaf(s, d_hi, w_hi));
-    return r_lo | (r_hi << 16);
+    const float w_lo = __uint_as_float(w2 << 16);
+    const float w_hi = __uint_as_float(w2 & 0xFFFF0000u);
+    const f32x2 r = {__builtin_fmaf(s, d_lo, w_lo), __builtin_fmaf(s, d_hi, w_hi)};
+    const bf16x2 b = __builtin_convertvector(r, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -131,11 +130,68 @@ __device__ __forceinline__ void apply_tile(uint32_t (&w)[16][NT / 2], const f32x
         for (int p = 0; p < NT / 2; ++p) w[v][p] = rmw2(w[v][p], acc[2 * p][v], acc[2 * p + 1][v], s);
 }
 
+// W is touched exactly once per pass, so its accesses carry the non-temporal hint (measured:
+// 4-6 % more bandwidth than plain accesses, the caches keep the A/B factors instead).
+template <typename V>
+__device__ __forceinline__ V load_w(const V* p) { return __builtin_nontemporal_load(p); }
+template <typename V>
+__device__ __forceinline__ void store_w(V* p, V v) { __builtin_nontemporal_store(v, p); }
+
+// The lane's part of a 32-row block: 16 rows (8*(v/4) + 4*h + v%4), NT adjacent columns each.
+// Interior blocks use one vector access per row; ragged ones go element by element.
+template <int NT>
+__device__ __forceinline__ void load_block(const uint16_t* __restrict__ W, int out, int in, int i0, int jl,
+                                           int h, bool full, uint32_t (&w)[16][NT / 2]) {
+    typedef typename RowVec<NT>::type vec_t;
+    if (full) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+            vec_t x = load_w((const vec_t*)(W + (int64_t)row * in + jl));
+            unpack_words<NT>(x, w[v]);
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+#pragma unroll
+            for (int p = 0; p < NT / 2; ++p) {
+                uint32_t lo = 0, hi = 0;
+                if (row < out && jl + 2 * p < in) lo = W[(int64_t)row * in + jl + 2 * p];
+                if (row < out && jl + 2 * p + 1 < in) hi = W[(int64_t)row * in + jl + 2 * p + 1];
+                w[v][p] = lo | (hi << 16);
+            }
+        }
+    }
+}
+
+template <int NT>
+__device__ __forceinline__ void store_block(uint16_t* __restrict__ W, int out, int in, int i0, int jl, int h,
+                                            bool full, const uint32_t (&w)[16][NT / 2]) {
+    typedef typename RowVec<NT>::type vec_t;
+    if (full) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+            store_w((vec_t*)(W + (int64_t)row * in + jl), pack_words<NT>(w[v]));
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
+#pragma unroll
+            for (int p = 0; p < NT / 2; ++p) {
+                if (row < out && jl + 2 * p < in) W[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[v][p] & 0xFFFFu);
+                if (row < out && jl + 2 * p + 1 < in) W[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[v][p] >> 16);
+            }
+        }
+    }
+}
+
 template <int NT, int KS0, int KS1>
 __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __restrict__ table,
                                                         int out, int in, int strips, int rowblocks,
                                                         int rc, int blocks_per_target, int total_blocks) {
-    typedef typename RowVec<NT>::type vec_t;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Workgroups are dealt round-robin to the 8 XCDs; undo that so that each XCD walks a
@@ -165,31 +221,14 @@ __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __r
     const bool strip_full = (j0 + 32 * NT <= in) && (in % NT == 0);
     const int rb_end = (rowchunk + 1) * rc < rowblocks ? (rowchunk + 1) * rc : rowblocks;
 
+    // One block of loads per wave is in flight at a time; requesting the next 32-row block
+    // early (software prefetch) was measured and is slower: the extra registers cost more than
+    // the overlap gains, the memory system is already saturated.
     for (int rb = rowchunk * rc; rb < rb_end; ++rb) {
         const int i0 = rb * 32;
         const bool full = strip_full && (i0 + 32 <= out);
         uint32_t w[16][NT / 2];
-        // lane's rows: 8*(v/4) + 4*h + v%4
-        if (full) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                vec_t x = *(const vec_t*)(W + (int64_t)row * in + jl);
-                unpack_words<NT>(x, w[v]);
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
-#pragma unroll
-                for (int p = 0; p < NT / 2; ++p) {
-                    uint32_t lo = 0, hi = 0;
-                    if (row < out && jl + 2 * p < in) lo = W[(int64_t)row * in + jl + 2 * p];
-                    if (row < out && jl + 2 * p + 1 < in) hi = W[(int64_t)row * in + jl + 2 * p + 1];
-                    w[v][p] = lo | (hi << 16);
-                }
-            }
-        }
+        load_block<NT>(W, out, in, i0, jl, h, full, w);
         f32x16 acc[NT];
         if constexpr (KS0 > 0) {
             delta_tile<NT, KS0>(d.Bp_old, out, i0, lane, bop0, acc);
@@ -199,23 +238,7 @@ __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __r
             delta_tile<NT, KS1>(d.Bp_new, out, i0, lane, bop1, acc);
             apply_tile<NT>(w, acc, d.s_new);
         }
-        if (full) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                *(vec_t*)(W + (int64_t)row * in + jl) = pack_words<NT>(w[v]);
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
-#pragma unroll
-                for (int p = 0; p < NT / 2; ++p) {
-                    if (row < out && jl + 2 * p < in) W[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[v][p] & 0xFFFFu);
-                    if (row < out && jl + 2 * p + 1 < in) W[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[v][p] >> 16);
-                }
-            }
-        }
+        store_block<NT>(W, out, in, i0, jl, h, full, w);
     }
 }
 
@@ -225,8 +248,13 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int rowblocks = (g.out + 31) / 32;
     // Rows per wave: long walks amortise the A strip, but small jobs need every CU busy.
     const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
-    int rc = (int)(tiles / 16384);
-    rc = rc < 1 ? 1 : (rc > 16 ? 16 : rc);
+    const int rc_max = (KS0 + KS1 >= 4) ? 32 : 16;
+    int rc = (int)(tiles / 8192);
+    rc = rc < 1 ? 1 : (rc > rc_max ? rc_max : rc);
+    if (const char* e = getenv("TIDAL_MFMA_RC")) {        // tuning runs only
+        const int v = atoi(e);
+        if (v >= 1 && v <= 1024) rc = v;
+    }
     const int rowchunks = (rowblocks + rc - 1) / rc;
     const int blocks_per_target = (strips * rowchunks + 3) / 4;
     const int64_t total = (int64_t)blocks_per_target * g.n_targets;
@@ -263,14 +291,11 @@ static int g_mfma_nt = 0;   // 0 = choose by rank; set from TIDAL_MFMA_NT for tu
 
 hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream) {
     if (g.n_targets <= 0 || g.out <= 0 || g.in <= 0) return hipSuccess;
-    static const int env_nt = [] {
-        const char* e = getenv("TIDAL_MFMA_NT");
-        return e ? atoi(e) : 0;
-    }();
-    int nt = env_nt ? env_nt : g_mfma_nt;
+    const char* e_nt = getenv("TIDAL_MFMA_NT");             // tuning runs only
+    int nt = e_nt ? atoi(e_nt) : g_mfma_nt;
     if (nt != 2 && nt != 4 && nt != 8) {
         // register budget: the A strips of both adapters stay resident (4*NT VGPRs per 16 ranks)
-        nt = (g.rp_old + g.rp_new <= 64) ? 4 : 2;
+        nt = (g.rp_old + g.rp_new <= 64) ? 8 : 4;
     }
     if (nt == 8) return launch_mfma_old<8>(g, stream);
     if (nt == 4) return launch_mfma_old<4>(g, stream);

@@ -14,7 +14,7 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
         c.flags = 0;
         c.coalesce_bytes = 0;
     }
-    if (c.chunk_bytes == 0) c.chunk_bytes = (size_t)32 << 20;
+    if (c.chunk_bytes == 0) c.chunk_bytes = (size_t)64 << 20;
     if (c.max_rank == 0) c.max_rank = 64;
     if (c.coalesce_bytes == 0) c.coalesce_bytes = (size_t)64 << 10;
     c.chunk_bytes = align_up(c.chunk_bytes, 4096);
@@ -24,7 +24,7 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
     if (c.max_rank < 0 || c.max_rank > 64) { *msg = "max_rank outside 1..64"; return false; }
     if (c.coalesce_bytes > c.chunk_bytes) { *msg = "coalesce_bytes above chunk_bytes"; return false; }
     const int32_t known = TIDAL_FLAG_ORDERED_ACCUM | TIDAL_FLAG_TWO_PASS_SWAP | TIDAL_FLAG_SLOT_EVENTS |
-                          TIDAL_FLAG_KERNEL_TIMING;
+                          TIDAL_FLAG_KERNEL_TIMING | TIDAL_FLAG_ASYNC_ENQUEUE;
     if (c.flags & ~known) { *msg = "unknown flag bits"; return false; }
     *out = c;
     return true;

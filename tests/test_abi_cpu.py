@@ -39,7 +39,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_config_defaults():
     c = tb.tidal_config_default()
-    assert c.chunk_bytes == 32 << 20 and c.max_rank == 64 and c.coalesce_bytes == 64 << 10
+    assert c.chunk_bytes == 64 << 20 and c.max_rank == 64 and c.coalesce_bytes == 64 << 10
     assert c.max_adapter_bytes == 0 and c.flags == 0
 
 
@@ -190,14 +190,14 @@ def test_copy_plan_covers_everything_once(pinned, dtype):
 
 
 def test_copy_plan_llama7b_chunk_count():
-    """Tensor merging at scale: 226 tensors / 13.48 GB of fp16 become ~400 uniform copies."""
+    """Tensor merging at scale: 226 tensors / 13.48 GB of fp16 become ~200 uniform chunks."""
     w = wl_mod.llama2_7b()
     t = tb.tidal_template_create(w.shapes, FAKE_ARENA, 1 << 40, None)
     try:
         srcs = [(i, tb.TIDAL_F16, 0x1000) for i in range(len(w.shapes))]
         plan = tb.tidal_materialize_plan(t, srcs, assume_pinned=1)
         assert sum(p.src_bytes for p in plan) == w.source_bytes
-        assert plan[-1].chunk + 1 == -(-w.source_bytes // (32 << 20))     # every chunk full but the last
+        assert plan[-1].chunk + 1 == -(-w.source_bytes // (64 << 20))     # every chunk full but the last
         assert not any(p.gathered for p in plan)
     finally:
         tb.tidal_template_destroy(t)
