@@ -84,18 +84,20 @@ def main() -> int:
     log("drew %d tensors, %.2f GB, in %.1f s (%d threads)" % (len(views), wl.source_bytes / 1e9,
                                                               time.perf_counter() - t0, threads))
 
-    adapters = []           # two adapters, host dtype of the base, pinned
-    keep = []
+    adapters = []           # two adapters, host dtype of the base, each one contiguous pinned block
+    keep = []               # (A, B of target 0, A, B of target 1, ...) like an adapter checkpoint in a host pool
     for a in (0, 1):
-        items = []
+        mats = []
         for s in wl.lora_slots:
-            A, B = wl_mod.draw_adapter(wl, a, s)
-            for m in (A, B):
-                pm = torch.empty(m.size * m.itemsize, dtype=torch.uint8, pin_memory=True)
-                v = pm.numpy().view(m.dtype).reshape(m.shape)
-                v[...] = m
-                keep.append(pm)
-                items.append(v)
+            mats.extend(wl_mod.draw_adapter(wl, a, s))
+        blob = torch.empty(sum(m.size * m.itemsize for m in mats), dtype=torch.uint8, pin_memory=True)
+        keep.append(blob)
+        items, o = [], 0
+        for m in mats:
+            v = blob.numpy()[o:o + m.size * m.itemsize].view(m.dtype).reshape(m.shape)
+            v[...] = m
+            items.append(v)
+            o += m.size * m.itemsize
         adapters.append([(s, wl.alpha, items[2 * i], items[2 * i + 1]) for i, s in enumerate(wl.lora_slots)])
     targets = [tb.targets_from_arrays(ad) for ad in adapters]
 

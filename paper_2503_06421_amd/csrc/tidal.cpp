@@ -347,31 +347,32 @@ struct Pipeline {
     }
 
     // Copy one piece of `bytes` host bytes to device address dst; gathered pieces pass through
-    // pinned buffer b at buf_off first.
+    // pinned buffer b at buf_off first.  Consecutive pieces whose source and destination both
+    // continue where the previous one ended go out as one DMA (tensor merging, Sec. 6): that is
+    // the case for CPU-gathered pieces by construction, and for caller memory whenever tensors
+    // sit back to back in a pinned pool.
     int put(bool gathered, int b, int64_t buf_off, const char* host, size_t bytes, char* dst) {
         t->stats.h2d_bytes += bytes;
-        if (!gathered) {
-            int rc = flush();
-            if (rc) return rc;
-            HIP_TRY(hipMemcpyAsync(dst, host, bytes, hipMemcpyHostToDevice, copy));
-            t->stats.h2d_copies++;
-            return TIDAL_OK;
+        const char* src = host;
+        size_t slack = 0;               // alignment gap that may be copied along
+        if (gathered) {
+            char* stage = t->bounce[b] + buf_off;
+            memcpy(stage, host, bytes);
+            t->stats.gathered_bytes += bytes;
+            src = stage;
+            slack = kSlotAlign - 1;     // gaps inside the library's own buffers only ever land in padding
         }
-        char* stage = t->bounce[b] + buf_off;
-        memcpy(stage, host, bytes);
-        t->stats.gathered_bytes += bytes;
-        // extend the run when source and destination advance by the same amount (alignment
-        // gaps are copied along; they only ever land in padding)
-        if (run && stage >= run_src && (size_t)(stage - run_src) == (size_t)(dst - run_dst) &&
-            (size_t)(stage - run_src) >= run_len && (size_t)(stage - run_src) - run_len < kSlotAlign) {
-            run_len = (size_t)(stage - run_src) + bytes;
+        if (run && src >= run_src && dst >= run_dst && (size_t)(src - run_src) == (size_t)(dst - run_dst) &&
+            (size_t)(src - run_src) >= run_len && (size_t)(src - run_src) - run_len <= slack &&
+            run_len + bytes <= ((size_t)1 << 30)) {
+            run_len = (size_t)(src - run_src) + bytes;
             return TIDAL_OK;
         }
         int rc = flush();
         if (rc) return rc;
         run = true;
         run_dst = dst;
-        run_src = stage;
+        run_src = src;
         run_len = bytes;
         return TIDAL_OK;
     }

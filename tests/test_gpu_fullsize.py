@@ -1,0 +1,120 @@
+"""GPU parity at full size, in the launch configuration bench.py times (default config: 64 MiB
+chunks, matrix-core LoRA kernels, pinned host pool, adapters by host pointers).
+
+Llama2-7B-shaped stack (13.48 GB fp16 -> bf16, r=16 on q and v of 32 layers):
+  * every one of the 226 slots is compared bit for bit with the oracle's conversion,
+  * after attach and after swap, three 64-row bands (top, a ragged middle, bottom) of every
+    targeted slot are recomputed by the oracle from the GPU's previous state and compared
+    within 2^-7 * max|W| (and one bf16 ulp per element),
+  * every untargeted slot must be bit-identical to its materialised state (compared on device).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2503_06421_amd import binding as tb            # noqa: E402
+from paper_2503_06421_amd import workloads as wl_mod      # noqa: E402
+
+
+def f32(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def test_llama2_7b_shaped_materialize_attach_swap(orc):
+    assert torch.cuda.is_available()
+    wl = wl_mod.llama2_7b()
+    isz = wl_mod.ITEMSIZE[wl.host_dtype]
+    pool = torch.empty(wl.source_bytes, dtype=torch.uint8, pin_memory=True)
+    pool_np = pool.numpy()
+    views, off = [], 0
+    for t in wl.tensors:
+        n = t.numel * isz
+        views.append(pool_np[off:off + n].view(np.float16).reshape(t.rows, t.cols))
+        off += n
+    wl_mod.draw_all(wl, views, threads=16)
+    print("drawn", flush=True)
+
+    ads = [[(s, wl.alpha) + wl_mod.draw_adapter(wl, a, s) for s in wl.lora_slots] for a in (0, 1)]
+    cfg0 = tb.make_config()
+    need0 = tb.tidal_template_required_bytes(wl.shapes, cfg0)
+    # size of the packed adapter: in x 16 + out x 16 bf16 per target
+    adapter_bytes = sum(2 * 16 * (wl.tensors[s].rows + wl.tensors[s].cols) for s in wl.lora_slots)
+    cfg = tb.make_config(max_adapter_bytes=adapter_bytes)
+    need = tb.tidal_template_required_bytes(wl.shapes, cfg)
+    assert need > need0
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    T = tb.tidal_template_create(wl.shapes, arena, need, cfg)
+    copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def dev_slot(i):
+        p, nb = tb.tidal_template_slot_ptr(T, i)
+        o = p - arena.data_ptr()
+        return arena[o:o + nb]
+
+    def host_rows(i, r0, r1):
+        cols = wl.tensors[i].cols
+        return dev_slot(i)[2 * r0 * cols: 2 * r1 * cols].cpu().numpy().view(np.uint16).reshape(r1 - r0, cols)
+
+    try:
+        tb.tidal_materialize(T, [(i, wl.host_dtype, tb.host_ptr(v)) for i, v in enumerate(views)], copy_s, comp_s)
+        tb.tidal_template_sync(T)
+        torch.cuda.synchronize()
+        print("materialised", flush=True)
+        for i, v in enumerate(views):
+            got = dev_slot(i).cpu().numpy().view(np.uint16).reshape(v.shape)
+            assert np.array_equal(got, orc.convert_to_bf16(v)), "slot %d (%s)" % (i, wl.tensors[i].name)
+        print("conversion and placement bit-exact on all %d slots" % len(views), flush=True)
+        end = tb.tidal_template_slot_ptr(T, len(views) - 1)
+        slot_area = end[0] - arena.data_ptr() + end[1]
+        pristine = arena[:slot_area].clone()
+
+        bands = [(0, 64), (1987, 2051), (4032, 4096)]
+        prev = {(s, b): host_rows(s, *b) for s in wl.lora_slots for b in bands}
+
+        def check(tag, old, new):
+            worst = 0.0
+            for idx, s in enumerate(wl.lora_slots):
+                for b in bands:
+                    want = prev[(s, b)].copy()
+                    if old is not None:
+                        _, al, A, B = old[idx]
+                        orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B[b[0]:b[1]]), al, -1)
+                    _, al, A, B = new[idx]
+                    orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B[b[0]:b[1]]), al, +1)
+                    got = host_rows(s, *b)
+                    g, w = f32(got), f32(want)
+                    assert np.max(np.abs(g - w)) <= 2.0 ** -7 * np.max(np.abs(w)), (tag, s, b)
+                    assert np.all(np.abs(g - w) <= np.abs(w) * 2.0 ** -7 + 2.0 ** -20 * np.max(np.abs(w))), (tag, s, b)
+                    assert np.mean(got != want) < 2e-3, (tag, s, b)
+                    assert np.any(got != prev[(s, b)]), (tag, s, b)          # the update happened
+                    worst = max(worst, float(np.max(np.abs(g - w)) / np.max(np.abs(w))))
+                    prev[(s, b)] = got
+            print("%s: %d bands checked, worst max-abs-err / max|W| = %.3g" % (tag, len(prev), worst), flush=True)
+
+        def untouched():
+            targeted = set(wl.lora_slots)
+            for i in range(len(views)):
+                if i in targeted:
+                    continue
+                p, nb = tb.tidal_template_slot_ptr(T, i)
+                o = p - arena.data_ptr()
+                assert torch.equal(arena[o:o + nb], pristine[o:o + nb]), "untargeted slot %d changed" % i
+
+        tb.tidal_lora_attach(T, tb.targets_from_arrays(ads[0]), comp_s)
+        tb.tidal_template_sync(T)
+        check("attach", None, ads[0])
+        untouched()
+        tb.tidal_lora_swap(T, tb.targets_from_arrays(ads[1]), comp_s)
+        tb.tidal_template_sync(T)
+        check("swap", ads[0], ads[1])
+        untouched()
+        st = tb.tidal_get_stats(T)
+        assert st["lora_launches"] == 2 and st["rmw_elems"] == 2 * wl.lora_w_elements
+        # 201 chunks of 64 MiB for the stack; an adapter upload packs at most 32 factors per chunk
+        assert st["chunks"] == -(-wl.source_bytes // (64 << 20)) + 2 * (2 * len(wl.lora_slots) // 32)
+    finally:
+        torch.cuda.synchronize()
+        tb.tidal_template_destroy(T)
