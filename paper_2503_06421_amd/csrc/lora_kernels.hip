@@ -36,6 +36,15 @@
 
 namespace tidal {
 
+// Pointers that reach a kernel through a descriptor in memory are generic to the compiler, and
+// generic accesses become flat_load/flat_store, which also occupy the LDS path and its counter.
+// Everything these kernels touch outside LDS is global memory, so say so.
+#define TIDAL_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ TIDAL_GLOBAL T* as_global(T* p) {
+    return (TIDAL_GLOBAL T*)p;
+}
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -95,7 +104,7 @@ __device__ __forceinline__ void load_strip(const uint16_t* __restrict__ At, int 
             j = j < in ? j : in - 1;                       // ragged strip: clamp, masked at the store
             const uint16_t* p = At + (int64_t)j * (16 * KS) + 8 * kg;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) bop[T][ks] = *(const bf16x8*)(p + 16 * ks);
+            for (int ks = 0; ks < KS; ++ks) bop[T][ks] = *as_global((const bf16x8*)(p + 16 * ks));
         }
     }
 }
@@ -110,7 +119,7 @@ __device__ __forceinline__ void delta_tile(const uint16_t* __restrict__ Bp, int 
         const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
         bf16x8 aop[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) aop[ks] = *(const bf16x8*)(p + 16 * ks);
+        for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
 #pragma unroll
         for (int T = 0; T < NT; ++T) {
             f32x16 c = {0};
@@ -133,9 +142,9 @@ __device__ __forceinline__ void apply_tile(uint32_t (&w)[16][NT / 2], const f32x
 // W is touched exactly once per pass, so its accesses carry the non-temporal hint (measured:
 // 4-6 % more bandwidth than plain accesses, the caches keep the A/B factors instead).
 template <typename V>
-__device__ __forceinline__ V load_w(const V* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ V load_w(const V* p) { return __builtin_nontemporal_load(as_global(p)); }
 template <typename V>
-__device__ __forceinline__ void store_w(V* p, V v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void store_w(V* p, V v) { __builtin_nontemporal_store(v, as_global(p)); }
 
 // The lane's part of a 32-row block: 16 rows (8*(v/4) + 4*h + v%4), NT adjacent columns each.
 // Interior blocks use one vector access per row; ragged ones go element by element.
@@ -157,8 +166,8 @@ __device__ __forceinline__ void load_block(const uint16_t* __restrict__ W, int o
 #pragma unroll
             for (int p = 0; p < NT / 2; ++p) {
                 uint32_t lo = 0, hi = 0;
-                if (row < out && jl + 2 * p < in) lo = W[(int64_t)row * in + jl + 2 * p];
-                if (row < out && jl + 2 * p + 1 < in) hi = W[(int64_t)row * in + jl + 2 * p + 1];
+                if (row < out && jl + 2 * p < in) lo = as_global(W)[(int64_t)row * in + jl + 2 * p];
+                if (row < out && jl + 2 * p + 1 < in) hi = as_global(W)[(int64_t)row * in + jl + 2 * p + 1];
                 w[v][p] = lo | (hi << 16);
             }
         }
@@ -181,8 +190,8 @@ __device__ __forceinline__ void store_block(uint16_t* __restrict__ W, int out, i
             const int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
 #pragma unroll
             for (int p = 0; p < NT / 2; ++p) {
-                if (row < out && jl + 2 * p < in) W[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[v][p] & 0xFFFFu);
-                if (row < out && jl + 2 * p + 1 < in) W[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[v][p] >> 16);
+                if (row < out && jl + 2 * p < in) as_global(W)[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[v][p] & 0xFFFFu);
+                if (row < out && jl + 2 * p + 1 < in) as_global(W)[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[v][p] >> 16);
             }
         }
     }
@@ -242,6 +251,109 @@ __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __r
     }
 }
 
+// Variant for large ranks.  With 64 + 64 ranks the A strips of both adapters would need 256
+// VGPRs per lane; instead the four waves of a workgroup share ONE column strip, stage its A
+// operands once in LDS -- already in MFMA operand order, so every later read is a linear,
+// conflict-free 16-byte-per-lane ds_read -- and take interleaved 32-row blocks of the same
+// row range.  Registers then hold only the accumulators and W, which buys a second or third
+// wave per SIMD exactly where the arithmetic per block is largest.
+template <int NT, int KS>
+__device__ __forceinline__ void delta_tile_lds(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
+                                               const bf16x8* strip, f32x16 (&acc)[NT]) {
+    int m = i0 + (lane & 31);
+    m = m < out ? m : out - 1;
+    const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
+    bf16x8 aop[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+#pragma unroll
+    for (int T = 0; T < NT; ++T) {
+        f32x16 c = {0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[(T * KS + ks) * 64 + lane], c, 0, 0, 0);
+        acc[T] = c;
+    }
+}
+
+template <int NT, int KS>
+__device__ __forceinline__ void stage_strip(const uint16_t* __restrict__ At, int in, int j0, int lane, int wave,
+                                            bf16x8* strip) {
+    const int n = lane & 31, kg = lane >> 5;
+    for (int p = wave; p < NT * KS; p += 4) {
+        const int T = p / KS, ks = p - T * KS;
+        int j = j0 + NT * n + T;
+        j = j < in ? j : in - 1;
+        strip[p * 64 + lane] = *as_global((const bf16x8*)(At + (int64_t)j * (16 * KS) + 16 * ks + 8 * kg));
+    }
+}
+
+template <int NT, int KS0, int KS1>
+__global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraTargetDev* __restrict__ table, int out,
+                                                            int in, int strips, int rowblocks, int rcb,
+                                                            int blocks_per_target, int total_blocks) {
+    __shared__ bf16x8 strip_lds[(KS0 + KS1) * NT * 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= total_blocks) return;                        // whole workgroup leaves together
+    const int target = L / blocks_per_target;
+    const int item = L - target * blocks_per_target;
+    const int rowchunk = item / strips;
+    const int strip = item - rowchunk * strips;
+    const int j0 = strip * (32 * NT);
+
+    const LoraTargetDev d = table[target];
+    uint16_t* __restrict__ W = d.W;
+    if constexpr (KS0 > 0) stage_strip<NT, KS0>(d.At_old, in, j0, lane, wave, strip_lds);
+    if constexpr (KS1 > 0) stage_strip<NT, KS1>(d.At_new, in, j0, lane, wave, strip_lds + KS0 * NT * 64);
+    __syncthreads();
+
+    const int n = lane & 31, h = lane >> 5;
+    const int jl = j0 + NT * n;
+    const bool strip_full = (j0 + 32 * NT <= in) && (in % NT == 0);
+    const int rb_end = (rowchunk + 1) * rcb < rowblocks ? (rowchunk + 1) * rcb : rowblocks;
+    for (int rb = rowchunk * rcb + wave; rb < rb_end; rb += 4) {
+        const int i0 = rb * 32;
+        const bool full = strip_full && (i0 + 32 <= out);
+        uint32_t w[16][NT / 2];
+        load_block<NT>(W, out, in, i0, jl, h, full, w);
+        f32x16 acc[NT];
+        if constexpr (KS0 > 0) {
+            delta_tile_lds<NT, KS0>(d.Bp_old, out, i0, lane, strip_lds, acc);
+            apply_tile<NT>(w, acc, d.s_old);
+        }
+        if constexpr (KS1 > 0) {
+            delta_tile_lds<NT, KS1>(d.Bp_new, out, i0, lane, strip_lds + KS0 * NT * 64, acc);
+            apply_tile<NT>(w, acc, d.s_new);
+        }
+        store_block<NT>(W, out, in, i0, jl, h, full, w);
+    }
+}
+
+template <int NT, int KS0, int KS1>
+static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
+    const int strips = (g.in + 32 * NT - 1) / (32 * NT);
+    const int rowblocks = (g.out + 31) / 32;
+    const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
+    int rc = (int)(tiles / 8192);                    // 32-row blocks per wave
+    rc = rc < 1 ? 1 : (rc > 32 ? 32 : rc);
+    if (const char* e = getenv("TIDAL_MFMA_RC")) {   // tuning runs only
+        const int v = atoi(e);
+        if (v >= 1 && v <= 1024) rc = v;
+    }
+    const int rcb = 4 * rc;
+    const int rowchunks = (rowblocks + rcb - 1) / rcb;
+    const int blocks_per_target = strips * rowchunks;
+    const int64_t total = (int64_t)blocks_per_target * g.n_targets;
+    if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((total + 7) / 8 * 8);
+    hipLaunchKernelGGL((lora_mfma_lds_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, g.table, g.out,
+                       g.in, strips, rowblocks, rcb, blocks_per_target, (int)total);
+    return hipGetLastError();
+}
+
 template <int NT, int KS0, int KS1>
 static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int strips = (g.in + 32 * NT - 1) / (32 * NT);
@@ -265,41 +377,53 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// A strips stay in registers below this many 16-rank steps in total (measured: >= 6.1 TB/s for
+// every rank pair but 64 -> 64); from it on they are staged in LDS (64 -> 64: 5.3 instead of
+// 4.7 TB/s).
+constexpr int kLdsFromSteps = 8;
+
+template <int NT, int KS0, int KS1>
+static hipError_t launch_mfma_pick(const LoraGroup& g, hipStream_t stream, int use_lds) {
+    if constexpr (KS0 + KS1 == 0) {
+        return hipSuccess;
+    } else {
+        if (use_lds < 0) use_lds = (KS0 + KS1 >= kLdsFromSteps) ? 1 : 0;
+        if (use_lds) return launch_mfma_lds_inst<NT, KS0, KS1>(g, stream);
+        return launch_mfma_inst<NT, KS0, KS1>(g, stream);
+    }
+}
+
 template <int NT, int KS0>
-static hipError_t launch_mfma_new(const LoraGroup& g, hipStream_t stream) {
+static hipError_t launch_mfma_new(const LoraGroup& g, hipStream_t stream, int use_lds) {
     switch (g.rp_new) {
-        case 0: if constexpr (KS0 > 0) return launch_mfma_inst<NT, KS0, 0>(g, stream); else return hipSuccess;
-        case 16: return launch_mfma_inst<NT, KS0, 1>(g, stream);
-        case 32: return launch_mfma_inst<NT, KS0, 2>(g, stream);
-        case 64: return launch_mfma_inst<NT, KS0, 4>(g, stream);
+        case 0: return launch_mfma_pick<NT, KS0, 0>(g, stream, use_lds);
+        case 16: return launch_mfma_pick<NT, KS0, 1>(g, stream, use_lds);
+        case 32: return launch_mfma_pick<NT, KS0, 2>(g, stream, use_lds);
+        case 64: return launch_mfma_pick<NT, KS0, 4>(g, stream, use_lds);
     }
     return hipErrorInvalidValue;
 }
 
 template <int NT>
-static hipError_t launch_mfma_old(const LoraGroup& g, hipStream_t stream) {
+static hipError_t launch_mfma_old(const LoraGroup& g, hipStream_t stream, int use_lds) {
     switch (g.rp_old) {
-        case 0: return launch_mfma_new<NT, 0>(g, stream);
-        case 16: return launch_mfma_new<NT, 1>(g, stream);
-        case 32: return launch_mfma_new<NT, 2>(g, stream);
-        case 64: return launch_mfma_new<NT, 4>(g, stream);
+        case 0: return launch_mfma_new<NT, 0>(g, stream, use_lds);
+        case 16: return launch_mfma_new<NT, 1>(g, stream, use_lds);
+        case 32: return launch_mfma_new<NT, 2>(g, stream, use_lds);
+        case 64: return launch_mfma_new<NT, 4>(g, stream, use_lds);
     }
     return hipErrorInvalidValue;
 }
 
-static int g_mfma_nt = 0;   // 0 = choose by rank; set from TIDAL_MFMA_NT for tuning runs
-
 hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream) {
     if (g.n_targets <= 0 || g.out <= 0 || g.in <= 0) return hipSuccess;
     const char* e_nt = getenv("TIDAL_MFMA_NT");             // tuning runs only
-    int nt = e_nt ? atoi(e_nt) : g_mfma_nt;
-    if (nt != 2 && nt != 4 && nt != 8) {
-        // register budget: the A strips of both adapters stay resident (4*NT VGPRs per 16 ranks)
-        nt = (g.rp_old + g.rp_new <= 64) ? 8 : 4;
-    }
-    if (nt == 8) return launch_mfma_old<8>(g, stream);
-    if (nt == 4) return launch_mfma_old<4>(g, stream);
-    return launch_mfma_old<2>(g, stream);
+    const char* e_lds = getenv("TIDAL_MFMA_LDS");           // tuning runs only
+    int nt = e_nt ? atoi(e_nt) : 0;
+    const int use_lds = e_lds ? atoi(e_lds) : -1;
+    if (nt != 4 && nt != 8) nt = 8;
+    if (nt == 8) return launch_mfma_old<8>(g, stream, use_lds);
+    return launch_mfma_old<4>(g, stream, use_lds);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -317,7 +441,7 @@ __device__ __forceinline__ void stage_rank_tiles(const uint16_t* __restrict__ At
     {   // 256 columns x 16 ranks: one column per thread, two 16-byte loads
         int j = j0 + tid;
         j = j < in ? j : in - 1;
-        const u32x4* p = (const u32x4*)(At + (int64_t)j * rp + k0);
+        const TIDAL_GLOBAL u32x4* p = as_global((const u32x4*)(At + (int64_t)j * rp + k0));
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             u32x4 x = p[q];
@@ -333,7 +457,7 @@ __device__ __forceinline__ void stage_rank_tiles(const uint16_t* __restrict__ At
         const int row = tid & 63, q = tid >> 6;
         int i = i0 + row;
         i = i < out ? i : out - 1;
-        u32x4 x = *(const u32x4*)(Bp + (int64_t)i * rp + k0 + 8 * q);
+        u32x4 x = *as_global((const u32x4*)(Bp + (int64_t)i * rp + k0 + 8 * q));
         const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -396,14 +520,14 @@ __global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraTargetDev* 
     for (int rr = 0; rr < 8; ++rr) {
         const int row = i0 + 8 * rg + rr;
         if (vec_ok && row < out) {
-            u32x4 x = *(const u32x4*)(W + (int64_t)row * in + jl);
+            u32x4 x = *as_global((const u32x4*)(W + (int64_t)row * in + jl));
             w[rr][0] = x.x; w[rr][1] = x.y; w[rr][2] = x.z; w[rr][3] = x.w;
         } else {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 uint32_t lo = 0, hi = 0;
-                if (row < out && jl + 2 * p < in) lo = W[(int64_t)row * in + jl + 2 * p];
-                if (row < out && jl + 2 * p + 1 < in) hi = W[(int64_t)row * in + jl + 2 * p + 1];
+                if (row < out && jl + 2 * p < in) lo = as_global(W)[(int64_t)row * in + jl + 2 * p];
+                if (row < out && jl + 2 * p + 1 < in) hi = as_global(W)[(int64_t)row * in + jl + 2 * p + 1];
                 w[rr][p] = lo | (hi << 16);
             }
         }
@@ -416,12 +540,12 @@ __global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraTargetDev* 
         if (vec_ok && row < out) {
             u32x4 x;
             x.x = w[rr][0]; x.y = w[rr][1]; x.z = w[rr][2]; x.w = w[rr][3];
-            *(u32x4*)(W + (int64_t)row * in + jl) = x;
+            *as_global((u32x4*)(W + (int64_t)row * in + jl)) = x;
         } else {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                if (row < out && jl + 2 * p < in) W[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[rr][p] & 0xFFFFu);
-                if (row < out && jl + 2 * p + 1 < in) W[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[rr][p] >> 16);
+                if (row < out && jl + 2 * p < in) as_global(W)[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[rr][p] & 0xFFFFu);
+                if (row < out && jl + 2 * p + 1 < in) as_global(W)[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[rr][p] >> 16);
             }
         }
     }
