@@ -135,7 +135,7 @@ int tidal_config_default(tidal_config* cfg /* [host] out */);
 
 /* Bytes of device arena tidal_template_create needs: slot area (each slot 256-byte aligned,
  * in the given order -- the access order of Sec. 4.2) + two staging buffers of chunk_bytes
- * + two adapter regions of max_adapter_bytes + a launch-descriptor area.  Returns 0 on
+ * + two adapter regions of max_adapter_bytes.  Returns 0 on
  * invalid arguments. */
 size_t tidal_template_required_bytes(const tidal_slot_desc* slots /* [host] */, int32_t n,
                                      const tidal_config* cfg /* [host] NULL = defaults */);

@@ -1,0 +1,256 @@
+"""Measurements of the other workload configurations (bench.py at the repository root times the
+Llama2-7B-shaped headline workload).
+
+    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b
+
+Each prints one JSON line.  Kernel times come from the library's HIP events around each launch
+(TIDAL_FLAG_KERNEL_TIMING); call-level times from events on the compute stream.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+import torch
+
+from . import binding as tb
+from . import harness as hz
+from . import workloads as wl_mod
+
+HBM_PEAK = 8000.0
+
+
+def log(*a):
+    print("[bench_configs]", *a, file=sys.stderr, flush=True)
+
+
+def ev():
+    return torch.cuda.Event(enable_timing=True)
+
+
+def lora_bytes(wl, rank_old, rank_new):
+    return 4 * wl.lora_w_elements + (hz.packed_adapter_bytes(wl, rank_old) if rank_old else 0) + \
+        (hz.packed_adapter_bytes(wl, rank_new) if rank_new else 0)
+
+
+def bench_single(args):
+    """Configuration 1: one 4096 x 4096 fp32 layer, r = 8.  W (32 MiB) fits in the 256 MB Infinity
+    Cache, so back-to-back timing of the same matrix measures the cache; a second set of numbers
+    rotates over 24 distinct copies (768 MiB) so every pass comes from HBM."""
+    wl = wl_mod.single_linear()
+    copies = 24
+    shapes = wl.shapes * copies
+    pool = hz.HostPool(wl)
+    ad = [hz.pinned_adapter(wl, a) for a in (0, 1)]
+    T = hz.DeviceTemplate(shapes, max_adapter_bytes=hz.packed_adapter_bytes(wl), flags=tb.TIDAL_FLAG_KERNEL_TIMING)
+    out = {"config": "single_linear_4096_fp32_r8"}
+    try:
+        src0 = pool.sources()[0]
+        # materialise (PCIe): 64 MiB of fp32 -> one chunk
+        times = []
+        for rep in range(6):
+            e0, e1 = ev(), ev()
+            e0.record(T.compute_stream)
+            tb.tidal_materialize(T.h, [(rep % copies, src0[1], src0[2])], T.copy_stream, T.compute_stream)
+            e1.record(T.compute_stream)
+            T.sync()
+            times.append(e0.elapsed_time(e1))
+        out["materialize_ms"] = round(float(np.median(times[1:])), 4)
+        out["materialize_GBps"] = round(wl.source_bytes / np.median(times[1:]) / 1e6, 2)
+        tb.tidal_materialize(T.h, [(i, src0[1], src0[2]) for i in range(copies)], T.copy_stream, T.compute_stream)
+        T.sync()
+
+        def targets(a, slot):
+            s, al, A, B = ad[a][0][0]
+            return tb.targets_from_arrays([(slot, al, A, B)])
+
+        # (a) same matrix again and again: attach / swap / detach, call-level (includes the upload)
+        call_ms = {"attach": [], "swap": [], "detach": []}
+        tb.tidal_reset_stats(T.h)
+        for rep in range(12):
+            e = [ev() for _ in range(4)]
+            e[0].record(T.compute_stream)
+            tb.tidal_lora_attach(T.h, targets(0, 0), T.compute_stream)
+            e[1].record(T.compute_stream)
+            tb.tidal_lora_swap(T.h, targets(1, 0), T.compute_stream)
+            e[2].record(T.compute_stream)
+            tb.tidal_lora_detach(T.h, T.compute_stream)
+            e[3].record(T.compute_stream)
+            T.sync()
+            if rep >= 2:
+                for k, name in enumerate(("attach", "swap", "detach")):
+                    call_ms[name].append(e[k].elapsed_time(e[k + 1]))
+        st = tb.tidal_get_stats(T.h)
+        kms = st["lora_kernel_ms"] / st["lora_launches"]
+        out["cache_resident"] = {
+            "attach_ms_per_invocation": round(float(np.median(call_ms["attach"])), 4),
+            "swap_ms_per_invocation": round(float(np.median(call_ms["swap"])), 4),
+            "detach_ms_per_invocation": round(float(np.median(call_ms["detach"])), 4),
+            "kernel_ms_avg": round(kms, 5),
+            "kernel_GBps": round(lora_bytes(wl, 0, 8) / kms / 1e6, 1),
+            "note": "32 MiB W stays in the Infinity Cache between passes"}
+        # (b) rotate over distinct copies with resident adapters: HBM-fed kernel time
+        mems, handles = [], []
+        for slot in range(copies):
+            for a in (0, 1):
+                tg = targets(a, slot)
+                nb = tb.tidal_adapter_required_bytes(T.h, tg)
+                mem = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+                handles.append(tb.tidal_adapter_upload(T.h, tg, mem, nb, T.compute_stream))
+                mems.append(mem)
+        T.sync()
+        tb.tidal_reset_stats(T.h)
+        for rep in range(3):
+            for slot in range(copies):
+                tb.tidal_lora_attach_adapter(T.h, handles[2 * slot], T.compute_stream)
+                tb.tidal_lora_swap_adapter(T.h, handles[2 * slot + 1], T.compute_stream)
+                tb.tidal_lora_detach(T.h, T.compute_stream)
+        T.sync()
+        st = tb.tidal_get_stats(T.h)
+        kms = st["lora_kernel_ms"] / st["lora_launches"]
+        out["hbm_fed"] = {"kernel_ms_avg": round(kms, 5), "kernel_GBps": round(lora_bytes(wl, 0, 8) / kms / 1e6, 1),
+                          "frac_of_hbm_peak": round(lora_bytes(wl, 0, 8) / kms / 1e6 / HBM_PEAK, 4),
+                          "note": "rotating over %d copies of W (%d MiB) so no pass is served from cache" % (copies, copies * 32)}
+        for h in handles:
+            tb.tidal_adapter_destroy(h)
+    finally:
+        T.close()
+    return out
+
+
+def bench_stack(args, wl, pool_limit=None):
+    """materialise + attach for a whole stack (13B-shaped, 70B-shaped)."""
+    pool = hz.HostPool(wl, limit_bytes=pool_limit)
+    log("host pool ready in %.1f s (%s)" % (pool.draw_seconds, "wrapped" if pool.wrapped else "full"))
+    items, keep = hz.pinned_adapter(wl, 0)
+    T = hz.DeviceTemplate(wl.shapes, max_adapter_bytes=hz.packed_adapter_bytes(wl), flags=tb.TIDAL_FLAG_KERNEL_TIMING)
+    out = {"config": wl.name, "source_GB": round(wl.source_bytes / 1e9, 3), "host_pool": "wrapped into %.1f GiB" % (pool_limit / 2**30) if pool.wrapped else "full"}
+    try:
+        probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        peak = tb.tidal_h2d_peak(probe, 1 << 30, 3, T.copy_stream)
+        del probe
+        srcs = pool.sources()
+        mat, att, det = [], [], []
+        tg = tb.targets_from_arrays(items)
+        for rep in range(args.reps + 1):
+            e = [ev() for _ in range(4)]
+            tb.tidal_reset_stats(T.h)
+            e[0].record(T.compute_stream)
+            tb.tidal_materialize(T.h, srcs, T.copy_stream, T.compute_stream)
+            e[1].record(T.compute_stream)
+            tb.tidal_lora_attach(T.h, tg, T.compute_stream)
+            e[2].record(T.compute_stream)
+            T.sync()
+            st = tb.tidal_get_stats(T.h)
+            if rep > 0 or args.reps == 0:
+                mat.append(e[0].elapsed_time(e[1]))
+                att.append((e[1].elapsed_time(e[2]), st["lora_kernel_ms"], st["lora_launches"]))
+            log("rep %d: materialize %.1f ms, attach %.2f ms (kernels %.3f ms in %d launches)" %
+                (rep, e[0].elapsed_time(e[1]), e[1].elapsed_time(e[2]), st["lora_kernel_ms"], st["lora_launches"]))
+        mat_ms = float(np.median(mat))
+        att_ms = float(np.median([a[0] for a in att]))
+        k_ms = float(np.median([a[1] for a in att]))
+        b = lora_bytes(wl, 0, wl.rank)
+        out.update({
+            "materialize_ms": round(mat_ms, 2), "materialize_GBps": round(wl.source_bytes / mat_ms / 1e6, 2),
+            "h2d_peak_measured": round(peak, 2), "frac_of_measured_peak": round(wl.source_bytes / mat_ms / 1e6 / peak, 4),
+            "attach_ms_per_invocation": round(att_ms, 3), "attach_kernel_ms": round(k_ms, 4),
+            "attach_launches": att[-1][2], "lora_algorithmic_GB": round(b / 1e9, 3),
+            "lora_kernel_GBps": round(b / k_ms / 1e6, 1), "frac_of_hbm_peak": round(b / k_ms / 1e6 / HBM_PEAK, 4)})
+    finally:
+        T.close()
+    return out
+
+
+def bench_churn(args):
+    """Configuration 4: resident 7B-shaped bf16 base, pool of 32 resident adapters (ranks from
+    {8,16,32,64}, alpha = 2r, targets q,k,v,o), 200 invocations by Zipf(1.1): step 0 attaches,
+    every later step is one fused swap."""
+    ch = wl_mod.adapter_churn()
+    wl = ch.base
+    # the base's values do not matter for timing: stream it from a wrapped pool
+    pool = hz.HostPool(wl, limit_bytes=2 << 30)
+    T = hz.DeviceTemplate(wl.shapes, flags=tb.TIDAL_FLAG_KERNEL_TIMING)
+    out = {"config": "adapter_churn_llama2_7b_shaped", "pool": len(ch.ranks), "steps": len(ch.schedule)}
+    try:
+        tb.tidal_materialize(T.h, pool.sources(), T.copy_stream, T.compute_stream)
+        T.sync()
+        handles, mems = [], []
+        t0 = time.perf_counter()
+        for a, r in enumerate(ch.ranks):
+            items, keep = hz.pinned_adapter(wl, a, rank=r, alpha=ch.alphas[a])
+            tg = tb.targets_from_arrays(items)
+            nb = tb.tidal_adapter_required_bytes(T.h, tg)
+            mem = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+            handles.append(tb.tidal_adapter_upload(T.h, tg, mem, nb, T.compute_stream))
+            mems.append(mem)
+            T.sync()
+        log("uploaded %d adapters (%.2f GB packed) in %.1f s" % (len(handles), sum(m.numel() for m in mems) / 1e9, time.perf_counter() - t0))
+        per_step = []
+        cur = None
+        for step, a in enumerate(ch.schedule):
+            tb.tidal_reset_stats(T.h)
+            e0, e1 = ev(), ev()
+            e0.record(T.compute_stream)
+            if step == 0:
+                tb.tidal_lora_attach_adapter(T.h, handles[a], T.compute_stream)
+            else:
+                tb.tidal_lora_swap_adapter(T.h, handles[a], T.compute_stream)
+            e1.record(T.compute_stream)
+            T.sync()
+            st = tb.tidal_get_stats(T.h)
+            r_old = ch.ranks[cur] if cur is not None else 0
+            per_step.append((r_old, ch.ranks[a], e0.elapsed_time(e1), st["lora_kernel_ms"], a == cur))
+            cur = a
+        swaps = per_step[1:]
+        call = np.array([s[2] for s in swaps])
+        kern = np.array([s[3] for s in swaps])
+        by = {}
+        for r0, r1, c, k, same in swaps:
+            by.setdefault((r0, r1), []).append(k)
+        byte_of = lambda r0, r1: lora_bytes(wl, r0, r1)
+        total_bytes = sum(byte_of(r0, r1) for r0, r1, *_ in swaps)
+        out.update({
+            "swap_ms_per_invocation": {"mean": round(float(call.mean()), 4), "p50": round(float(np.median(call)), 4),
+                                       "p95": round(float(np.percentile(call, 95)), 4)},
+            "swap_kernel_ms": {"mean": round(float(kern.mean()), 4), "p50": round(float(np.median(kern)), 4),
+                               "p95": round(float(np.percentile(kern, 95)), 4)},
+            "swap_GBps_overall": round(total_bytes / kern.sum() / 1e6, 1),
+            "frac_of_hbm_peak": round(total_bytes / kern.sum() / 1e6 / HBM_PEAK, 4),
+            "first_attach_ms": round(per_step[0][2], 4),
+            "repeats_of_attached_adapter": int(sum(1 for s in swaps if s[4])),
+            "by_rank_pair_GBps": {"%d->%d" % k: round(byte_of(*k) / float(np.median(v)) / 1e6, 0) for k, v in sorted(by.items())},
+            "by_rank_pair_count": {"%d->%d" % k: len(v) for k, v in sorted(by.items())}})
+        tb.tidal_lora_detach(T.h, T.compute_stream)
+        T.sync()
+        for h in handles:
+            tb.tidal_adapter_destroy(h)
+    finally:
+        T.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b"])
+    ap.add_argument("--reps", type=int, default=2)
+    ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
+    args = ap.parse_args()
+    assert torch.cuda.is_available(), "needs a GPU (there is no CPU path)"
+    torch.cuda.set_device(0)
+    if args.config == "single":
+        out = bench_single(args)
+    elif args.config == "13b":
+        out = bench_stack(args, wl_mod.llama2_13b(), int(args.pool_gib * 2**30) if args.pool_gib else None)
+    elif args.config == "70b":
+        out = bench_stack(args, wl_mod.llama3_70b(), int((args.pool_gib or 24.0) * 2**30))
+    else:
+        out = bench_churn(args)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -198,8 +198,7 @@ __device__ __forceinline__ void store_block(uint16_t* __restrict__ W, int out, i
 }
 
 template <int NT, int KS0, int KS1>
-__global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __restrict__ table,
-                                                        int out, int in, int strips, int rowblocks,
+__global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraBatch batch, int out, int in, int strips, int rowblocks,
                                                         int rc, int blocks_per_target, int total_blocks) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -217,13 +216,17 @@ __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __r
     const int strip = item - rowchunk * strips;
     const int j0 = strip * (32 * NT);
 
-    const LoraTargetDev d = table[target];
-    uint16_t* __restrict__ W = d.W;
+    const LoraTargetDev d = batch.t[target];
+    uint16_t* __restrict__ W = (uint16_t*)(batch.w_base + (size_t)d.w * kLoraUnit);
+    const uint16_t* At_old = (const uint16_t*)(batch.old_base + (size_t)d.at_old * kLoraUnit);
+    const uint16_t* Bp_old = (const uint16_t*)(batch.old_base + (size_t)d.bp_old * kLoraUnit);
+    const uint16_t* At_new = (const uint16_t*)(batch.new_base + (size_t)d.at_new * kLoraUnit);
+    const uint16_t* Bp_new = (const uint16_t*)(batch.new_base + (size_t)d.bp_new * kLoraUnit);
 
     bf16x8 bop0[NT][KS0 ? KS0 : 1];
     bf16x8 bop1[NT][KS1 ? KS1 : 1];
-    load_strip<NT, KS0>(d.At_old, in, j0, lane, bop0);
-    load_strip<NT, KS1>(d.At_new, in, j0, lane, bop1);
+    load_strip<NT, KS0>(At_old, in, j0, lane, bop0);
+    load_strip<NT, KS1>(At_new, in, j0, lane, bop1);
 
     const int n = lane & 31, h = lane >> 5;
     const int jl = j0 + NT * n;                              // lane's first column
@@ -240,11 +243,11 @@ __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraTargetDev* __r
         load_block<NT>(W, out, in, i0, jl, h, full, w);
         f32x16 acc[NT];
         if constexpr (KS0 > 0) {
-            delta_tile<NT, KS0>(d.Bp_old, out, i0, lane, bop0, acc);
+            delta_tile<NT, KS0>(Bp_old, out, i0, lane, bop0, acc);
             apply_tile<NT>(w, acc, d.s_old);
         }
         if constexpr (KS1 > 0) {
-            delta_tile<NT, KS1>(d.Bp_new, out, i0, lane, bop1, acc);
+            delta_tile<NT, KS1>(Bp_new, out, i0, lane, bop1, acc);
             apply_tile<NT>(w, acc, d.s_new);
         }
         store_block<NT>(W, out, in, i0, jl, h, full, w);
@@ -289,7 +292,7 @@ __device__ __forceinline__ void stage_strip(const uint16_t* __restrict__ At, int
 }
 
 template <int NT, int KS0, int KS1>
-__global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraTargetDev* __restrict__ table, int out,
+__global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraBatch batch, int out,
                                                             int in, int strips, int rowblocks, int rcb,
                                                             int blocks_per_target, int total_blocks) {
     __shared__ bf16x8 strip_lds[(KS0 + KS1) * NT * 64];
@@ -304,10 +307,14 @@ __global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraTargetDev*
     const int strip = item - rowchunk * strips;
     const int j0 = strip * (32 * NT);
 
-    const LoraTargetDev d = table[target];
-    uint16_t* __restrict__ W = d.W;
-    if constexpr (KS0 > 0) stage_strip<NT, KS0>(d.At_old, in, j0, lane, wave, strip_lds);
-    if constexpr (KS1 > 0) stage_strip<NT, KS1>(d.At_new, in, j0, lane, wave, strip_lds + KS0 * NT * 64);
+    const LoraTargetDev d = batch.t[target];
+    uint16_t* __restrict__ W = (uint16_t*)(batch.w_base + (size_t)d.w * kLoraUnit);
+    const uint16_t* At_old = (const uint16_t*)(batch.old_base + (size_t)d.at_old * kLoraUnit);
+    const uint16_t* Bp_old = (const uint16_t*)(batch.old_base + (size_t)d.bp_old * kLoraUnit);
+    const uint16_t* At_new = (const uint16_t*)(batch.new_base + (size_t)d.at_new * kLoraUnit);
+    const uint16_t* Bp_new = (const uint16_t*)(batch.new_base + (size_t)d.bp_new * kLoraUnit);
+    if constexpr (KS0 > 0) stage_strip<NT, KS0>(At_old, in, j0, lane, wave, strip_lds);
+    if constexpr (KS1 > 0) stage_strip<NT, KS1>(At_new, in, j0, lane, wave, strip_lds + KS0 * NT * 64);
     __syncthreads();
 
     const int n = lane & 31, h = lane >> 5;
@@ -321,11 +328,11 @@ __global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraTargetDev*
         load_block<NT>(W, out, in, i0, jl, h, full, w);
         f32x16 acc[NT];
         if constexpr (KS0 > 0) {
-            delta_tile_lds<NT, KS0>(d.Bp_old, out, i0, lane, strip_lds, acc);
+            delta_tile_lds<NT, KS0>(Bp_old, out, i0, lane, strip_lds, acc);
             apply_tile<NT>(w, acc, d.s_old);
         }
         if constexpr (KS1 > 0) {
-            delta_tile_lds<NT, KS1>(d.Bp_new, out, i0, lane, strip_lds + KS0 * NT * 64, acc);
+            delta_tile_lds<NT, KS1>(Bp_new, out, i0, lane, strip_lds + KS0 * NT * 64, acc);
             apply_tile<NT>(w, acc, d.s_new);
         }
         store_block<NT>(W, out, in, i0, jl, h, full, w);
@@ -337,8 +344,9 @@ static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
     const int strips = (g.in + 32 * NT - 1) / (32 * NT);
     const int rowblocks = (g.out + 31) / 32;
     const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
-    int rc = (int)(tiles / 8192);                    // 32-row blocks per wave
-    rc = rc < 1 ? 1 : (rc > 32 ? 32 : rc);
+    int rc = 16;                                     // 32-row blocks per wave
+    const int64_t by_size = tiles / 4096;
+    if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
     if (const char* e = getenv("TIDAL_MFMA_RC")) {   // tuning runs only
         const int v = atoi(e);
         if (v >= 1 && v <= 1024) rc = v;
@@ -349,7 +357,7 @@ static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
     const int64_t total = (int64_t)blocks_per_target * g.n_targets;
     if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((lora_mfma_lds_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, g.table, g.out,
+    hipLaunchKernelGGL((lora_mfma_lds_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
                        g.in, strips, rowblocks, rcb, blocks_per_target, (int)total);
     return hipGetLastError();
 }
@@ -358,11 +366,14 @@ template <int NT, int KS0, int KS1>
 static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int strips = (g.in + 32 * NT - 1) / (32 * NT);
     const int rowblocks = (g.out + 31) / 32;
-    // Rows per wave: long walks amortise the A strip, but small jobs need every CU busy.
+    // 32-row blocks per wave.  Short walks keep waves short-lived, which this memory system
+    // rewards (about 4 blocks at r <= 16), long walks amortise the A strip, which grows with the
+    // rank (about 16 blocks at 64 ranks); small jobs get fewer so that every CU has work.
     const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
-    const int rc_max = (KS0 + KS1 >= 4) ? 32 : 16;
-    int rc = (int)(tiles / 8192);
-    rc = rc < 1 ? 1 : (rc > rc_max ? rc_max : rc);
+    int rc = 4 * (KS0 + KS1);
+    rc = rc < 4 ? 4 : (rc > 16 ? 16 : rc);
+    const int64_t by_size = tiles / 4096;
+    if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
     if (const char* e = getenv("TIDAL_MFMA_RC")) {        // tuning runs only
         const int v = atoi(e);
         if (v >= 1 && v <= 1024) rc = v;
@@ -372,7 +383,7 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int64_t total = (int64_t)blocks_per_target * g.n_targets;
     if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, g.table, g.out,
+    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
                        g.in, strips, rowblocks, rc, blocks_per_target, (int)total);
     return hipGetLastError();
 }
@@ -500,7 +511,7 @@ __device__ __forceinline__ void ordered_phase(const uint16_t* __restrict__ At, c
         for (int p = 0; p < 4; ++p) w[rr][p] = rmw2(w[rr][p], acc[rr][2 * p], acc[rr][2 * p + 1], s);
 }
 
-__global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraTargetDev* __restrict__ table, int out,
+__global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraBatch batch, int out,
                                                            int in, int r_old, int rp_old, int r_new,
                                                            int rp_new, int col_tiles, int tiles_per_target) {
     __shared__ __attribute__((aligned(16))) float Atile[kOrdK * kOrdCols];
@@ -509,8 +520,12 @@ __global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraTargetDev* 
     const int tile = blockIdx.x - target * tiles_per_target;
     const int i0 = (tile / col_tiles) * kOrdRows;
     const int j0 = (tile % col_tiles) * kOrdCols;
-    const LoraTargetDev d = table[target];
-    uint16_t* __restrict__ W = d.W;
+    const LoraTargetDev d = batch.t[target];
+    uint16_t* __restrict__ W = (uint16_t*)(batch.w_base + (size_t)d.w * kLoraUnit);
+    const uint16_t* At_old = (const uint16_t*)(batch.old_base + (size_t)d.at_old * kLoraUnit);
+    const uint16_t* Bp_old = (const uint16_t*)(batch.old_base + (size_t)d.bp_old * kLoraUnit);
+    const uint16_t* At_new = (const uint16_t*)(batch.new_base + (size_t)d.at_new * kLoraUnit);
+    const uint16_t* Bp_new = (const uint16_t*)(batch.new_base + (size_t)d.bp_new * kLoraUnit);
     const int cg = threadIdx.x & 31, rg = threadIdx.x >> 5;
     const int jl = j0 + 8 * cg;
     const bool vec_ok = (in % 8 == 0) && (jl + 8 <= in);
@@ -532,8 +547,8 @@ __global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraTargetDev* 
             }
         }
     }
-    if (rp_old > 0) ordered_phase(d.At_old, d.Bp_old, r_old, rp_old, d.s_old, out, in, i0, j0, Atile, Btile, w);
-    if (rp_new > 0) ordered_phase(d.At_new, d.Bp_new, r_new, rp_new, d.s_new, out, in, i0, j0, Atile, Btile, w);
+    if (rp_old > 0) ordered_phase(At_old, Bp_old, r_old, rp_old, d.s_old, out, in, i0, j0, Atile, Btile, w);
+    if (rp_new > 0) ordered_phase(At_new, Bp_new, r_new, rp_new, d.s_new, out, in, i0, j0, Atile, Btile, w);
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr) {
         const int row = i0 + 8 * rg + rr;
@@ -559,7 +574,7 @@ hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream) {
     const int64_t tiles_per_target = (int64_t)col_tiles * row_tiles;
     const int64_t total = tiles_per_target * g.n_targets;
     if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(lora_ordered_kernel, dim3((unsigned)total), dim3(256), 0, stream, g.table, g.out, g.in,
+    hipLaunchKernelGGL(lora_ordered_kernel, dim3((unsigned)total), dim3(256), 0, stream, *g.batch, g.out, g.in,
                        g.r_old, g.rp_old, g.r_new, g.rp_new, col_tiles, (int)tiles_per_target);
     return hipGetLastError();
 }

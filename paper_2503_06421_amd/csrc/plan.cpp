@@ -50,8 +50,6 @@ bool layout_arena(const tidal_slot_desc* slots, int32_t n, const tidal_config& c
     out->adapter_region[0] = off;
     out->adapter_region[1] = off + cfg.max_adapter_bytes;
     off += 2 * cfg.max_adapter_bytes;
-    out->desc = off;
-    off += kDescBytes;
     out->total = off;
     return true;
 }

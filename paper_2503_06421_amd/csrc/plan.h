@@ -13,7 +13,6 @@
 namespace tidal {
 
 constexpr size_t kSlotAlign = 256;        // every slot, staging piece and packed factor starts on this
-constexpr size_t kDescBytes = 128 << 10;  // launch-descriptor area at the end of the arena
 constexpr int64_t kSplitElems = 128;      // tensors are split between chunks at multiples of this
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -24,7 +23,6 @@ struct ArenaLayout {
     std::vector<size_t> slot_offset;   // n + 1 entries; last = size of the slot area
     size_t staging[2];
     size_t adapter_region[2];
-    size_t desc;
     size_t total;
 };
 

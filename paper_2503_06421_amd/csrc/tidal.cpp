@@ -64,8 +64,6 @@ struct SlotState {
     bool ready_recorded = false;
 };
 
-constexpr int kDescRing = 4;
-
 }  // namespace
 
 struct tidal_adapter {
@@ -91,10 +89,6 @@ struct tidal_template {
     char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
     bool bounce_used[2] = {false, false};
     bool staging_rec[2] = {false, false};
-    char* desc_host = nullptr;                         // pinned host, kDescRing * kDescBytes
-    hipEvent_t desc_free[kDescRing] = {};
-    bool desc_rec[kDescRing] = {};
-    int desc_next = 0;
 
     // attach state
     bool attached = false;
@@ -131,8 +125,6 @@ static int ensure_device(tidal_template* t) {
     HIP_TRY(hipEventCreateWithFlags(&t->ev_copy_done, flags));
     HIP_TRY(hipEventCreateWithFlags(&t->ev_last_compute, flags));
     HIP_TRY(hipEventCreateWithFlags(&t->ev_last_lora, flags));
-    for (int i = 0; i < kDescRing; ++i) HIP_TRY(hipEventCreateWithFlags(&t->desc_free[i], flags));
-    HIP_TRY(hipHostMalloc((void**)&t->desc_host, kDescRing * kDescBytes, hipHostMallocDefault));
     t->dev_ready = true;
     return TIDAL_OK;
 }
@@ -702,18 +694,18 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
         const Side& n = kv.second.second;
         LoraTargetDev d;
         memset(&d, 0, sizeof d);
-        d.W = (uint16_t*)slot_ptr(t, kv.first);
+        d.w = (uint32_t)(t->lay.slot_offset[kv.first] / kLoraUnit);
         int rp_old = 0, rp_new = 0, r_old = 0, r_new = 0;
         if (o.p) {
-            d.At_old = (const uint16_t*)(o.rec->dev + o.p->at_off);
-            d.Bp_old = (const uint16_t*)(o.rec->dev + o.p->bp_off);
+            d.at_old = (uint32_t)(o.p->at_off / kLoraUnit);
+            d.bp_old = (uint32_t)(o.p->bp_off / kLoraUnit);
             d.s_old = -(o.p->alpha / (float)o.p->r);
             rp_old = o.p->rp;
             r_old = o.p->r;
         }
         if (n.p) {
-            d.At_new = (const uint16_t*)(n.rec->dev + n.p->at_off);
-            d.Bp_new = (const uint16_t*)(n.rec->dev + n.p->bp_off);
+            d.at_new = (uint32_t)(n.p->at_off / kLoraUnit);
+            d.bp_new = (uint32_t)(n.p->bp_off / kLoraUnit);
             d.s_new = n.p->alpha / (float)n.p->r;
             rp_new = n.p->rp;
             r_new = n.p->r;
@@ -721,46 +713,33 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
         groups[Key(s.rows, s.cols, rp_old, rp_new, r_old, r_new)].push_back(d);
         t->stats.rmw_elems += (uint64_t)s.elems;
     }
-    size_t total = 0;
-    for (auto& g : groups) total += g.second.size();
-    if (total * sizeof(LoraTargetDev) > kDescBytes)
-        return fail(TIDAL_E_INVAL, "too many LoRA targets in one call (%zu)", total);
-
-    // descriptor table: pinned host ring -> descriptor area of the arena, on the caller's stream
-    const int ring = t->desc_next;
-    t->desc_next = (ring + 1) % kDescRing;
-    if (t->desc_rec[ring]) HIP_TRY(hipEventSynchronize(t->desc_free[ring]));
-    LoraTargetDev* host_tab = (LoraTargetDev*)(t->desc_host + (size_t)ring * kDescBytes);
-    LoraTargetDev* dev_tab = (LoraTargetDev*)(t->arena + t->lay.desc);
-    size_t at = 0;
-    for (auto& g : groups) {
-        memcpy(host_tab + at, g.second.data(), g.second.size() * sizeof(LoraTargetDev));
-        at += g.second.size();
-    }
-    HIP_TRY(hipMemcpyAsync(dev_tab, host_tab, total * sizeof(LoraTargetDev), hipMemcpyHostToDevice, stream));
-    HIP_TRY(hipEventRecord(t->desc_free[ring], stream));
-    t->desc_rec[ring] = true;
-
     const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
-    at = 0;
     for (auto& g : groups) {
-        LoraGroup lg;
-        lg.table = dev_tab + at;
-        lg.n_targets = (int32_t)g.second.size();
-        lg.out = (int32_t)std::get<0>(g.first);
-        lg.in = (int32_t)std::get<1>(g.first);
-        lg.rp_old = std::get<2>(g.first);
-        lg.rp_new = std::get<3>(g.first);
-        lg.r_old = std::get<4>(g.first);
-        lg.r_new = std::get<5>(g.first);
-        hipEvent_t t0;
-        int trc = timing_begin(t, stream, &t0);
-        if (trc) return trc;
-        HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, stream));
-        trc = timing_end(t, stream, t0, true);
-        if (trc) return trc;
-        t->stats.lora_launches++;
-        at += g.second.size();
+        const std::vector<LoraTargetDev>& all = g.second;
+        for (size_t at = 0; at < all.size(); at += kMaxLoraTargets) {
+            const size_t n = std::min(all.size() - at, (size_t)kMaxLoraTargets);
+            LoraBatch batch;
+            batch.w_base = t->arena;
+            batch.old_base = older ? older->dev : nullptr;
+            batch.new_base = newer ? newer->dev : nullptr;
+            memcpy(batch.t, all.data() + at, n * sizeof(LoraTargetDev));
+            LoraGroup lg;
+            lg.batch = &batch;
+            lg.n_targets = (int32_t)n;
+            lg.out = (int32_t)std::get<0>(g.first);
+            lg.in = (int32_t)std::get<1>(g.first);
+            lg.rp_old = std::get<2>(g.first);
+            lg.rp_new = std::get<3>(g.first);
+            lg.r_old = std::get<4>(g.first);
+            lg.r_new = std::get<5>(g.first);
+            hipEvent_t t0;
+            int trc = timing_begin(t, stream, &t0);
+            if (trc) return trc;
+            HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, stream));
+            trc = timing_end(t, stream, t0, true);
+            if (trc) return trc;
+            t->stats.lora_launches++;
+        }
     }
     HIP_TRY(hipEventRecord(t->ev_last_lora, stream));
     t->last_lora_rec = true;
@@ -941,8 +920,6 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
         (void)hipEventDestroy(t->ev_copy_done);
         (void)hipEventDestroy(t->ev_last_compute);
         (void)hipEventDestroy(t->ev_last_lora);
-        for (int i = 0; i < kDescRing; ++i) (void)hipEventDestroy(t->desc_free[i]);
-        if (t->desc_host) (void)hipHostFree(t->desc_host);
         for (SlotState& s : t->slots)
             if (s.ready) (void)hipEventDestroy(s.ready);
         (void)timing_drain(t);

@@ -36,21 +36,30 @@ struct PackBatch { PackSegment seg[kMaxPackSeg]; };
 hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream);
 
 // ---- LoRA read-modify-write ---------------------------------------------------------------
-// One entry per targeted slot of a launch group.  All slots of a group share out, in and the
-// padded ranks of the old and new adapter.  A side that is absent has a null At/Bp.
+// One entry per targeted slot of a launch.  All slots of a launch share out, in and the padded
+// ranks of the old and new adapter.  Addresses are 256-byte units relative to three bases (the
+// arena and the memory of the two adapters), which keeps an entry at 28 bytes so that 128 of them
+// travel in the kernel arguments: no table in device memory, no copy before the launch.  Larger
+// groups are split; every launch still covers tens of millions of elements.
 struct LoraTargetDev {
-    uint16_t* W;             // out x in bf16
-    const uint16_t* At_old;  // in x rp_old bf16 (A transposed, zero padded)
-    const uint16_t* Bp_old;  // out x rp_old bf16
-    const uint16_t* At_new;
-    const uint16_t* Bp_new;
+    uint32_t w;              // slot: out x in bf16, relative to w_base
+    uint32_t at_old, bp_old; // in x rp_old (A transposed, zero padded) and out x rp_old, rel. to old_base
+    uint32_t at_new, bp_new; // same for the new adapter, relative to new_base
     float s_old;             // already negated: W - (alpha/r) * delta_old
     float s_new;
 };
+constexpr int kMaxLoraTargets = 128;
+constexpr size_t kLoraUnit = 256;
+struct LoraBatch {
+    char* w_base;
+    const char* old_base;
+    const char* new_base;
+    LoraTargetDev t[kMaxLoraTargets];     // 3584 bytes
+};
 
 struct LoraGroup {
-    const LoraTargetDev* table;  // device
-    int32_t n_targets;
+    const LoraBatch* batch;      // host; copied into the kernel arguments at launch
+    int32_t n_targets;           // <= kMaxLoraTargets
     int32_t out, in;
     int32_t r_old, r_new;        // true ranks (ordered-accumulation kernel)
     int32_t rp_old, rp_new;      // padded ranks: 0, 16, 32 or 64

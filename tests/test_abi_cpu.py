@@ -48,7 +48,7 @@ def test_required_bytes_and_slot_offsets(orc):
     cfg = tb.make_config(chunk_bytes=1 << 20, max_adapter_bytes=1000)
     need = tb.tidal_template_required_bytes(shapes, cfg)
     off = orc.layout(shapes)
-    assert need == int(off[-1]) + 2 * (1 << 20) + 2 * 1024 + (128 << 10)
+    assert need == int(off[-1]) + 2 * (1 << 20) + 2 * 1024
     t = tb.tidal_template_create(shapes, FAKE_ARENA, need, cfg)
     try:
         for i, (r, c) in enumerate(shapes):
