@@ -1,0 +1,89 @@
+"""GPU parity on the true matrix shapes of the larger configurations, with fewer layers so that
+the host holds them: 13B-shaped layers (hidden 5120, FFN 13824, fp16 host, r = 64 on all seven
+projections: three launch groups, row pitches that are not powers of two) and a 70B-shaped layer
+(hidden 8192, FFN 28672, grouped-query k/v 1024 x 8192, bf16 host copied straight into the slots,
+r = 16).  Conversion/placement: every slot bit for bit.  LoRA: 64-row bands of every targeted slot
+recomputed by the oracle from the GPU's previous state, within 2^-7 * max|W|; untargeted slots
+untouched."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2503_06421_amd import binding as tb            # noqa: E402
+from paper_2503_06421_amd import harness as hz            # noqa: E402
+from paper_2503_06421_amd import workloads as wl_mod      # noqa: E402
+
+
+def f32(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def bands_of(rows):
+    mid = (rows // 2 // 7) * 7 + 3                    # a start that is not a multiple of 32
+    return [(0, min(64, rows)), (mid, min(mid + 64, rows)), (max(rows - 64, 0), rows)]
+
+
+def run_stack(orc, wl):
+    pool = hz.HostPool(wl)
+    ads = [hz.pinned_adapter(wl, a)[0] for a in (0, 1)]
+    T = hz.DeviceTemplate(wl.shapes, max_adapter_bytes=hz.packed_adapter_bytes(wl))
+    try:
+        tb.tidal_materialize(T.h, pool.sources(), T.copy_stream, T.compute_stream)
+        T.sync()
+        for i, v in enumerate(pool.views):
+            assert np.array_equal(T.slot_host(i), orc.convert_to_bf16(v)), wl.tensors[i].name
+        pristine = {i: T.slot_bytes(i).clone() for i in range(len(wl.shapes)) if i not in set(wl.lora_slots)}
+
+        def rows_of(s, b):
+            cols = wl.tensors[s].cols
+            return T.slot_bytes(s)[2 * b[0] * cols: 2 * b[1] * cols].cpu().numpy().view(np.uint16).reshape(b[1] - b[0], cols)
+
+        prev = {(s, b): rows_of(s, b) for s in wl.lora_slots for b in bands_of(wl.tensors[s].rows)}
+
+        def check(tag, old, new):
+            for idx, s in enumerate(wl.lora_slots):
+                for b in bands_of(wl.tensors[s].rows):
+                    want = prev[(s, b)].copy()
+                    if old is not None:
+                        _, al, A, B = old[idx]
+                        orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B[b[0]:b[1]]), al, -1)
+                    _, al, A, B = new[idx]
+                    orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B[b[0]:b[1]]), al, +1)
+                    got = rows_of(s, b)
+                    g, w = f32(got), f32(want)
+                    assert np.max(np.abs(g - w)) <= 2.0 ** -7 * np.max(np.abs(w)), (tag, wl.tensors[s].name, b)
+                    assert np.mean(got != want) < 2e-3, (tag, wl.tensors[s].name, b)
+                    assert np.any(got != prev[(s, b)])
+                    prev[(s, b)] = got
+            for i, p in pristine.items():
+                assert torch.equal(T.slot_bytes(i), p), "untargeted slot %d changed" % i
+
+        tb.tidal_lora_attach(T.h, tb.targets_from_arrays(ads[0]), T.compute_stream)
+        T.sync()
+        check("attach", None, ads[0])
+        tb.tidal_lora_swap(T.h, tb.targets_from_arrays(ads[1]), T.compute_stream)
+        T.sync()
+        check("swap", ads[0], ads[1])
+        tb.tidal_lora_detach(T.h, T.compute_stream)
+        T.sync()
+        return tb.tidal_get_stats(T.h)
+    finally:
+        T.close()
+
+
+def test_13b_shaped_layers_rank64_all_projections(orc):
+    wl = wl_mod.llama2_13b(layers=2)
+    st = run_stack(orc, wl)
+    assert st["lora_launches"] == 3 * 3          # three shape groups per pass, three passes
+
+
+def test_70b_shaped_layer_bf16_direct_gqa(orc):
+    wl = wl_mod.llama3_70b(layers=1)
+    wl.tensors[0] = wl_mod.TensorSpec("embed", 4096, 8192)           # the 128256-row tables add nothing here
+    wl.tensors[-1] = wl_mod.TensorSpec("lm_head", 4096, 8192)
+    st = run_stack(orc, wl)
+    assert st["converted_elems"] == 0                                   # bf16 sources: DMA straight into slots
+    assert st["lora_launches"] == 4 * 3          # q/o, k/v, gate/up, down
