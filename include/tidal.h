@@ -212,6 +212,26 @@ int tidal_template_slot_ptr(const tidal_template* t, int32_t slot, void** dev_pt
  * materialised gives TIDAL_E_STATE. */
 int tidal_template_slot_wait(tidal_template* t, int32_t slot, void* stream);
 
+/* Template size rule, Eq. 1 of Sec. 5.2:  M_prefetch = max(M_model - T_TTFT * B_PCIe, 0): the
+ * bytes that must already be resident so that streaming the rest hides under an inference of
+ * duration T_TTFT.  Pure arithmetic, host-only; negative or non-finite inputs give 0. */
+size_t tidal_prefetch_bytes(size_t model_bytes, double ttft_seconds, double link_bytes_per_second);
+
+/* How many leading slots (in slot = access order, Sec. 4.2) fit into prefetch_bytes: the part
+ * of the template to keep resident; the rest stays "memory layout only" until it is streamed in
+ * by tidal_materialize at invocation time.  Host-only. */
+int tidal_template_resident_prefix(const tidal_template* t, size_t prefetch_bytes,
+                                   int32_t* n_slots /* [host] out */, size_t* bytes /* [host] out, may be NULL */);
+
+/* Stand-in consumer for an inference kernel that reads a weight: adds to *dev_sum the sum of the
+ * slot's bf16 bit patterns (as unsigned 16-bit integers, wrapping in 64 bits), reading the slot
+ * `passes` times (passes >= 1 scales its duration; the sum grows by the same amount each pass).
+ * Bandwidth-bound, enqueued on `stream`; with TIDAL_FLAG_SLOT_EVENTS it first makes `stream` wait
+ * for the slot's materialisation (the injected synchronisation of Sec. 5.2).  The caller zeroes
+ * *dev_sum. */
+int tidal_slot_checksum(tidal_template* t, int32_t slot, int32_t passes, void* stream,
+                        uint64_t* dev_sum /* [device] 8-byte aligned */);
+
 /* Standalone conversion of n device-resident elements of `dtype` to bf16 (the kernel
  * tidal_materialize runs on each staged chunk).  src and dst 16-byte aligned, not
  * overlapping. */

@@ -194,3 +194,32 @@ void orc_lora_swap_bf16(uint16_t* W, int64_t out, int64_t in,
     orc_lora_merge_bf16(W, out, in, A_old, B_old, r_old, alpha_old, -1, 1);
     orc_lora_merge_bf16(W, out, in, A_new, B_new, r_new, alpha_new, +1, 1);
 }
+
+/* ---------------------------------------------------------------------------
+ * Template size rule, Eq. 1 of Sec. 5.2:  M_prefetch = max(M_model - T_TTFT * B_PCIe, 0),
+ * in bytes (rounded up to a whole byte).
+ * ------------------------------------------------------------------------- */
+uint64_t orc_prefetch_bytes(uint64_t model_bytes, double ttft_seconds, double link_bytes_per_second) {
+    double m = (double)model_bytes - ttft_seconds * link_bytes_per_second;
+    if (!(m > 0.0)) return 0;
+    return (uint64_t)ceil(m);
+}
+
+/* Number of leading slots (access order, Sec. 4.2) needed to hold prefetch_bytes. */
+int32_t orc_resident_prefix(const int64_t* rows, const int64_t* cols, int32_t n, uint64_t prefetch_bytes) {
+    uint64_t sum = 0;
+    int32_t k = 0;
+    while (k < n && sum < prefetch_bytes) {
+        sum += 2u * (uint64_t)(rows[k] * cols[k]);
+        ++k;
+    }
+    return k;
+}
+
+/* Stand-in consumer: sum of a slot's bf16 bit patterns as integers, `passes` times, mod 2^64. */
+uint64_t orc_slot_checksum(const uint16_t* slot, int64_t elems, int32_t passes) {
+    uint64_t s = 0;
+    int64_t i;
+    for (i = 0; i < elems; ++i) s += slot[i];
+    return s * (uint64_t)passes;
+}

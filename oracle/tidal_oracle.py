@@ -55,6 +55,12 @@ def lib() -> ctypes.CDLL:
         L.orc_lora_merge_f32.argtypes = [vp, i64, i64, vp, vp, i32, f32, ctypes.c_int, ctypes.c_int]
         L.orc_lora_swap_bf16.restype = None
         L.orc_lora_swap_bf16.argtypes = [vp, i64, i64, vp, vp, i32, f32, vp, vp, i32, f32]
+        L.orc_prefetch_bytes.restype = ctypes.c_uint64
+        L.orc_prefetch_bytes.argtypes = [ctypes.c_uint64, ctypes.c_double, ctypes.c_double]
+        L.orc_resident_prefix.restype = i32
+        L.orc_resident_prefix.argtypes = [vp, vp, i32, ctypes.c_uint64]
+        L.orc_slot_checksum.restype = ctypes.c_uint64
+        L.orc_slot_checksum.argtypes = [vp, i64, i32]
         _lib = L
     return _lib
 
@@ -161,3 +167,18 @@ def lora_swap(W: np.ndarray, A_old, B_old, alpha_old, A_new, B_new, alpha_new) -
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     """Exact widening of bf16 bit patterns to float32 values (a reinterpretation, no arithmetic)."""
     return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+def prefetch_bytes(model_bytes: int, ttft_seconds: float, link_bytes_per_second: float) -> int:
+    return lib().orc_prefetch_bytes(model_bytes, ttft_seconds, link_bytes_per_second)
+
+
+def resident_prefix(shapes, prefetch: int) -> int:
+    rows = np.array([s[0] for s in shapes], dtype=np.int64)
+    cols = np.array([s[1] for s in shapes], dtype=np.int64)
+    return lib().orc_resident_prefix(_ptr(rows), _ptr(cols), len(shapes), prefetch)
+
+
+def slot_checksum(bits: np.ndarray, passes: int = 1) -> int:
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    return lib().orc_slot_checksum(_ptr(bits), bits.size, passes)

@@ -1,7 +1,7 @@
 """Measurements of the other workload configurations (bench.py at the repository root times the
 Llama2-7B-shaped headline workload).
 
-    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b
+    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap
 
 Each prints one JSON line.  Kernel times come from the library's HIP events around each launch
 (TIDAL_FLAG_KERNEL_TIMING); call-level times from events on the compute stream.
@@ -233,9 +233,72 @@ def bench_churn(args):
     return out
 
 
+def bench_overlap(args):
+    """Sec. 5.2 of the paper on this hardware: time-to-finish of a consumer that reads every slot in
+    access order (stand-in for the first inference; its duration is set by the number of passes over
+    each slot) while the template streams in, (C) from nothing in access order, (D) from nothing in
+    reverse order, (E) with the leading M_prefetch bytes of Eq. 1 already resident.  Expectation:
+    C ~ max(load, compute) + first slot, D ~ load + compute, E ~ compute."""
+    wl = wl_mod.llama2_7b()
+    pool = hz.HostPool(wl, limit_bytes=2 << 30)
+    T = hz.DeviceTemplate(wl.shapes, flags=tb.TIDAL_FLAG_SLOT_EVENTS | tb.TIDAL_FLAG_ASYNC_ENQUEUE)
+    consumer = torch.cuda.Stream()
+    n = len(wl.shapes)
+    sums = torch.zeros(n, dtype=torch.int64, device="cuda:0")
+    srcs = pool.sources()
+    out = {"config": "overlap_llama2_7b_shaped", "model_GB": round(wl.source_bytes / 1e9, 3), "cases": []}
+
+    def load(which):
+        tb.tidal_materialize(T.h, which, T.copy_stream, T.compute_stream)
+
+    def consume(passes):
+        for i in range(n):
+            tb.tidal_slot_checksum(T.h, i, passes, consumer, sums[i:])
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        T.sync()
+        consumer.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    try:
+        load(srcs); T.sync()                                           # warm-up, everything resident
+        t_load = min(timed(lambda: load(srcs)) for _ in range(2))
+        t_c1 = min(timed(lambda: consume(1)) for _ in range(2))
+        t_c9 = min(timed(lambda: consume(9)) for _ in range(2))
+        per_pass = max((t_c9 - t_c1) / 8.0, 1e-3)
+        link = wl.source_bytes / (t_load * 1e-3)
+        out["load_ms"] = round(t_load, 2)
+        out["link_GBps"] = round(link / 1e9, 2)
+        out["consume_ms_first_pass"] = round(t_c1, 3)
+        out["consume_ms_per_extra_pass"] = round(per_pass, 3)
+        for ratio in (0.5, 1.0, 2.0):
+            passes = max(1, 1 + int(round((ratio * t_load - t_c1) / per_pass)))
+            t_c = min(timed(lambda: consume(passes)) for _ in range(2))
+            t_cold = timed(lambda: (load(srcs), consume(passes)))
+            t_rev = timed(lambda: (load(srcs[::-1]), consume(passes)))
+            pre = tb.tidal_prefetch_bytes(wl.source_bytes, t_c * 1e-3, link)
+            n_res, res_bytes = tb.tidal_template_resident_prefix(T.h, pre)
+            # the resident part is the template; only the rest is loaded at invocation time
+            t_pre = timed(lambda: ((load(srcs[n_res:]) if n_res < n else None), consume(passes)))
+            out["cases"].append({
+                "compute_over_load": ratio, "passes": passes, "compute_ms": round(t_c, 2),
+                "cold_access_order_ms": round(t_cold, 2), "cold_reverse_order_ms": round(t_rev, 2),
+                "reverse_over_access": round(t_rev / t_cold, 3),
+                "eq1_prefetch_GB": round(pre / 1e9, 3), "resident_slots": n_res, "resident_GB": round(res_bytes / 1e9, 3),
+                "with_prefetch_ms": round(t_pre, 2),
+                "max_load_compute_ms": round(max(t_load, t_c), 2), "load_plus_compute_ms": round(t_load + t_c, 2)})
+            log(json.dumps(out["cases"][-1]))
+    finally:
+        T.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b"])
+    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap"])
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
     args = ap.parse_args()
@@ -247,6 +310,8 @@ def main():
         out = bench_stack(args, wl_mod.llama2_13b(), int(args.pool_gib * 2**30) if args.pool_gib else None)
     elif args.config == "70b":
         out = bench_stack(args, wl_mod.llama3_70b(), int((args.pool_gib or 24.0) * 2**30))
+    elif args.config == "overlap":
+        out = bench_overlap(args)
     else:
         out = bench_churn(args)
     print(json.dumps(out), flush=True)

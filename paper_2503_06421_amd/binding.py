@@ -28,7 +28,8 @@ EXPORTS = [
     "tidal_materialize_plan", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
     "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_template_slot_ptr",
-    "tidal_template_slot_wait", "tidal_convert_device", "tidal_h2d_peak", "tidal_get_stats",
+    "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
+    "tidal_convert_device", "tidal_h2d_peak", "tidal_get_stats",
     "tidal_reset_stats", "tidal_template_sync", "tidal_template_destroy", "tidal_last_error",
 ]
 
@@ -110,6 +111,10 @@ def lib() -> ctypes.CDLL:
     L.tidal_lora_swap_adapter.argtypes = [vp, vp, vp]
     L.tidal_template_slot_ptr.argtypes = [vp, c_int32, POINTER(vp), POINTER(c_size_t)]
     L.tidal_template_slot_wait.argtypes = [vp, c_int32, vp]
+    L.tidal_prefetch_bytes.restype = c_size_t
+    L.tidal_prefetch_bytes.argtypes = [c_size_t, c_double, c_double]
+    L.tidal_template_resident_prefix.argtypes = [vp, c_size_t, POINTER(c_int32), POINTER(c_size_t)]
+    L.tidal_slot_checksum.argtypes = [vp, c_int32, c_int32, vp, vp]
     L.tidal_convert_device.argtypes = [vp, vp, c_int32, c_int64, vp]
     L.tidal_h2d_peak.argtypes = [vp, c_size_t, c_int32, vp, POINTER(c_double)]
     L.tidal_get_stats.argtypes = [vp, POINTER(tidal_stats)]
@@ -295,6 +300,20 @@ def tidal_template_slot_ptr(t, slot: int):
 
 def tidal_template_slot_wait(t, slot: int, stream=None) -> None:
     _check(lib().tidal_template_slot_wait(t, slot, stream_ptr(stream)))
+
+
+def tidal_prefetch_bytes(model_bytes: int, ttft_seconds: float, link_bytes_per_second: float) -> int:
+    return lib().tidal_prefetch_bytes(model_bytes, ttft_seconds, link_bytes_per_second)
+
+
+def tidal_template_resident_prefix(t, prefetch_bytes: int):
+    n, b = c_int32(), c_size_t()
+    _check(lib().tidal_template_resident_prefix(t, prefetch_bytes, byref(n), byref(b)))
+    return n.value, b.value
+
+
+def tidal_slot_checksum(t, slot: int, passes: int, stream, dev_sum) -> None:
+    _check(lib().tidal_slot_checksum(t, slot, passes, stream_ptr(stream), device_ptr(dev_sum)))
 
 
 def tidal_convert_device(dst, src, dtype: int, n: int, stream=None) -> None:

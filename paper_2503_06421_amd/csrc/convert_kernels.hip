@@ -171,4 +171,50 @@ hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Stand-in consumer: integer checksum of a slot, read `passes` times.  Grid-stride over 16-byte
+// vectors with a bounded number of workgroups, reduction by shuffles and LDS, one 64-bit atomic
+// per workgroup (thousands of atomics on one address would cost more than the reads).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void slot_checksum_kernel(const uint16_t* __restrict__ slot, int64_t elems,
+                                                            int passes, unsigned long long* __restrict__ out) {
+    const int64_t nvec = elems >> 3;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t v0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned long long sum = 0;
+    for (int p = 0; p < passes; ++p) {
+        for (int64_t v = v0; v < nvec; v += stride) {
+            const u32x4 x = __builtin_nontemporal_load((const u32x4*)slot + v);
+            sum += (x.x & 0xFFFFu) + (x.x >> 16) + (x.y & 0xFFFFu) + (x.y >> 16) + (x.z & 0xFFFFu) + (x.z >> 16) +
+                   (x.w & 0xFFFFu) + (x.w >> 16);
+        }
+        if (v0 == 0) {                                     // ragged tail (< 8 elements), one lane
+            for (int64_t i = nvec << 3; i < elems; ++i) sum += slot[i];
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned lo = __shfl_down((unsigned)(sum & 0xFFFFFFFFull), off, 64);
+        const unsigned hi = __shfl_down((unsigned)(sum >> 32), off, 64);
+        sum += ((unsigned long long)hi << 32) | lo;
+    }
+    __shared__ unsigned long long part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned long long total = part[0] + part[1] + part[2] + part[3];
+        if (total) atomicAdd(out, total);
+    }
+}
+
+hipError_t launch_slot_checksum(const void* slot, int64_t elems, int passes, void* dev_sum, hipStream_t stream) {
+    if (elems <= 0) return hipSuccess;
+    int64_t blocks = ((elems >> 3) + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(slot_checksum_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint16_t*)slot,
+                       elems, passes, (unsigned long long*)dev_sum);
+    return hipGetLastError();
+}
+
 }  // namespace tidal

@@ -840,6 +840,48 @@ extern "C" int tidal_lora_detach(tidal_template* t, void* stream) {
 }
 
 // ---------------------------------------------------------------------------------------
+// partial residency (Sec. 5.2, Eq. 1) and the stand-in consumer
+// ---------------------------------------------------------------------------------------
+extern "C" size_t tidal_prefetch_bytes(size_t model_bytes, double ttft_seconds, double link_bytes_per_second) {
+    if (!(ttft_seconds >= 0.0) || !(link_bytes_per_second >= 0.0)) return 0;
+    const double hidden = ttft_seconds * link_bytes_per_second;      // bytes that stream in under the inference
+    if (!(hidden < (double)model_bytes)) return 0;
+    const double need = (double)model_bytes - hidden;
+    size_t r = (size_t)need;
+    if ((double)r < need) ++r;                                       // round up: never prefetch too little
+    return r > model_bytes ? model_bytes : r;
+}
+
+extern "C" int tidal_template_resident_prefix(const tidal_template* t, size_t prefetch_bytes, int32_t* n_slots,
+                                              size_t* bytes) {
+    if (!t || !n_slots) return fail(TIDAL_E_INVAL, "NULL argument");
+    size_t sum = 0;
+    int32_t n = 0;
+    // smallest prefix that covers prefetch_bytes (residency is slot-granular, so round up)
+    while (n < (int32_t)t->slots.size() && sum < prefetch_bytes) {
+        sum += 2 * (size_t)t->slots[n].elems;
+        ++n;
+    }
+    *n_slots = n;
+    if (bytes) *bytes = sum;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_slot_checksum(tidal_template* t, int32_t slot, int32_t passes, void* stream, uint64_t* dev_sum) {
+    if (!t || !dev_sum) return fail(TIDAL_E_INVAL, "NULL argument");
+    if (slot < 0 || slot >= (int32_t)t->slots.size()) return fail(TIDAL_E_INVAL, "slot %d out of range", slot);
+    if (passes < 1 || passes > (1 << 20)) return fail(TIDAL_E_INVAL, "passes outside 1..2^20");
+    if ((uintptr_t)dev_sum % 8) return fail(TIDAL_E_INVAL, "dev_sum is not 8-byte aligned");
+    SlotState& s = t->slots[slot];
+    if (s.elems == 0) return TIDAL_OK;
+    if (!s.materialised) return fail(TIDAL_E_STATE, "slot %d was never materialised", slot);
+    if ((t->cfg.flags & TIDAL_FLAG_SLOT_EVENTS) && s.ready_recorded)
+        HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, s.ready, 0));
+    HIP_TRY(launch_slot_checksum(slot_ptr(t, slot), s.elems, passes, dev_sum, (hipStream_t)stream));
+    return TIDAL_OK;
+}
+
+// ---------------------------------------------------------------------------------------
 // utilities
 // ---------------------------------------------------------------------------------------
 extern "C" int tidal_convert_device(void* dst_bf16, const void* src, int32_t dtype, int64_t n, void* stream) {

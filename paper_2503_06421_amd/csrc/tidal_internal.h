@@ -22,6 +22,7 @@ constexpr int kMaxConvertSeg = 32;
 struct ConvertBatch { ConvertSegment seg[kMaxConvertSeg]; };
 
 hipError_t launch_convert(const ConvertBatch& batch, int nseg, hipStream_t stream);
+hipError_t launch_slot_checksum(const void* slot, int64_t elems, int passes, void* dev_sum, hipStream_t stream);
 
 // ---- packing of LoRA factors ------------------------------------------------------------
 struct PackSegment {

@@ -214,3 +214,22 @@ def test_no_device_means_error_not_fallback(small_template):
     t, shapes = small_template
     a = np.zeros((8, 16), np.float32)
     _expect(tb.TIDAL_E_HIP, tb.tidal_materialize, t, [(0, tb.TIDAL_F32, a.ctypes.data)])
+
+
+def test_prefetch_rule_and_resident_prefix_match_oracle(orc):
+    """Eq. 1 of the paper's Sec. 5.2 and the slot-granular prefix that realises it (host-only)."""
+    cases = [(24_300_000_000, 0.4, 32e9), (24_300_000_000, 1.0, 32e9), (13_476_298_752, 0.12, 57.3e9),
+             (1000, 1e-9, 1e9), (1000, 0.5e-9, 1e9), (0, 1.0, 1.0), (5, 0.0, 0.0)]
+    for m, tt, bw in cases:
+        assert tb.tidal_prefetch_bytes(m, tt, bw) == orc.prefetch_bytes(m, tt, bw), (m, tt, bw)
+    assert tb.tidal_prefetch_bytes(100, -1.0, 1.0) == 0 and tb.tidal_prefetch_bytes(100, float("nan"), 1.0) == 0
+    w = wl_mod.llama2_7b()
+    t = tb.tidal_template_create(w.shapes, FAKE_ARENA, 1 << 40, None)
+    try:
+        for pre in (0, 1, 262_144_000, 262_144_001, 5_000_000_000, w.source_bytes, w.source_bytes + 1):
+            n, b = tb.tidal_template_resident_prefix(t, pre)
+            assert n == orc.resident_prefix(w.shapes, pre)
+            assert b == sum(2 * r * c for r, c in w.shapes[:n])
+            assert b >= min(pre, w.source_bytes)
+    finally:
+        tb.tidal_template_destroy(t)

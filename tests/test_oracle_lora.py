@@ -251,3 +251,25 @@ def test_workload_shapes():
     assert len(ch.base.lora_slots) == 128 and 4 * ch.base.lora_w_elements == 8_589_934_592
     assert len(ch.schedule) == 200 and set(ch.ranks) <= {8, 16, 32, 64}
     assert wl_mod.adapter_churn().schedule == ch.schedule          # seeded
+
+
+def test_prefetch_rule_eq1(orc):
+    """Eq. 1 of the paper's Sec. 5.2: M_prefetch = max(M_model - T_TTFT * B_PCIe, 0).  Worked by
+    hand: a 24.3 GB model, 0.4 s of inference and a 32 GB/s link leave 24.3 - 12.8 = 11.5 GB to
+    prefetch; a long inference hides everything."""
+    assert orc.prefetch_bytes(24_300_000_000, 0.4, 32e9) == 11_500_000_000
+    assert orc.prefetch_bytes(24_300_000_000, 1.0, 32e9) == 0
+    assert orc.prefetch_bytes(24_300_000_000, 0.0, 32e9) == 24_300_000_000
+    assert orc.prefetch_bytes(1000, 1e-9, 1e9) == 999
+    assert orc.prefetch_bytes(1000, 0.5e-9, 1e9) == 1000          # 999.5 rounds up to a whole byte
+    shapes = [(4, 8), (2, 2), (16, 16), (1, 1)]                   # 64, 8, 512, 2 bytes
+    assert [orc.resident_prefix(shapes, b) for b in (0, 1, 64, 65, 72, 73, 584, 585, 10 ** 6)] == [0, 1, 1, 2, 2, 3, 3, 4, 4]
+
+
+def test_slot_checksum_closed_form(orc):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    assert orc.slot_checksum(bits) == 65535 * 65536 // 2
+    assert orc.slot_checksum(bits, 7) == 7 * (65535 * 65536 // 2)
+    assert orc.slot_checksum(np.full(3, 0xFFFF, np.uint16), 2) == 6 * 0xFFFF
+    big = np.full(1 << 20, 0xFFFF, np.uint16)
+    assert orc.slot_checksum(big, 1 << 20) == ((1 << 20) * 0xFFFF * (1 << 20)) % (1 << 64)
