@@ -42,6 +42,7 @@ extern "C" {
 
 typedef struct tidal_template tidal_template;   /* opaque, freed by tidal_template_destroy */
 typedef struct tidal_adapter tidal_adapter;     /* opaque, freed by tidal_adapter_destroy  */
+typedef struct tidal_fork tidal_fork;           /* opaque, freed by tidal_fork_destroy     */
 
 typedef enum { TIDAL_F32 = 0, TIDAL_F16 = 1, TIDAL_BF16 = 2 } tidal_dtype;
 
@@ -202,6 +203,27 @@ int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* targets /* 
 int tidal_adapter_destroy(tidal_adapter* a);   /* must not be attached */
 int tidal_lora_attach_adapter(tidal_template* t, const tidal_adapter* a, void* stream);
 int tidal_lora_swap_adapter(tidal_template* t, const tidal_adapter* a_new, void* stream);
+
+/* Copy-on-write forks (Sec. 1: a template must stay request-agnostic, "a copy-on-write
+ * mechanism is critical for safe template sharing"; Sec. 5.2: a write to a forked weight goes
+ * to a new tensor).  A fork owns private copies, in caller-owned device memory, of the slots an
+ * invocation's adapter writes; the template's slots are only read.  tidal_fork_apply rewrites
+ * every private copy from the pristine template in one pass:
+ *     fork[s] <- bf16( f32(template[s]) + (alpha/r) * B * A )   for slots the adapter targets,
+ *     fork[s] <- template[s]                                    for the fork's other slots
+ * (a == NULL: all plain copies).  Changing adapters is just another apply: there is no unmerge,
+ * so rounding never accumulates over a sequence of adapters -- the result always equals a
+ * first attach bit for bit -- and the traffic is the same 4 bytes per element as the in-place
+ * swap.  TIDAL_E_STATE while an adapter is merged into the template in place; TIDAL_E_INVAL if
+ * the adapter targets a slot outside the fork.  Several forks of one template may coexist. */
+size_t tidal_fork_required_bytes(const tidal_template* t, const int32_t* slots /* [host] */, int32_t n);
+int tidal_fork_create(tidal_template* t, const int32_t* slots /* [host] copied */, int32_t n,
+                      void* dev_mem /* [device] 256-byte aligned, borrowed until tidal_fork_destroy */,
+                      size_t dev_bytes, tidal_fork** out /* [host] out */);
+int tidal_fork_apply(tidal_fork* f, const tidal_adapter* a /* resident adapter or NULL */, void* stream);
+int tidal_fork_slot_ptr(const tidal_fork* f, int32_t slot, void** dev_ptr /* [host] out */,
+                        size_t* bytes /* [host] out, may be NULL */);
+int tidal_fork_destroy(tidal_fork* f);
 
 /* Device address and byte length (2*rows*cols) of a slot. */
 int tidal_template_slot_ptr(const tidal_template* t, int32_t slot, void** dev_ptr /* [host] out */,

@@ -226,6 +226,26 @@ def bench_churn(args):
             "by_rank_pair_count": {"%d->%d" % k: len(v) for k, v in sorted(by.items())}})
         tb.tidal_lora_detach(T.h, T.compute_stream)
         T.sync()
+        # the same schedule through a copy-on-write fork: every step rewrites the private copies of
+        # the 128 targeted slots from the pristine template (no unmerge, no accumulated rounding)
+        need = tb.tidal_fork_required_bytes(T.h, wl.lora_slots)
+        fmem = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+        F = tb.tidal_fork_create(T.h, wl.lora_slots, fmem, need)
+        fk, fbytes = [], 0
+        for step, a in enumerate(ch.schedule):
+            tb.tidal_reset_stats(T.h)
+            tb.tidal_fork_apply(F, handles[a], T.compute_stream)
+            T.sync()
+            st = tb.tidal_get_stats(T.h)
+            if step:
+                fk.append(st["lora_kernel_ms"])
+                fbytes += lora_bytes(wl, 0, ch.ranks[a])
+        fk = np.array(fk)
+        out["fork_apply_kernel_ms"] = {"mean": round(float(fk.mean()), 4), "p50": round(float(np.median(fk)), 4),
+                                       "p95": round(float(np.percentile(fk, 95)), 4)}
+        out["fork_apply_GBps_overall"] = round(fbytes / fk.sum() / 1e6, 1)
+        out["fork_extra_GB"] = round(need / 1e9, 3)
+        tb.tidal_fork_destroy(F)
         for h in handles:
             tb.tidal_adapter_destroy(h)
     finally:

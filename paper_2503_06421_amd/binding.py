@@ -27,7 +27,8 @@ EXPORTS = [
     "tidal_config_default", "tidal_template_required_bytes", "tidal_template_create", "tidal_materialize",
     "tidal_materialize_plan", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
-    "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_template_slot_ptr",
+    "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_fork_required_bytes", "tidal_fork_create",
+    "tidal_fork_apply", "tidal_fork_slot_ptr", "tidal_fork_destroy", "tidal_template_slot_ptr",
     "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
     "tidal_convert_device", "tidal_h2d_peak", "tidal_get_stats",
     "tidal_reset_stats", "tidal_template_sync", "tidal_template_destroy", "tidal_last_error",
@@ -109,6 +110,12 @@ def lib() -> ctypes.CDLL:
     L.tidal_adapter_destroy.argtypes = [vp]
     L.tidal_lora_attach_adapter.argtypes = [vp, vp, vp]
     L.tidal_lora_swap_adapter.argtypes = [vp, vp, vp]
+    L.tidal_fork_required_bytes.restype = c_size_t
+    L.tidal_fork_required_bytes.argtypes = [vp, POINTER(c_int32), c_int32]
+    L.tidal_fork_create.argtypes = [vp, POINTER(c_int32), c_int32, vp, c_size_t, POINTER(vp)]
+    L.tidal_fork_apply.argtypes = [vp, vp, vp]
+    L.tidal_fork_slot_ptr.argtypes = [vp, c_int32, POINTER(vp), POINTER(c_size_t)]
+    L.tidal_fork_destroy.argtypes = [vp]
     L.tidal_template_slot_ptr.argtypes = [vp, c_int32, POINTER(vp), POINTER(c_size_t)]
     L.tidal_template_slot_wait.argtypes = [vp, c_int32, vp]
     L.tidal_prefetch_bytes.restype = c_size_t
@@ -290,6 +297,38 @@ def tidal_lora_attach_adapter(t, a, stream=None) -> None:
 
 def tidal_lora_swap_adapter(t, a, stream=None) -> None:
     _check(lib().tidal_lora_swap_adapter(t, a, stream_ptr(stream)))
+
+
+def _slot_list(slots):
+    slots = list(slots)
+    arr = (c_int32 * max(1, len(slots)))(*slots)
+    return arr, len(slots)
+
+
+def tidal_fork_required_bytes(t, slots) -> int:
+    arr, n = _slot_list(slots)
+    return lib().tidal_fork_required_bytes(t, arr, n)
+
+
+def tidal_fork_create(t, slots, dev_mem, dev_bytes: int) -> int:
+    arr, n = _slot_list(slots)
+    out = c_void_p()
+    _check(lib().tidal_fork_create(t, arr, n, device_ptr(dev_mem), dev_bytes, byref(out)))
+    return out.value
+
+
+def tidal_fork_apply(f, a=None, stream=None) -> None:
+    _check(lib().tidal_fork_apply(f, a, stream_ptr(stream)))
+
+
+def tidal_fork_slot_ptr(f, slot: int):
+    p, n = c_void_p(), c_size_t()
+    _check(lib().tidal_fork_slot_ptr(f, slot, byref(p), byref(n)))
+    return (p.value or 0), n.value
+
+
+def tidal_fork_destroy(f) -> None:
+    _check(lib().tidal_fork_destroy(f))
 
 
 def tidal_template_slot_ptr(t, slot: int):

@@ -197,9 +197,12 @@ __device__ __forceinline__ void store_block(uint16_t* __restrict__ W, int out, i
     }
 }
 
-template <int NT, int KS0, int KS1>
+// FORK: the result goes to a separate destination (old_base + at_old, which are free because a
+// fork never unmerges: KS0 == 0) and W itself, the template's pristine slot, is only read.
+template <int NT, int KS0, int KS1, bool FORK = false>
 __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraBatch batch, int out, int in, int strips, int rowblocks,
                                                         int rc, int blocks_per_target, int total_blocks) {
+    static_assert(!FORK || KS0 == 0, "a fork starts from the pristine template: nothing to unmerge");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Workgroups are dealt round-robin to the 8 XCDs; undo that so that each XCD walks a
@@ -250,7 +253,8 @@ __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraBatch batch, i
             delta_tile<NT, KS1>(Bp_new, out, i0, lane, bop1, acc);
             apply_tile<NT>(w, acc, d.s_new);
         }
-        store_block<NT>(W, out, in, i0, jl, h, full, w);
+        store_block<NT>(FORK ? (uint16_t*)(batch.old_base + (size_t)d.at_old * kLoraUnit) : W, out, in, i0, jl, h,
+                        full, w);
     }
 }
 
@@ -362,7 +366,7 @@ static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int NT, int KS0, int KS1>
+template <int NT, int KS0, int KS1, bool FORK = false>
 static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int strips = (g.in + 32 * NT - 1) / (32 * NT);
     const int rowblocks = (g.out + 31) / 32;
@@ -383,7 +387,7 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int64_t total = (int64_t)blocks_per_target * g.n_targets;
     if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
+    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1, FORK>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
                        g.in, strips, rowblocks, rc, blocks_per_target, (int)total);
     return hipGetLastError();
 }
@@ -398,6 +402,10 @@ static hipError_t launch_mfma_pick(const LoraGroup& g, hipStream_t stream, int u
     if constexpr (KS0 + KS1 == 0) {
         return hipSuccess;
     } else {
+        if constexpr (KS0 == 0) {
+            if (g.fork) return launch_mfma_inst<NT, 0, KS1, true>(g, stream);
+        }
+        if (g.fork) return hipErrorInvalidValue;
         if (use_lds < 0) use_lds = (KS0 + KS1 >= kLdsFromSteps) ? 1 : 0;
         if (use_lds) return launch_mfma_lds_inst<NT, KS0, KS1>(g, stream);
         return launch_mfma_inst<NT, KS0, KS1>(g, stream);
@@ -513,7 +521,8 @@ __device__ __forceinline__ void ordered_phase(const uint16_t* __restrict__ At, c
 
 __global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraBatch batch, int out,
                                                            int in, int r_old, int rp_old, int r_new,
-                                                           int rp_new, int col_tiles, int tiles_per_target) {
+                                                           int rp_new, int col_tiles, int tiles_per_target,
+                                                           int fork) {
     __shared__ __attribute__((aligned(16))) float Atile[kOrdK * kOrdCols];
     __shared__ __attribute__((aligned(16))) float Btile[kOrdK * kOrdRows];
     const int target = blockIdx.x / tiles_per_target;
@@ -547,6 +556,7 @@ __global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraBatch batch
             }
         }
     }
+    uint16_t* __restrict__ Wd = fork ? (uint16_t*)(batch.old_base + (size_t)d.at_old * kLoraUnit) : W;
     if (rp_old > 0) ordered_phase(At_old, Bp_old, r_old, rp_old, d.s_old, out, in, i0, j0, Atile, Btile, w);
     if (rp_new > 0) ordered_phase(At_new, Bp_new, r_new, rp_new, d.s_new, out, in, i0, j0, Atile, Btile, w);
 #pragma unroll
@@ -555,12 +565,12 @@ __global__ __launch_bounds__(256) void lora_ordered_kernel(const LoraBatch batch
         if (vec_ok && row < out) {
             u32x4 x;
             x.x = w[rr][0]; x.y = w[rr][1]; x.z = w[rr][2]; x.w = w[rr][3];
-            *as_global((u32x4*)(W + (int64_t)row * in + jl)) = x;
+            *as_global((u32x4*)(Wd + (int64_t)row * in + jl)) = x;
         } else {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                if (row < out && jl + 2 * p < in) as_global(W)[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[rr][p] & 0xFFFFu);
-                if (row < out && jl + 2 * p + 1 < in) as_global(W)[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[rr][p] >> 16);
+                if (row < out && jl + 2 * p < in) as_global(Wd)[(int64_t)row * in + jl + 2 * p] = (uint16_t)(w[rr][p] & 0xFFFFu);
+                if (row < out && jl + 2 * p + 1 < in) as_global(Wd)[(int64_t)row * in + jl + 2 * p + 1] = (uint16_t)(w[rr][p] >> 16);
             }
         }
     }
@@ -575,7 +585,7 @@ hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream) {
     const int64_t total = tiles_per_target * g.n_targets;
     if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(lora_ordered_kernel, dim3((unsigned)total), dim3(256), 0, stream, *g.batch, g.out, g.in,
-                       g.r_old, g.rp_old, g.r_new, g.rp_new, col_tiles, (int)tiles_per_target);
+                       g.r_old, g.rp_old, g.r_new, g.rp_new, col_tiles, (int)tiles_per_target, g.fork ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -673,6 +673,43 @@ extern "C" int tidal_adapter_destroy(tidal_adapter* a) {
 // ---------------------------------------------------------------------------------------
 // LoRA launches
 // ---------------------------------------------------------------------------------------
+typedef std::tuple<int64_t, int64_t, int, int, int, int> LoraKey;   // out, in, rp_old, rp_new, r_old, r_new
+
+// One launch per (shape, ranks) group and at most kMaxLoraTargets slots.
+static int launch_groups(tidal_template* t, const std::map<LoraKey, std::vector<LoraTargetDev>>& groups,
+                         const char* old_base, const char* new_base, bool fork, hipStream_t stream) {
+    const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
+    for (auto& g : groups) {
+        const std::vector<LoraTargetDev>& all = g.second;
+        for (size_t at = 0; at < all.size(); at += kMaxLoraTargets) {
+            const size_t n = std::min(all.size() - at, (size_t)kMaxLoraTargets);
+            LoraBatch batch;
+            batch.w_base = t->arena;
+            batch.old_base = old_base;
+            batch.new_base = new_base;
+            memcpy(batch.t, all.data() + at, n * sizeof(LoraTargetDev));
+            LoraGroup lg;
+            lg.batch = &batch;
+            lg.n_targets = (int32_t)n;
+            lg.out = (int32_t)std::get<0>(g.first);
+            lg.in = (int32_t)std::get<1>(g.first);
+            lg.rp_old = std::get<2>(g.first);
+            lg.rp_new = std::get<3>(g.first);
+            lg.r_old = std::get<4>(g.first);
+            lg.r_new = std::get<5>(g.first);
+            lg.fork = fork;
+            hipEvent_t t0;
+            int trc = timing_begin(t, stream, &t0);
+            if (trc) return trc;
+            HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, stream));
+            trc = timing_end(t, stream, t0, true);
+            if (trc) return trc;
+            t->stats.lora_launches++;
+        }
+    }
+    return TIDAL_OK;
+}
+
 // One pass over the union of the slots of `older` (subtracted) and `newer` (added); either
 // may be NULL.  Slots are grouped by (shape, padded ranks) and each group is one launch.
 static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterRec* newer, hipStream_t stream) {
@@ -686,7 +723,7 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
             if (p.active() && t->slots[p.slot].elems > 0) by_slot[p.slot].second = Side{&p, newer};
     if (by_slot.empty()) return TIDAL_OK;
 
-    typedef std::tuple<int64_t, int64_t, int, int, int, int> Key;   // out, in, rp_old, rp_new, r_old, r_new
+    typedef LoraKey Key;
     std::map<Key, std::vector<LoraTargetDev>> groups;
     for (auto& kv : by_slot) {
         const SlotState& s = t->slots[kv.first];
@@ -713,34 +750,8 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
         groups[Key(s.rows, s.cols, rp_old, rp_new, r_old, r_new)].push_back(d);
         t->stats.rmw_elems += (uint64_t)s.elems;
     }
-    const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
-    for (auto& g : groups) {
-        const std::vector<LoraTargetDev>& all = g.second;
-        for (size_t at = 0; at < all.size(); at += kMaxLoraTargets) {
-            const size_t n = std::min(all.size() - at, (size_t)kMaxLoraTargets);
-            LoraBatch batch;
-            batch.w_base = t->arena;
-            batch.old_base = older ? older->dev : nullptr;
-            batch.new_base = newer ? newer->dev : nullptr;
-            memcpy(batch.t, all.data() + at, n * sizeof(LoraTargetDev));
-            LoraGroup lg;
-            lg.batch = &batch;
-            lg.n_targets = (int32_t)n;
-            lg.out = (int32_t)std::get<0>(g.first);
-            lg.in = (int32_t)std::get<1>(g.first);
-            lg.rp_old = std::get<2>(g.first);
-            lg.rp_new = std::get<3>(g.first);
-            lg.r_old = std::get<4>(g.first);
-            lg.r_new = std::get<5>(g.first);
-            hipEvent_t t0;
-            int trc = timing_begin(t, stream, &t0);
-            if (trc) return trc;
-            HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, stream));
-            trc = timing_end(t, stream, t0, true);
-            if (trc) return trc;
-            t->stats.lora_launches++;
-        }
-    }
+    int rc = launch_groups(t, groups, older ? older->dev : nullptr, newer ? newer->dev : nullptr, false, stream);
+    if (rc) return rc;
     HIP_TRY(hipEventRecord(t->ev_last_lora, stream));
     t->last_lora_rec = true;
     return TIDAL_OK;
@@ -836,6 +847,129 @@ extern "C" int tidal_lora_detach(tidal_template* t, void* stream) {
     // cur_region keeps its value: the next host-pointer attach then uses the other region,
     // so a still-running detach kernel never has its factors overwritten
     t->cur.targets.clear();
+    return TIDAL_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// copy-on-write forks
+// ---------------------------------------------------------------------------------------
+struct tidal_fork {
+    tidal_template* t;
+    std::vector<int32_t> slots;      // sorted
+    std::vector<size_t> offset;      // byte offset of each slot's private copy in dev
+    char* dev;
+    size_t bytes;
+};
+
+static int fork_layout(const tidal_template* t, const int32_t* slots, int32_t n, std::vector<int32_t>* sl,
+                       std::vector<size_t>* off, size_t* total) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    if (n < 0 || (!slots && n > 0)) return fail(TIDAL_E_INVAL, "bad slot list (n=%d)", n);
+    sl->assign(slots, slots + n);
+    std::sort(sl->begin(), sl->end());
+    size_t o = 0;
+    off->clear();
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t s = (*sl)[i];
+        if (s < 0 || s >= (int32_t)t->slots.size()) return fail(TIDAL_E_INVAL, "slot %d out of range", s);
+        if (i > 0 && s == (*sl)[i - 1]) return fail(TIDAL_E_INVAL, "slot %d given twice", s);
+        off->push_back(o);
+        o = align_up(o + 2 * (size_t)t->slots[s].elems, kSlotAlign);
+    }
+    *total = o ? o : kSlotAlign;
+    return TIDAL_OK;
+}
+
+extern "C" size_t tidal_fork_required_bytes(const tidal_template* t, const int32_t* slots, int32_t n) {
+    std::vector<int32_t> sl;
+    std::vector<size_t> off;
+    size_t total = 0;
+    if (fork_layout(t, slots, n, &sl, &off, &total)) return 0;
+    return total;
+}
+
+extern "C" int tidal_fork_create(tidal_template* t, const int32_t* slots, int32_t n, void* dev_mem, size_t dev_bytes,
+                                 tidal_fork** out) {
+    if (!out) return fail(TIDAL_E_INVAL, "out is NULL");
+    *out = nullptr;
+    std::vector<int32_t> sl;
+    std::vector<size_t> off;
+    size_t total = 0;
+    int rc = fork_layout(t, slots, n, &sl, &off, &total);
+    if (rc) return rc;
+    if (!dev_mem) return fail(TIDAL_E_INVAL, "dev_mem is NULL");
+    if ((uintptr_t)dev_mem % kSlotAlign) return fail(TIDAL_E_INVAL, "dev_mem is not 256-byte aligned");
+    if (total > dev_bytes) return fail(TIDAL_E_NOMEM, "fork needs %zu bytes, got %zu", total, dev_bytes);
+    if (total / kLoraUnit > 0xFFFFFFFFull) return fail(TIDAL_E_INVAL, "fork too large");
+    tidal_fork* f = new (std::nothrow) tidal_fork();
+    if (!f) return fail(TIDAL_E_NOMEM, "out of host memory");
+    f->t = t;
+    f->slots = sl;
+    f->offset = off;
+    f->dev = (char*)dev_mem;
+    f->bytes = total;
+    *out = f;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_fork_destroy(tidal_fork* f) {
+    delete f;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_fork_slot_ptr(const tidal_fork* f, int32_t slot, void** dev_ptr, size_t* bytes) {
+    if (!f || !dev_ptr) return fail(TIDAL_E_INVAL, "NULL argument");
+    auto it = std::lower_bound(f->slots.begin(), f->slots.end(), slot);
+    if (it == f->slots.end() || *it != slot) return fail(TIDAL_E_INVAL, "slot %d is not part of this fork", slot);
+    *dev_ptr = f->dev + f->offset[(size_t)(it - f->slots.begin())];
+    if (bytes) *bytes = 2 * (size_t)f->t->slots[slot].elems;
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_fork_apply(tidal_fork* f, const tidal_adapter* a, void* stream_) {
+    if (!f) return fail(TIDAL_E_INVAL, "fork is NULL");
+    tidal_template* t = f->t;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (a && a->owner != t) return fail(TIDAL_E_INVAL, "adapter belongs to another template");
+    if (t->attached) return fail(TIDAL_E_STATE, "an adapter is merged into the template in place; detach it first");
+    for (int32_t s : f->slots)
+        if (!t->slots[s].materialised && t->slots[s].elems > 0)
+            return fail(TIDAL_E_STATE, "fork slot %d was never materialised", s);
+    std::map<int32_t, const PackedTarget*> active;
+    if (a)
+        for (const PackedTarget& p : a->rec.targets) {
+            if (!std::binary_search(f->slots.begin(), f->slots.end(), p.slot))
+                return fail(TIDAL_E_INVAL, "adapter targets slot %d, which is not part of the fork", p.slot);
+            if (p.active() && t->slots[p.slot].elems > 0) active[p.slot] = &p;
+        }
+    int rc = ensure_device(t);
+    if (rc) return rc;
+    std::map<LoraKey, std::vector<LoraTargetDev>> groups;
+    for (size_t i = 0; i < f->slots.size(); ++i) {
+        const int32_t slot = f->slots[i];
+        const SlotState& s = t->slots[slot];
+        if (s.elems == 0) continue;
+        auto it = active.find(slot);
+        if (it == active.end()) {
+            // not written by this adapter: the private copy is the template's value again
+            HIP_TRY(hipMemcpyAsync(f->dev + f->offset[i], slot_ptr(t, slot), 2 * (size_t)s.elems, hipMemcpyDeviceToDevice, stream));
+            continue;
+        }
+        const PackedTarget* p = it->second;
+        LoraTargetDev d;
+        memset(&d, 0, sizeof d);
+        d.w = (uint32_t)(t->lay.slot_offset[slot] / kLoraUnit);
+        d.at_old = (uint32_t)(f->offset[i] / kLoraUnit);               // destination, relative to the fork's memory
+        d.at_new = (uint32_t)(p->at_off / kLoraUnit);
+        d.bp_new = (uint32_t)(p->bp_off / kLoraUnit);
+        d.s_new = p->alpha / (float)p->r;
+        groups[LoraKey(s.rows, s.cols, 0, p->rp, 0, p->r)].push_back(d);
+        t->stats.rmw_elems += (uint64_t)s.elems;
+    }
+    rc = launch_groups(t, groups, f->dev, a ? a->rec.dev : nullptr, true, stream);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(t->ev_last_lora, stream));
+    t->last_lora_rec = true;
     return TIDAL_OK;
 }
 

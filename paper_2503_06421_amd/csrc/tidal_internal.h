@@ -64,6 +64,7 @@ struct LoraGroup {
     int32_t out, in;
     int32_t r_old, r_new;        // true ranks (ordered-accumulation kernel)
     int32_t rp_old, rp_new;      // padded ranks: 0, 16, 32 or 64
+    bool fork;                   // write to old_base + at_old instead of in place (rp_old must be 0)
 };
 
 // Matrix-core path (default) and ordered-accumulation vector path.
