@@ -91,7 +91,11 @@ enum {
      * transfer, like a template-server thread would), because a deep queue of cross-stream
      * waits makes every copy slower; with this flag the call returns as soon as everything is
      * enqueued, at a lower transfer rate for large jobs.                                      */
-    TIDAL_FLAG_ASYNC_ENQUEUE = 16
+    TIDAL_FLAG_ASYNC_ENQUEUE = 16,
+    /* Issue one hipMemcpyAsync per planned piece: neighbouring pieces are not merged into one
+     * copy and tiny tensors are not gathered by the CPU.  For measuring what tensor merging
+     * (Sec. 6) buys; results are identical.                                                    */
+    TIDAL_FLAG_NO_COPY_MERGE = 32
 };
 
 typedef struct {

@@ -1,7 +1,7 @@
 """Measurements of the other workload configurations (bench.py at the repository root times the
 Llama2-7B-shaped headline workload).
 
-    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap
+    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging
 
 Each prints one JSON line.  Kernel times come from the library's HIP events around each launch
 (TIDAL_FLAG_KERNEL_TIMING); call-level times from events on the compute stream.
@@ -316,9 +316,40 @@ def bench_overlap(args):
     return out
 
 
+def bench_merging(args):
+    """Tensor-merging study (Sec. 6 / Sec. 7.4 of the paper): 1,202 tensors of a 70B-shaped TP-8
+    shard, streamed with and without merging neighbouring copies, for several chunk sizes."""
+    wl = wl_mod.llama70b_tp8_shard_many_tensors()
+    pool = hz.HostPool(wl, limit_bytes=4 << 30)
+    srcs = pool.sources()
+    out = {"config": wl.name, "tensors": len(wl.tensors), "source_GB": round(wl.source_bytes / 1e9, 3), "runs": []}
+    for merge in (True, False):
+        for mib in (16, 64, 256):
+            flags = 0 if merge else tb.TIDAL_FLAG_NO_COPY_MERGE
+            T = hz.DeviceTemplate(wl.shapes, chunk_bytes=mib << 20, flags=flags)
+            try:
+                ms = []
+                for rep in range(3):
+                    tb.tidal_reset_stats(T.h)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    tb.tidal_materialize(T.h, srcs, T.copy_stream, T.compute_stream)
+                    T.sync()
+                    ms.append((time.perf_counter() - t0) * 1e3)
+                st = tb.tidal_get_stats(T.h)
+                run = {"merge": merge, "chunk_mib": mib, "ms": round(min(ms[1:]), 2),
+                       "GBps": round(wl.source_bytes / min(ms[1:]) / 1e6, 2), "h2d_copies": st["h2d_copies"],
+                       "chunks": st["chunks"], "gathered_MB": round(st["gathered_bytes"] / 1e6, 3)}
+                out["runs"].append(run)
+                log(json.dumps(run))
+            finally:
+                T.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap"])
+    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging"])
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
     args = ap.parse_args()
@@ -332,6 +363,8 @@ def main():
         out = bench_stack(args, wl_mod.llama3_70b(), int((args.pool_gib or 24.0) * 2**30))
     elif args.config == "overlap":
         out = bench_overlap(args)
+    elif args.config == "merging":
+        out = bench_merging(args)
     else:
         out = bench_churn(args)
     print(json.dumps(out), flush=True)

@@ -24,7 +24,7 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
     if (c.max_rank < 0 || c.max_rank > 64) { *msg = "max_rank outside 1..64"; return false; }
     if (c.coalesce_bytes > c.chunk_bytes) { *msg = "coalesce_bytes above chunk_bytes"; return false; }
     const int32_t known = TIDAL_FLAG_ORDERED_ACCUM | TIDAL_FLAG_TWO_PASS_SWAP | TIDAL_FLAG_SLOT_EVENTS |
-                          TIDAL_FLAG_KERNEL_TIMING | TIDAL_FLAG_ASYNC_ENQUEUE;
+                          TIDAL_FLAG_KERNEL_TIMING | TIDAL_FLAG_ASYNC_ENQUEUE | TIDAL_FLAG_NO_COPY_MERGE;
     if (c.flags & ~known) { *msg = "unknown flag bits"; return false; }
     *out = c;
     return true;
@@ -67,7 +67,7 @@ void plan_copies(const std::vector<SourceInfo>& srcs, const tidal_config& cfg, i
         if (s.elems == 0) continue;
         const int64_t isz = (int64_t)dtype_size(s.dtype);
         const int64_t bytes = s.elems * isz;
-        const bool gathered = !s.pinned || (size_t)bytes < cfg.coalesce_bytes;
+        const bool gathered = !s.pinned || ((size_t)bytes < cfg.coalesce_bytes && !(cfg.flags & TIDAL_FLAG_NO_COPY_MERGE));
         const bool staged = s.dtype != TIDAL_BF16;
         int64_t remaining = s.elems, eoff = 0;
 

@@ -354,7 +354,8 @@ struct Pipeline {
             src = stage;
             slack = kSlotAlign - 1;     // gaps inside the library's own buffers only ever land in padding
         }
-        if (run && src >= run_src && dst >= run_dst && (size_t)(src - run_src) == (size_t)(dst - run_dst) &&
+        if (run && !(t->cfg.flags & TIDAL_FLAG_NO_COPY_MERGE) && src >= run_src && dst >= run_dst &&
+            (size_t)(src - run_src) == (size_t)(dst - run_dst) &&
             (size_t)(src - run_src) >= run_len && (size_t)(src - run_src) - run_len <= slack &&
             run_len + bytes <= ((size_t)1 << 30)) {
             run_len = (size_t)(src - run_src) + bytes;

@@ -188,6 +188,24 @@ def llama3_70b(layers: int = 80, **kw) -> Workload:
                        lora_on=_PROJ, rank=16, alpha=32.0, kv_dim=1024, **kw)
 
 
+def llama70b_tp8_shard_many_tensors(layers: int = 80) -> Workload:
+    """One tensor-parallel rank's share (1/8) of a Llama2-70B-shaped stack as a framework would
+    initialise it: 15 tensors per layer -- the seven projection shards, two norm vectors and six
+    tiny per-layer buffers -- i.e. 1,200 tensors for 80 layers, the count the paper quotes for
+    Llama2-70B on 8 GPUs in its tensor-merging experiment (Sec. 7.4)."""
+    h, ffn, kv, tp = 8192, 28672, 1024, 8
+    tensors = [TensorSpec("embed_shard", 32000 // tp, h)]
+    for l in range(layers):
+        tensors += [TensorSpec(f"l{l}.attn_norm", 1, h), TensorSpec(f"l{l}.q", h // tp, h),
+                    TensorSpec(f"l{l}.k", kv // tp, h), TensorSpec(f"l{l}.v", kv // tp, h),
+                    TensorSpec(f"l{l}.o", h, h // tp), TensorSpec(f"l{l}.ffn_norm", 1, h),
+                    TensorSpec(f"l{l}.gate", ffn // tp, h), TensorSpec(f"l{l}.up", ffn // tp, h),
+                    TensorSpec(f"l{l}.down", h, ffn // tp)]
+        tensors += [TensorSpec(f"l{l}.buf{b}", 1, 128) for b in range(6)]
+    tensors.append(TensorSpec("lm_head_shard", 32000 // tp, h))
+    return Workload(name="llama70b_tp8_shard_1200_tensors", wid=6, host_dtype=F16, tensors=tensors)
+
+
 def tiny_stack(host_dtype: int = F16, layers: int = 2, hidden: int = 192, ffn: int = 520,
                vocab: int = 1000, kv_dim: int | None = None, lora_on=("q", "v"), rank: int = 16,
                alpha: float = 32.0, with_norms: bool = False, wid: int = 9) -> Workload:
