@@ -21,7 +21,11 @@
  *   - Host source / adapter pointers are borrowed until the stream work of the call
  *     has completed (tidal_template_sync, or a sync of the streams given).
  *   - Calls are asynchronous with respect to the host and ordered on the given
- *     streams.  One thread at a time per template.
+ *     streams; in addition every LoRA / fork call waits (on the GPU) for the template's
+ *     last materialisation and every materialisation for its last LoRA call, whatever
+ *     streams those used.  LoRA calls among themselves are ordered only by their streams:
+ *     issue them on one stream or order them yourself.  One thread at a time per template.
+ *   - Adapters and forks refer to their template: destroy them before it.
  *   - Every int-returning call returns TIDAL_OK (0) or a negative tidal_status;
  *     tidal_last_error() then holds a message (thread-local).  Arguments are validated
  *     before any work is enqueued: a failed call leaves every slot untouched.  Nothing

@@ -431,6 +431,11 @@ extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32
     plan_copies(infos, t->cfg, kMaxConvertSeg, &plan);
 
     Pipeline pl{t, (hipStream_t)copy_stream, (hipStream_t)compute_stream};
+    // LoRA kernels of this template may have run on another stream: order after them
+    if (t->last_lora_rec) {
+        HIP_TRY(hipStreamWaitEvent(pl.compute, t->ev_last_lora, 0));
+        if (pl.copy != pl.compute) HIP_TRY(hipStreamWaitEvent(pl.copy, t->ev_last_lora, 0));
+    }
     // copies may write slots that earlier work on the compute stream still reads
     if (pl.copy != pl.compute) {
         HIP_TRY(hipEventRecord(t->ev_start, pl.compute));
@@ -723,6 +728,8 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
         for (const PackedTarget& p : newer->targets)
             if (p.active() && t->slots[p.slot].elems > 0) by_slot[p.slot].second = Side{&p, newer};
     if (by_slot.empty()) return TIDAL_OK;
+    // the slots may still be streaming in on the materialisation's streams
+    if (t->last_compute_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_compute, 0));
 
     typedef LoraKey Key;
     std::map<Key, std::vector<LoraTargetDev>> groups;
@@ -945,6 +952,8 @@ extern "C" int tidal_fork_apply(tidal_fork* f, const tidal_adapter* a, void* str
         }
     int rc = ensure_device(t);
     if (rc) return rc;
+    if (t->last_compute_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_compute, 0));
+    if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));
     std::map<LoraKey, std::vector<LoraTargetDev>> groups;
     for (size_t i = 0; i < f->slots.size(); ++i) {
         const int32_t slot = f->slots[i];

@@ -160,3 +160,55 @@ def test_fp32_all_2_to_32_patterns_device_resident(orc, G):
         u = (np.arange(n, dtype=np.uint64) + (hi << 26)).astype(np.uint32)
         want = orc.convert_to_bf16(u.view(np.float32))
         assert np.array_equal(got, want), "block %d" % hi
+
+
+def test_one_stream_for_everything_and_null_stream(orc, G):
+    """copy_stream == compute_stream, and the null stream, are legal."""
+    w = wl_mod.tiny_stack(host_dtype=wl_mod.F16, with_norms=True)
+    arrays = {i: wl_mod.draw_tensor(w, i) for i in range(len(w.tensors))}
+    for use_null in (False, True):
+        with G.Template(w.shapes, chunk_bytes=64 << 10) as T:
+            s = None if use_null else T.compute_stream
+            keep = [G.pinned_like(np.ascontiguousarray(a)) for a in arrays.values()]
+            srcs = [(i, tb.dtype_code(v), tb.host_ptr(v)) for i, (_, v) in zip(arrays.keys(), keep)]
+            tb.tidal_materialize(T.h, srcs, s, s)
+            T.sync()
+            _compare_all_slots(orc, T, w.shapes, arrays)
+
+
+def test_lora_on_another_stream_waits_for_the_materialisation(orc, G):
+    """attach issued on a third stream right after an asynchronous materialisation, no host sync in
+    between: the library orders the two on the GPU."""
+    rng = np.random.default_rng(3)
+    shapes = [(512, 1024)] * 6
+    arrays = {i: rng.normal(0, 0.02, shapes[i]).astype(np.float16) for i in range(6)}
+    A = rng.normal(0, 0.05, (8, 1024)).astype(np.float16)
+    B = rng.normal(0, 0.05, (512, 8)).astype(np.float16)
+    with G.Template(shapes, chunk_bytes=64 << 10, max_adapter_bytes=1 << 20,
+                    flags=tb.TIDAL_FLAG_ORDERED_ACCUM | tb.TIDAL_FLAG_ASYNC_ENQUEUE) as T:
+        T.arena.fill_(0x77)
+        keep = [G.pinned_like(a) for a in arrays.values()]
+        srcs = [(i, tb.TIDAL_F16, tb.host_ptr(v)) for i, (_, v) in enumerate(keep)]
+        other = torch.cuda.Stream()
+        tb.tidal_materialize(T.h, srcs, T.copy_stream, T.compute_stream)
+        tb.tidal_lora_attach(T.h, tb.targets_from_arrays([(i, 16.0, A, B) for i in range(6)]), other)
+        other.synchronize()
+        T.sync()
+        merged = []
+        for i in range(6):
+            want = orc.convert_to_bf16(arrays[i])
+            orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 16.0, +1)
+            assert np.array_equal(T.slot(i), want), i
+            merged.append(want)
+        # the other direction: a materialisation right behind a LoRA call on another stream
+        tb.tidal_lora_detach(T.h, other)
+        tb.tidal_materialize(T.h, srcs[:3], T.copy_stream, T.compute_stream)
+        other.synchronize()
+        T.sync()
+        for i in range(6):
+            if i < 3:
+                want = orc.convert_to_bf16(arrays[i])
+            else:
+                want = merged[i].copy()
+                orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 16.0, -1)
+            assert np.array_equal(T.slot(i), want), i
