@@ -233,3 +233,34 @@ def test_prefetch_rule_and_resident_prefix_match_oracle(orc):
             assert b >= min(pre, w.source_bytes)
     finally:
         tb.tidal_template_destroy(t)
+
+
+def test_copy_plan_property_fuzz():
+    """Random slot lists, dtypes, chunk sizes, coalescing thresholds and pinned-ness: the plan always
+    covers every element once, in order, within the buffer limits (hypothesis)."""
+    hyp = pytest.importorskip("hypothesis")
+    st = hyp.strategies
+
+    @hyp.settings(max_examples=150, deadline=None)
+    @hyp.given(shapes=st.lists(st.tuples(st.integers(0, 700), st.integers(0, 900)), min_size=1, max_size=24),
+               dtype=st.sampled_from([tb.TIDAL_F32, tb.TIDAL_F16, tb.TIDAL_BF16]),
+               chunk_kib=st.integers(64, 512), coalesce_log=st.integers(0, 16), pinned=st.booleans(),
+               skip=st.integers(0, 5))
+    def run(shapes, dtype, chunk_kib, coalesce_log, pinned, skip):
+        chunk = -(-(chunk_kib << 10) // 4096) * 4096
+        coalesce = 1 << coalesce_log
+        cfg = tb.make_config(chunk_bytes=chunk, coalesce_bytes=coalesce)
+        t = tb.tidal_template_create(shapes, FAKE_ARENA, 1 << 40, cfg)
+        try:
+            used = [i for i in range(len(shapes)) if (i + skip) % 6 != 0]
+            srcs = [(i, dtype, 0x1000 + 64 * i) for i in used]
+            plan = tb.tidal_materialize_plan(t, srcs, assume_pinned=int(pinned))
+            sub = [shapes[i] if i in used else (0, 0) for i in range(len(shapes))]
+            if any(r * c for r, c in sub):
+                _check_plan(plan, sub, [dtype] * len(shapes), chunk, coalesce, pinned)
+            else:
+                assert plan == []
+        finally:
+            tb.tidal_template_destroy(t)
+
+    run()

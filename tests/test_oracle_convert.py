@@ -150,3 +150,24 @@ def test_convert_dispatch_fp16_and_bf16_passthrough(orc):
     assert orc.convert_to_bf16(np.array([0x3C0C], np.uint16).view(np.float16))[0] == 0x3F82  # 1+12/1024 tie -> even (up)
     assert orc.convert_to_bf16(np.array([0x3C05], np.uint16).view(np.float16))[0] == 0x3F81
     assert np.array_equal(orc.convert_to_bf16(h), h)                 # uint16 = bf16 bits: copied
+
+
+def test_bf16_rounding_all_2_to_32_patterns_vs_torch(orc):
+    """Every binary32 pattern against an independent library conversion (torch CPU), 2^26 at a
+    time.  NaN inputs: the library may canonicalise the payload, so only NaN-ness is compared there
+    (the payload rule is pinned by the golden table and the by-value test above)."""
+    torch = pytest.importorskip("torch")
+    n = 1 << 26
+    base = np.arange(n, dtype=np.uint32)
+    for hi in range(64):
+        u = base + np.uint32(hi << 26)
+        x = u.view(np.float32)
+        got = orc.convert_to_bf16(x)
+        want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        nan = (u & 0x7FFFFFFF) > 0x7F800000
+        if nan.any():
+            assert np.array_equal(got[~nan], want[~nan]), hi
+            assert np.all((got[nan] & 0x7F80) == 0x7F80) and np.all((got[nan] & 0x007F) != 0)
+            assert np.array_equal(got[nan], ((u[nan] >> 16) | 0x40).astype(np.uint16))
+        else:
+            assert np.array_equal(got, want), hi
