@@ -18,9 +18,11 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtidal.so")
 
-SOURCES = ["tidal.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip"]
+SOURCES = ["tidal.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip", "lora_lds_kernel.hip"]
+# per-file extras: the LDS swap kernel wants its MFMA results in VGPRs (see the file's header)
+EXTRA_FLAGS = {"lora_lds_kernel.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 HEADERS = [os.path.join(ROOT, "include", "tidal.h"), os.path.join(CSRC, "tidal_internal.h"),
-           os.path.join(CSRC, "plan.h")]
+           os.path.join(CSRC, "plan.h"), os.path.join(CSRC, "lora_device.h")]
 
 # -packed-fp32-ops off: packed fp32 VALU forms are not to be generated on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
@@ -40,7 +42,7 @@ def _compile(src: str, force: bool) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
     if force or _stale(obj, [path, *HEADERS]):
-        cmd = ["hipcc", *FLAGS, "-c", path, "-o", obj]
+        cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", path, "-o", obj]
         p = subprocess.run(cmd, capture_output=True, text=True)
         # the host pass does not know the gfx feature name and says so; that is expected
         err = "\n".join(l for l in p.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -53,7 +55,7 @@ def _compile(src: str, force: bool) -> str:
 
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=5) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
     if force or _stale(LIB, objs):
         tmp = LIB + ".tmp%d" % os.getpid()

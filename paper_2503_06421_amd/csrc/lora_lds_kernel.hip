@@ -1,0 +1,125 @@
+// LoRA fused swap for the largest ranks (64 -> 64): A strips staged in LDS.  gfx950 only.
+//
+// This file is compiled with -mllvm -amdgpu-mfma-vgpr-form: the MFMA results land in ordinary
+// VGPRs, which saves one accumulator-read instruction per element and, here, lets two waves
+// share a SIMD (measured 6.4 instead of 5.3 TB/s).  The other LoRA kernels are faster with the
+// accumulators in AGPRs and stay in their own translation unit.
+#include "lora_device.h"
+
+namespace tidal {
+
+// Variant for large ranks.  With 64 + 64 ranks the A strips of both adapters would need 256
+// VGPRs per lane; instead the four waves of a workgroup share ONE column strip, stage its A
+// operands once in LDS -- already in MFMA operand order, so every later read is a linear,
+// conflict-free 16-byte-per-lane ds_read -- and take interleaved 32-row blocks of the same
+// row range.  Registers then hold only the accumulators and W, which buys a second or third
+// wave per SIMD exactly where the arithmetic per block is largest.
+template <int NT, int KS>
+__device__ __forceinline__ void delta_tile_lds(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
+                                               const bf16x8* strip, f32x16 (&acc)[NT]) {
+    int m = i0 + (lane & 31);
+    m = m < out ? m : out - 1;
+    const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
+    bf16x8 aop[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+#pragma unroll
+    for (int T = 0; T < NT; ++T) {
+        f32x16 c = {0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[(T * KS + ks) * 64 + lane], c, 0, 0, 0);
+        acc[T] = c;
+    }
+}
+
+template <int NT, int KS>
+__device__ __forceinline__ void stage_strip(const uint16_t* __restrict__ At, int in, int j0, int lane, int wave,
+                                            bf16x8* strip) {
+    const int n = lane & 31, kg = lane >> 5;
+    for (int p = wave; p < NT * KS; p += 4) {
+        const int T = p / KS, ks = p - T * KS;
+        int j = j0 + NT * n + T;
+        j = j < in ? j : in - 1;
+        strip[p * 64 + lane] = *as_global((const bf16x8*)(At + (int64_t)j * (16 * KS) + 16 * ks + 8 * kg));
+    }
+}
+
+template <int NT, int KS0, int KS1>
+__global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraBatch batch, int out,
+                                                            int in, int strips, int rowblocks, int rcb,
+                                                            int blocks_per_target, int total_blocks) {
+    __shared__ bf16x8 strip_lds[(KS0 + KS1) * NT * 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= total_blocks) return;                        // whole workgroup leaves together
+    const int target = L / blocks_per_target;
+    const int item = L - target * blocks_per_target;
+    const int rowchunk = item / strips;
+    const int strip = item - rowchunk * strips;
+    const int j0 = strip * (32 * NT);
+
+    const LoraTargetDev d = batch.t[target];
+    uint16_t* __restrict__ W = (uint16_t*)(batch.w_base + (size_t)d.w * kLoraUnit);
+    const uint16_t* At_old = (const uint16_t*)(batch.old_base + (size_t)d.at_old * kLoraUnit);
+    const uint16_t* Bp_old = (const uint16_t*)(batch.old_base + (size_t)d.bp_old * kLoraUnit);
+    const uint16_t* At_new = (const uint16_t*)(batch.new_base + (size_t)d.at_new * kLoraUnit);
+    const uint16_t* Bp_new = (const uint16_t*)(batch.new_base + (size_t)d.bp_new * kLoraUnit);
+    if constexpr (KS0 > 0) stage_strip<NT, KS0>(At_old, in, j0, lane, wave, strip_lds);
+    if constexpr (KS1 > 0) stage_strip<NT, KS1>(At_new, in, j0, lane, wave, strip_lds + KS0 * NT * 64);
+    __syncthreads();
+
+    const int n = lane & 31, h = lane >> 5;
+    const int jl = j0 + NT * n;
+    const bool strip_full = (j0 + 32 * NT <= in) && (in % NT == 0);
+    const int rb_end = (rowchunk + 1) * rcb < rowblocks ? (rowchunk + 1) * rcb : rowblocks;
+    for (int rb = rowchunk * rcb + wave; rb < rb_end; rb += 4) {
+        const int i0 = rb * 32;
+        const bool full = strip_full && (i0 + 32 <= out);
+        uint32_t w[16][NT / 2];
+        load_block<NT>(W, out, in, i0, jl, h, full, w);
+        f32x16 acc[NT];
+        if constexpr (KS0 > 0) {
+            delta_tile_lds<NT, KS0>(Bp_old, out, i0, lane, strip_lds, acc);
+            apply_tile<NT>(w, acc, d.s_old);
+        }
+        if constexpr (KS1 > 0) {
+            delta_tile_lds<NT, KS1>(Bp_new, out, i0, lane, strip_lds + KS0 * NT * 64, acc);
+            apply_tile<NT>(w, acc, d.s_new);
+        }
+        store_block<NT>(W, out, in, i0, jl, h, full, w);
+    }
+}
+
+template <int NT, int KS0, int KS1>
+static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
+    const int strips = (g.in + 32 * NT - 1) / (32 * NT);
+    const int rowblocks = (g.out + 31) / 32;
+    const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
+    int rc = 16;                                     // 32-row blocks per wave
+    const int64_t by_size = tiles / 4096;
+    if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
+    if (const char* e = getenv("TIDAL_MFMA_RC")) {   // tuning runs only
+        const int v = atoi(e);
+        if (v >= 1 && v <= 1024) rc = v;
+    }
+    const int rcb = 4 * rc;
+    const int rowchunks = (rowblocks + rcb - 1) / rcb;
+    const int blocks_per_target = strips * rowchunks;
+    const int64_t total = (int64_t)blocks_per_target * g.n_targets;
+    if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((total + 7) / 8 * 8);
+    hipLaunchKernelGGL((lora_mfma_lds_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
+                       g.in, strips, rowblocks, rcb, blocks_per_target, (int)total);
+    return hipGetLastError();
+}
+
+
+hipError_t launch_lora_mfma_lds(const LoraGroup& g, hipStream_t stream) {
+    if (g.rp_old == 64 && g.rp_new == 64) return launch_mfma_lds_inst<8, 4, 4>(g, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace tidal
