@@ -223,3 +223,37 @@ uint64_t orc_slot_checksum(const uint16_t* slot, int64_t elems, int32_t passes) 
     for (i = 0; i < elems; ++i) s += slot[i];
     return s * (uint64_t)passes;
 }
+
+/* ---------------------------------------------------------------------------
+ * Unmerged adapter (the paper's dynamic function keeps LoRA adapters as separate
+ * weights next to the shared base model, Sec. 3 programming interface and Sec. 5.2):
+ * for tokens t0 <= t < t1 that use this adapter,
+ *     u[t][k] = bf16( sum_j A[k][j] * X[t][j] )            (fp32 chain, j ascending;
+ *                                                           the intermediate is stored in the
+ *                                                           activation type, bf16)
+ *     Y[t][i] = bf16( Y[t][i] + (alpha/r) * sum_k B[i][k] * u[t][k] )   (fp32 chain, k ascending,
+ *                                                           one fused multiply-add with Y, one rounding)
+ * X is T x in, Y is T x out, A is r x in, B is out x r; all bf16, row-major.
+ * ------------------------------------------------------------------------- */
+void orc_lora_apply(const uint16_t* X, uint16_t* Y, int64_t in, int64_t out, const uint16_t* A,
+                    const uint16_t* B, int32_t r, float alpha, int64_t t0, int64_t t1) {
+    int64_t t, i, j;
+    int32_t k;
+    float s;
+    float u[64];
+    if (r == 0 || alpha == 0.0f) return;
+    s = alpha / (float)r;
+    for (t = t0; t < t1; ++t) {
+        for (k = 0; k < r; ++k) {
+            float acc = 0.0f;
+            for (j = 0; j < in; ++j)
+                acc = fmaf(bf16_to_float(A[(int64_t)k * in + j]), bf16_to_float(X[t * in + j]), acc);
+            u[k] = bf16_to_float(float_to_bf16(acc));
+        }
+        for (i = 0; i < out; ++i) {
+            float acc = 0.0f;
+            for (k = 0; k < r; ++k) acc = fmaf(bf16_to_float(B[i * (int64_t)r + k]), u[k], acc);
+            Y[t * out + i] = float_to_bf16(fmaf(s, acc, bf16_to_float(Y[t * out + i])));
+        }
+    }
+}

@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.orc_resident_prefix.argtypes = [vp, vp, i32, ctypes.c_uint64]
         L.orc_slot_checksum.restype = ctypes.c_uint64
         L.orc_slot_checksum.argtypes = [vp, i64, i32]
+        L.orc_lora_apply.restype = None
+        L.orc_lora_apply.argtypes = [vp, vp, i64, i64, vp, vp, i32, f32, i64, i64]
         _lib = L
     return _lib
 
@@ -182,3 +184,15 @@ def resident_prefix(shapes, prefetch: int) -> int:
 def slot_checksum(bits: np.ndarray, passes: int = 1) -> int:
     bits = np.ascontiguousarray(bits, dtype=np.uint16)
     return lib().orc_slot_checksum(_ptr(bits), bits.size, passes)
+
+
+def lora_apply(X: np.ndarray, Y: np.ndarray, A: np.ndarray, B: np.ndarray, alpha: float, t0: int, t1: int) -> None:
+    """Y[t0:t1] += (alpha/r) * B (A x) for the tokens of one segment, in place.  All arrays are bf16
+    bit patterns: X (T, in), Y (T, out), A (r, in), B (out, r)."""
+    r = A.shape[0]
+    assert r <= 64
+    for a in (X, Y, A, B):
+        assert a.dtype == np.uint16 and a.flags.c_contiguous
+    assert A.shape == (r, X.shape[1]) and B.shape == (Y.shape[1], r) and X.shape[0] == Y.shape[0]
+    assert 0 <= t0 <= t1 <= X.shape[0]
+    lib().orc_lora_apply(_ptr(X), _ptr(Y), X.shape[1], Y.shape[1], _ptr(A), _ptr(B), r, float(alpha), t0, t1)
