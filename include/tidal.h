@@ -200,8 +200,11 @@ int tidal_lora_swap(tidal_template* t, const tidal_lora_target* targets_new /* [
 int tidal_lora_detach(tidal_template* t, void* stream);
 
 /* Resident adapters: the packed bf16 device copy lives in caller-owned device memory, so
- * attach / swap move no host data (multi-tenant pools of adapters kept on the GPU).
- * tidal_adapter_required_bytes returns 0 on invalid arguments. */
+ * attach / swap move no host data (multi-tenant pools of adapters kept on the GPU).  A resident
+ * adapter holds, per target, A transposed (in x rp) and B (out x rp), zero padded to
+ * rp = 16, 32 or 64 ranks, plus A row-major (r x in) for tidal_lora_apply; the in-arena copy of
+ * tidal_lora_attach / _swap holds only the first two, so this size also bounds
+ * max_adapter_bytes.  tidal_adapter_required_bytes returns 0 on invalid arguments. */
 size_t tidal_adapter_required_bytes(const tidal_template* t, const tidal_lora_target* targets /* [host] */,
                                     int32_t n_targets);
 int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* targets /* [host] */,
@@ -211,6 +214,33 @@ int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* targets /* 
 int tidal_adapter_destroy(tidal_adapter* a);   /* must not be attached */
 int tidal_lora_attach_adapter(tidal_template* t, const tidal_adapter* a, void* stream);
 int tidal_lora_swap_adapter(tidal_template* t, const tidal_adapter* a_new, void* stream);
+
+/* Unmerged adapters for mixed batches.  The paper's dynamic function keeps a request's LoRA
+ * adapter as weights of its own next to the shared base model (Sec. 3, programming interface;
+ * Sec. 5.2, adaptive template state reusing), which is what lets requests with different adapters
+ * share one batch: the base projection runs once for all tokens and each request's tokens get
+ *     y[t] <- bf16( y[t] + (alpha/r) * B * bf16( A * x[t] ) )         (fp32 accumulation)
+ * from their own adapter.  tidal_lora_apply does that for one LoRA target slot (out x in): x is
+ * n_tokens x in and y is n_tokens x out, both bf16 row-major device memory; y holds the base
+ * projection's output and is updated in place.  Segment i gives tokens [token_begin, token_end)
+ * to adapters[adapter] (adapter < 0, r = 0 or alpha = 0: tokens left as they are).  Segments must
+ * not overlap.  Every adapter must be resident (tidal_adapter_upload on this template) and list
+ * `slot` among its targets; in and out must be multiples of 8; x and y 16-byte aligned.  Nothing here
+ * touches the template's weights, so it may run while an adapter is merged, and attach state is
+ * not changed.  `workspace` is caller-owned device memory of at least
+ * tidal_lora_apply_workspace_bytes(n_tokens) bytes, 256-byte aligned, used only during the call's
+ * kernels (the rank-space intermediate bf16(A x)); calls that share a workspace must be ordered on
+ * one stream.  Kernels are enqueued on `stream` after the adapters' uploads. */
+typedef struct tidal_lora_segment {
+    int32_t adapter;       /* index into adapters[], or < 0 for "no adapter" */
+    int32_t token_begin;   /* first token row of the segment                 */
+    int32_t token_end;     /* one past the last token row                    */
+} tidal_lora_segment;
+size_t tidal_lora_apply_workspace_bytes(int32_t n_tokens);
+int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_adapter* const* adapters /* [host] */,
+                     int32_t n_adapters, const tidal_lora_segment* segments /* [host] */, int32_t n_segments,
+                     const void* x /* [device] */, void* y /* [device] in/out */, int32_t n_tokens,
+                     void* workspace /* [device] */, size_t workspace_bytes, void* stream);
 
 /* Copy-on-write forks (Sec. 1: a template must stay request-agnostic, "a copy-on-write
  * mechanism is critical for safe template sharing"; Sec. 5.2: a write to a forked weight goes

@@ -28,7 +28,8 @@ EXPORTS = [
     "tidal_config_default", "tidal_template_required_bytes", "tidal_template_create", "tidal_materialize",
     "tidal_materialize_plan", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
-    "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_fork_required_bytes", "tidal_fork_create",
+    "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_lora_apply_workspace_bytes", "tidal_lora_apply",
+    "tidal_fork_required_bytes", "tidal_fork_create",
     "tidal_fork_apply", "tidal_fork_slot_ptr", "tidal_fork_destroy", "tidal_template_slot_ptr",
     "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
     "tidal_convert_device", "tidal_h2d_peak", "tidal_get_stats",
@@ -47,6 +48,10 @@ class tidal_src(Structure):
 class tidal_lora_target(Structure):
     _fields_ = [("slot", c_int32), ("r", c_int32), ("alpha", c_float), ("dtype", c_int32),
                 ("A", c_void_p), ("B", c_void_p)]
+
+
+class tidal_lora_segment(Structure):
+    _fields_ = [("adapter", c_int32), ("token_begin", c_int32), ("token_end", c_int32)]
 
 
 class tidal_config(Structure):
@@ -111,6 +116,10 @@ def lib() -> ctypes.CDLL:
     L.tidal_adapter_destroy.argtypes = [vp]
     L.tidal_lora_attach_adapter.argtypes = [vp, vp, vp]
     L.tidal_lora_swap_adapter.argtypes = [vp, vp, vp]
+    L.tidal_lora_apply_workspace_bytes.restype = c_size_t
+    L.tidal_lora_apply_workspace_bytes.argtypes = [c_int32]
+    L.tidal_lora_apply.argtypes = [vp, c_int32, POINTER(vp), c_int32, POINTER(tidal_lora_segment), c_int32, vp, vp,
+                                   c_int32, vp, c_size_t, vp]
     L.tidal_fork_required_bytes.restype = c_size_t
     L.tidal_fork_required_bytes.argtypes = [vp, POINTER(c_int32), c_int32]
     L.tidal_fork_create.argtypes = [vp, POINTER(c_int32), c_int32, vp, c_size_t, POINTER(vp)]
@@ -298,6 +307,21 @@ def tidal_lora_attach_adapter(t, a, stream=None) -> None:
 
 def tidal_lora_swap_adapter(t, a, stream=None) -> None:
     _check(lib().tidal_lora_swap_adapter(t, a, stream_ptr(stream)))
+
+
+def tidal_lora_apply_workspace_bytes(n_tokens: int) -> int:
+    return lib().tidal_lora_apply_workspace_bytes(n_tokens)
+
+
+def tidal_lora_apply(t, slot: int, adapters, segments, x, y, n_tokens: int, workspace, workspace_bytes: int,
+                     stream=None) -> None:
+    """segments: iterable of (adapter index, token_begin, token_end)."""
+    adapters = list(adapters)
+    segments = list(segments)
+    aarr = (c_void_p * max(1, len(adapters)))(*adapters)
+    sarr = (tidal_lora_segment * max(1, len(segments)))(*[tidal_lora_segment(a, b, e) for a, b, e in segments])
+    _check(lib().tidal_lora_apply(t, slot, aarr, len(adapters), sarr, len(segments), device_ptr(x), device_ptr(y),
+                                  n_tokens, device_ptr(workspace), workspace_bytes, stream_ptr(stream)))
 
 
 def _slot_list(slots):

@@ -18,7 +18,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtidal.so")
 
-SOURCES = ["tidal.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip", "lora_lds_kernel.hip"]
+SOURCES = ["tidal.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip", "lora_lds_kernel.hip",
+           "lora_apply_kernels.hip"]
 # per-file extras: the LDS swap kernel wants its MFMA results in VGPRs (see the file's header)
 EXTRA_FLAGS = {"lora_lds_kernel.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 HEADERS = [os.path.join(ROOT, "include", "tidal.h"), os.path.join(CSRC, "tidal_internal.h"),
@@ -55,7 +56,7 @@ def _compile(src: str, force: bool) -> str:
 
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
     if force or _stale(LIB, objs):
         tmp = LIB + ".tmp%d" % os.getpid()

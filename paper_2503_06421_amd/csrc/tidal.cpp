@@ -43,11 +43,14 @@ static int fail(int code, const char* fmt, ...) {
 // ---------------------------------------------------------------------------------------
 namespace {
 
+constexpr size_t kNoOffset = ~(size_t)0;
+
 struct PackedTarget {
     int32_t slot;
     int32_t r, rp;
     float alpha;
     size_t at_off, bp_off;   // byte offsets of At (in x rp) and Bp (out x rp) in the adapter memory
+    size_t ar_off;           // byte offset of A row-major (r x in), or kNoOffset if not kept
     bool active() const { return r > 0 && alpha != 0.0f; }
 };
 
@@ -526,8 +529,10 @@ extern "C" int tidal_template_slot_wait(tidal_template* t, int32_t slot, void* s
 // ---------------------------------------------------------------------------------------
 // adapters: validation, packed layout, upload
 // ---------------------------------------------------------------------------------------
+// keep_rows: also reserve A in row-major form (resident adapters: the unmerged apply contracts
+// over the input width and wants A's rows contiguous).
 static int validate_targets(const tidal_template* t, const tidal_lora_target* tg, int32_t n, bool need_host,
-                            AdapterRec* rec) {
+                            AdapterRec* rec, bool keep_rows = false) {
     if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
     if (n < 0 || (!tg && n > 0)) return fail(TIDAL_E_INVAL, "bad target list (n=%d)", n);
     rec->targets.clear();
@@ -552,6 +557,7 @@ static int validate_targets(const tidal_template* t, const tidal_lora_target* tg
         p.rp = padded_rank(g.r);
         p.alpha = g.alpha;
         p.at_off = p.bp_off = 0;
+        p.ar_off = kNoOffset;
         if (p.active() && s.elems > 0) {
             if (!dtype_ok(g.dtype)) return fail(TIDAL_E_INVAL, "target %d: unknown dtype %d", i, g.dtype);
             if (need_host && (!g.A || !g.B)) return fail(TIDAL_E_INVAL, "target %d: A or B is NULL", i);
@@ -559,6 +565,10 @@ static int validate_targets(const tidal_template* t, const tidal_lora_target* tg
             off = align_up(off + 2 * (size_t)s.cols * p.rp, kSlotAlign);
             p.bp_off = off;
             off = align_up(off + 2 * (size_t)s.rows * p.rp, kSlotAlign);
+            if (keep_rows && s.cols % 8 == 0) {
+                p.ar_off = off;
+                off = align_up(off + 2 * (size_t)s.cols * p.r, kSlotAlign);
+            }
         }
         rec->targets.push_back(p);
     }
@@ -576,14 +586,16 @@ static int check_materialised(const tidal_template* t, const AdapterRec& rec) {
 extern "C" size_t tidal_adapter_required_bytes(const tidal_template* t, const tidal_lora_target* targets,
                                                int32_t n_targets) {
     AdapterRec rec;
-    if (validate_targets(t, targets, n_targets, false, &rec)) return 0;
+    if (validate_targets(t, targets, n_targets, false, &rec, true)) return 0;
     return rec.bytes ? rec.bytes : kSlotAlign;
 }
 
 // Stage A and B of every active target through the staging buffers and pack them into
 // rec.dev on `stream`.
 static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t stream) {
-    struct Job { const char* host; size_t bytes; PackSegment seg; bool pinned; };
+    // A job is one factor staged once; A may be packed twice (transposed and, as a plain
+    // conversion written as lines of 8, row-major)
+    struct Job { const char* host; size_t bytes; PackSegment seg; bool pinned; bool has2; PackSegment seg2; };
     std::vector<Job> jobs;
     for (size_t i = 0; i < rec.targets.size(); ++i) {
         const PackedTarget& p = rec.targets[i];
@@ -591,9 +603,13 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
         if (!p.active() || s.elems == 0) continue;
         const size_t isz = dtype_size(tg[i].dtype);
         Job a{(const char*)tg[i].A, (size_t)p.r * (size_t)s.cols * isz,
-              PackSegment{nullptr, rec.dev + p.at_off, s.cols, p.r, p.rp, tg[i].dtype, 1}, false};
+              PackSegment{nullptr, rec.dev + p.at_off, s.cols, p.r, p.rp, tg[i].dtype, 1}, false, false, {}};
+        if (p.ar_off != kNoOffset) {
+            a.has2 = true;
+            a.seg2 = PackSegment{nullptr, rec.dev + p.ar_off, (int64_t)p.r * s.cols / 8, 8, 8, tg[i].dtype, 0};
+        }
         Job b{(const char*)tg[i].B, (size_t)p.r * (size_t)s.rows * isz,
-              PackSegment{nullptr, rec.dev + p.bp_off, s.rows, p.r, p.rp, tg[i].dtype, 0}, false};
+              PackSegment{nullptr, rec.dev + p.bp_off, s.rows, p.r, p.rp, tg[i].dtype, 0}, false, false, {}};
         if (a.bytes > t->cfg.chunk_bytes || b.bytes > t->cfg.chunk_bytes)
             return fail(TIDAL_E_INVAL, "target %zu: a LoRA factor is larger than chunk_bytes", i);
         jobs.push_back(a);
@@ -611,10 +627,12 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
         size_t fill = 0, j = i;
         bool need_bounce = false;
         std::vector<size_t> offs;
-        while (j < jobs.size() && (int)(j - i) < kMaxPackSeg) {
+        int segs = 0;
+        while (j < jobs.size() && segs + (jobs[j].has2 ? 2 : 1) <= kMaxPackSeg) {
             size_t off = align_up(fill, kSlotAlign);
             if (off + jobs[j].bytes > t->cfg.chunk_bytes) break;
             offs.push_back(off);
+            segs += jobs[j].has2 ? 2 : 1;
             fill = off + jobs[j].bytes;
             need_bounce |= !jobs[j].pinned || jobs[j].bytes < t->cfg.coalesce_bytes;
             ++j;
@@ -631,6 +649,10 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
             if (rc) return rc;
             job.seg.src = dst;
             batch.seg[nseg++] = job.seg;
+            if (job.has2) {
+                job.seg2.src = dst;
+                batch.seg[nseg++] = job.seg2;
+            }
         }
         rc = pl.copies_done(b, need_bounce, true);
         if (rc) return rc;
@@ -648,7 +670,7 @@ extern "C" int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* 
     if (!out) return fail(TIDAL_E_INVAL, "out is NULL");
     *out = nullptr;
     AdapterRec rec;
-    int rc = validate_targets(t, targets, n_targets, true, &rec);
+    int rc = validate_targets(t, targets, n_targets, true, &rec, true);
     if (rc) return rc;
     if (!dev_mem) return fail(TIDAL_E_INVAL, "dev_mem is NULL");
     if ((uintptr_t)dev_mem % kSlotAlign) return fail(TIDAL_E_INVAL, "dev_mem is not 256-byte aligned");
@@ -839,6 +861,96 @@ extern "C" int tidal_lora_attach_adapter(tidal_template* t, const tidal_adapter*
 
 extern "C" int tidal_lora_swap_adapter(tidal_template* t, const tidal_adapter* a_new, void* stream) {
     return attach_resident(t, a_new, stream, true);
+}
+
+// ---------------------------------------------------------------------------------------
+// unmerged adapters applied to a mixed batch
+// ---------------------------------------------------------------------------------------
+extern "C" size_t tidal_lora_apply_workspace_bytes(int32_t n_tokens) {
+    if (n_tokens <= 0) return kSlotAlign;
+    return align_up((size_t)n_tokens * kApplyRankStride * 2, kSlotAlign);
+}
+
+extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_adapter* const* adapters,
+                                int32_t n_adapters, const tidal_lora_segment* segs, int32_t n_segs, const void* x,
+                                void* y, int32_t n_tokens, void* workspace, size_t workspace_bytes, void* stream_) {
+    if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
+    if (slot < 0 || slot >= (int32_t)t->slots.size()) return fail(TIDAL_E_INVAL, "slot %d out of range", slot);
+    if (n_adapters < 0 || (!adapters && n_adapters > 0)) return fail(TIDAL_E_INVAL, "bad adapter list");
+    if (n_segs < 0 || (!segs && n_segs > 0)) return fail(TIDAL_E_INVAL, "bad segment list");
+    if (n_tokens < 0) return fail(TIDAL_E_INVAL, "n_tokens is negative");
+    const SlotState& st = t->slots[slot];
+    if (st.rows > 0x7FFFFFFF || st.cols > 0x7FFFFFFF) return fail(TIDAL_E_INVAL, "slot %d is too large", slot);
+    const int out = (int)st.rows, in = (int)st.cols;
+    if (st.elems > 0 && (in % 8 || out % 8))
+        return fail(TIDAL_E_INVAL, "slot %d is %d x %d: both must be multiples of 8", slot, out, in);
+    // per adapter: its entry for this slot
+    std::vector<const PackedTarget*> entry((size_t)n_adapters, nullptr);
+    for (int32_t a = 0; a < n_adapters; ++a) {
+        if (!adapters[a]) return fail(TIDAL_E_INVAL, "adapter %d is NULL", a);
+        if (adapters[a]->owner != t) return fail(TIDAL_E_INVAL, "adapter %d belongs to another template", a);
+        for (const PackedTarget& p : adapters[a]->rec.targets)
+            if (p.slot == slot) entry[a] = &p;
+        if (!entry[a]) return fail(TIDAL_E_INVAL, "adapter %d does not target slot %d", a, slot);
+    }
+    // segments: in range, disjoint
+    std::vector<std::pair<int32_t, int32_t>> spans;
+    for (int32_t i = 0; i < n_segs; ++i) {
+        const tidal_lora_segment& g = segs[i];
+        if (g.token_begin < 0 || g.token_end < g.token_begin || g.token_end > n_tokens)
+            return fail(TIDAL_E_INVAL, "segment %d: tokens [%d, %d) outside 0..%d", i, g.token_begin, g.token_end,
+                        n_tokens);
+        if (g.adapter >= n_adapters) return fail(TIDAL_E_INVAL, "segment %d: adapter %d out of range", i, g.adapter);
+        if (g.token_end > g.token_begin) spans.push_back({g.token_begin, g.token_end});
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i].first < spans[i - 1].second)
+            return fail(TIDAL_E_INVAL, "segments overlap at token %d", spans[i].first);
+
+    std::vector<ApplyTile> tiles;
+    for (int32_t i = 0; i < n_segs; ++i) {
+        const tidal_lora_segment& g = segs[i];
+        if (g.adapter < 0 || g.token_end == g.token_begin || st.elems == 0) continue;
+        const PackedTarget* p = entry[g.adapter];
+        if (!p->active()) continue;
+        if (p->ar_off == kNoOffset) return fail(TIDAL_E_STATE, "adapter %d holds no row-major A for slot %d", g.adapter, slot);
+        const char* base = adapters[g.adapter]->rec.dev;
+        for (int32_t t0 = g.token_begin; t0 < g.token_end; t0 += 32) {
+            ApplyTile tl;
+            tl.Ar = (const uint16_t*)(base + p->ar_off);
+            tl.Bp = (const uint16_t*)(base + p->bp_off);
+            tl.t0 = t0;
+            tl.rows = std::min(32, g.token_end - t0);
+            tl.s = p->alpha / (float)p->r;
+            tl.r = p->r;
+            tl.rp = p->rp;
+            tl.pad_ = 0;
+            tiles.push_back(tl);
+        }
+    }
+    if (tiles.empty()) return TIDAL_OK;
+    if (!x || !y) return fail(TIDAL_E_INVAL, "x or y is NULL");
+    if ((uintptr_t)x % 16 || (uintptr_t)y % 16) return fail(TIDAL_E_INVAL, "x and y must be 16-byte aligned");
+    if (!workspace || (uintptr_t)workspace % kSlotAlign) return fail(TIDAL_E_INVAL, "workspace is NULL or not 256-byte aligned");
+    if (workspace_bytes < tidal_lora_apply_workspace_bytes(n_tokens))
+        return fail(TIDAL_E_NOMEM, "workspace needs %zu bytes, got %zu", tidal_lora_apply_workspace_bytes(n_tokens),
+                    workspace_bytes);
+    int rc = ensure_device(t);
+    if (rc) return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));   // adapter uploads
+    for (size_t at = 0; at < tiles.size(); at += kMaxApplyTiles) {
+        const int n = (int)std::min(tiles.size() - at, (size_t)kMaxApplyTiles);
+        ApplyBatch b;
+        b.x = (const uint16_t*)x;
+        b.y = (uint16_t*)y;
+        b.u = (uint16_t*)workspace;
+        memcpy(b.tile, tiles.data() + at, (size_t)n * sizeof(ApplyTile));
+        HIP_TRY(launch_apply_shrink(b, n, in, stream));
+        HIP_TRY(launch_apply_expand(b, n, out, stream));
+    }
+    return TIDAL_OK;
 }
 
 extern "C" int tidal_lora_detach(tidal_template* t, void* stream) {

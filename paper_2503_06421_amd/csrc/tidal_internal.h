@@ -71,6 +71,30 @@ struct LoraGroup {
 hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream);
 hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream);
 
+// ---- unmerged adapter apply ---------------------------------------------------------------
+// One entry per tile of up to 32 consecutive tokens that share an adapter.  Adapters live in
+// separate caller-owned allocations, hence full pointers; 112 entries travel in the kernel
+// arguments, longer batches take several launches.
+struct ApplyTile {
+    const uint16_t* Ar;      // r x in bf16, A row-major
+    const uint16_t* Bp;      // out x rp bf16, zero padded
+    int32_t t0, rows;        // first token row, number of token rows (1..32)
+    float s;                 // alpha / r
+    int32_t r, rp;           // true and padded rank
+    int32_t pad_;
+};
+constexpr int kMaxApplyTiles = 112;
+constexpr int kApplyRankStride = 64;   // workspace elements reserved per token
+struct ApplyBatch {
+    const uint16_t* x;       // n_tokens x in
+    uint16_t* y;             // n_tokens x out
+    uint16_t* u;             // workspace: tile at u + t0 * kApplyRankStride, rows x rp bf16
+    ApplyTile tile[kMaxApplyTiles];   // 3584 bytes
+};
+// u = bf16(A x) for every tile, then y += s * B u.
+hipError_t launch_apply_shrink(const ApplyBatch& b, int n_tiles, int in, hipStream_t stream);
+hipError_t launch_apply_expand(const ApplyBatch& b, int n_tiles, int out, hipStream_t stream);
+
 inline int padded_rank(int r) { return r <= 0 ? 0 : (r <= 16 ? 16 : (r <= 32 ? 32 : 64)); }
 
 }  // namespace tidal

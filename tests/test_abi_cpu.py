@@ -110,7 +110,8 @@ def test_validation_happens_before_any_device_work(small_template):
     _expect(tb.TIDAL_E_STATE, tb.tidal_lora_detach, t)
     _expect(tb.TIDAL_E_STATE, tb.tidal_lora_attach, t, [ok])
     _expect(tb.TIDAL_E_STATE, tb.tidal_template_slot_wait, t, 0)
-    assert tb.tidal_adapter_required_bytes(t, [ok]) == 2 * 16 * 16 + 2 * 8 * 16
+    # At (16 x 16) + Bp (8 x 16) + row-major A (2 x 16 -> one 256-byte unit)
+    assert tb.tidal_adapter_required_bytes(t, [ok]) == 2 * 16 * 16 + 2 * 8 * 16 + 256
     assert tb.tidal_adapter_required_bytes(t, [(9,) + ok[1:]]) == 0
 
 
@@ -122,7 +123,7 @@ def test_adapter_too_large_for_region():
         A = np.zeros((4, 64), np.float32)
         B = np.zeros((64, 4), np.float32)
         # the size check comes after the materialised check, so look at the size directly
-        assert tb.tidal_adapter_required_bytes(t, [(0, 4, 8.0, tb.TIDAL_F32, A.ctypes.data, B.ctypes.data)]) == 4096
+        assert tb.tidal_adapter_required_bytes(t, [(0, 4, 8.0, tb.TIDAL_F32, A.ctypes.data, B.ctypes.data)]) == 4096 + 512
     finally:
         tb.tidal_template_destroy(t)
 
@@ -264,3 +265,19 @@ def test_copy_plan_property_fuzz():
             tb.tidal_template_destroy(t)
 
     run()
+
+
+def test_lora_apply_validates_segments_without_a_device():
+    t = tb.tidal_template_create([(64, 64)], FAKE_ARENA, 1 << 40, tb.make_config())
+    try:
+        assert tb.tidal_lora_apply_workspace_bytes(0) == 256
+        assert tb.tidal_lora_apply_workspace_bytes(3) == 512            # 3 tokens x 64 ranks x 2 bytes, 256-aligned
+        # no adapters: segments without an adapter are a no-op that needs no device
+        tb.tidal_lora_apply(t, 0, [], [(-1, 0, 4)], 0, 0, 8, 0, 0)
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_apply, t, 0, [], [(-1, 0, 5), (-1, 4, 8)], 0, 0, 8, 0, 0)
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_apply, t, 0, [], [(-1, 0, 9)], 0, 0, 8, 0, 0)
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_apply, t, 0, [], [(0, 0, 4)], 0, 0, 8, 0, 0)
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_apply, t, 1, [], [], 0, 0, 8, 0, 0)
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_apply, t, 0, [], [], 0, 0, -1, 0, 0)
+    finally:
+        tb.tidal_template_destroy(t)
