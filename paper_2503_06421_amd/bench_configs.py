@@ -1,7 +1,7 @@
 """Measurements of the other workload configurations (bench.py at the repository root times the
 Llama2-7B-shaped headline workload).
 
-    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging
+    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging|apply
 
 Each prints one JSON line.  Kernel times come from the library's HIP events around each launch
 (TIDAL_FLAG_KERNEL_TIMING); call-level times from events on the compute stream.
@@ -347,11 +347,88 @@ def bench_merging(args):
     return out
 
 
+def bench_apply(args):
+    """Unmerged adapters on mixed batches (the paper's dynamic function keeps adapters as separate
+    weights, Sec. 3 / Sec. 5.2): y += (alpha/r) B bf16(A x) on the 4096 x 4096 query projection of
+    32 layers, one call per layer, so that a pass touches 32 distinct sets of factors and
+    activations (more than the 256 MB Infinity Cache holds for the larger batches).  A pool of 32
+    adapters with ranks {8, 16, 32, 64} and Zipf(1.1) popularity, as in the churn configuration."""
+    layers, hidden = 32, 4096
+    ch = wl_mod.adapter_churn()
+    rng = np.random.default_rng(0)
+    shapes = [(hidden, hidden)] * layers
+    T = hz.DeviceTemplate(shapes, max_adapter_bytes=0)
+    out = {"config": "apply_q_proj_4096_x32_layers_pool32", "cases": []}
+    keep, handles = [], []
+    try:
+        host = {}
+        for r in sorted(set(ch.ranks)):
+            A = torch.empty((r, hidden), dtype=torch.float32, pin_memory=True)
+            B = torch.empty((hidden, r), dtype=torch.float32, pin_memory=True)
+            A.numpy()[...] = rng.normal(0, 0.02, (r, hidden))
+            B.numpy()[...] = rng.normal(0, 0.02, (hidden, r))
+            host[r] = (A, B)
+        for a, r in enumerate(ch.ranks):
+            A, B = host[r]
+            tg = [(s, r, ch.alphas[a], tb.TIDAL_F32, A.data_ptr(), B.data_ptr()) for s in range(layers)]
+            nb = tb.tidal_adapter_required_bytes(T.h, tg)
+            mem = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+            handles.append(tb.tidal_adapter_upload(T.h, tg, mem, nb, T.compute_stream))
+            keep.append(mem)
+        T.sync()
+        sched = ch.schedule
+
+        def requests(lengths):
+            segs, t = [], 0
+            for i, n in enumerate(lengths):
+                segs.append((sched[i % len(sched)], t, t + n))
+                t += n
+            return segs, t
+
+        cases = [("decode_64_requests_x1_token", [1] * 64), ("decode_256_requests_x1_token", [1] * 256),
+                 ("prefill_8_requests_x512_tokens", [512] * 8), ("mixed_4x512_prefill_plus_60_decode", [512] * 4 + [1] * 60),
+                 ("prompt_16384_tokens_one_adapter", [16384])]
+        for name, lengths in cases:
+            if args.case and args.case not in name:
+                continue
+            segs, n = requests(lengths)
+            X = [torch.randn((n, hidden), device="cuda:0").to(torch.bfloat16) for _ in range(layers)]
+            Y = [torch.randn((n, hidden), device="cuda:0").to(torch.bfloat16) for _ in range(layers)]
+            nb = tb.tidal_lora_apply_workspace_bytes(n)
+            ws = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+            used = sorted({a for a, _, _ in segs})
+            factor_bytes = sum(2 * (ch.ranks[a] * hidden + hidden * max(16, 1 << (ch.ranks[a] - 1).bit_length())) for a in used)
+            alg = n * hidden * 2 + n * hidden * 4 + factor_bytes       # x once, y read + written, factors once
+            best = None
+            for rep in range(args.reps + 1):
+                e0, e1 = ev(), ev()
+                e0.record(T.compute_stream)
+                for l in range(layers):
+                    tb.tidal_lora_apply(T.h, l, handles, segs, X[l], Y[l], n, ws, nb, T.compute_stream)
+                e1.record(T.compute_stream)
+                T.sync()
+                ms = e0.elapsed_time(e1) / layers
+                if rep > 0:
+                    best = ms if best is None else min(best, ms)
+            case = {"case": name, "tokens": n, "requests": len(lengths), "adapters_used": len(used),
+                    "us_per_layer_call": round(best * 1e3, 2), "algorithmic_MB": round(alg / 1e6, 3),
+                    "GBps": round(alg / best / 1e6, 1), "hbm_frac": round(alg / best / 1e6 / HBM_PEAK, 4)}
+            out["cases"].append(case)
+            log(json.dumps(case))
+            del X, Y, ws
+    finally:
+        for h in handles:
+            tb.tidal_adapter_destroy(h)
+        T.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging"])
+    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply"])
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
+    ap.add_argument("--case", default="", help="apply: only cases whose name contains this")
     args = ap.parse_args()
     assert torch.cuda.is_available(), "needs a GPU (there is no CPU path)"
     torch.cuda.set_device(0)
@@ -365,6 +442,8 @@ def main():
         out = bench_overlap(args)
     elif args.config == "merging":
         out = bench_merging(args)
+    elif args.config == "apply":
+        out = bench_apply(args)
     else:
         out = bench_churn(args)
     print(json.dumps(out), flush=True)

@@ -4,100 +4,170 @@
 // base model (Sec. 3, programming interface; Sec. 5.2, adaptive template state reusing), so that
 // requests with different adapters can share a batch.  For the tokens t of one request
 //     u[t] = bf16( A x[t] ),      y[t] <- bf16( y[t] + s * B u[t] ),      s = alpha / r
-// with fp32 accumulation.  Tokens are cut into tiles of up to 32 rows that share an adapter; both
-// steps run on the matrix cores (v_mfma_f32_32x32x16_bf16) with the token rows as the M index:
+// with fp32 accumulation.  A batch is a list of segments (runs of token rows with one adapter).
 //
-//  * apply_shrink_kernel: one workgroup of 8 waves per tile.  The contraction runs over the whole
-//    input width, so the waves split it: wave w takes the 64-column groups w, w+8, ... and a lane
-//    reads 64 contiguous bytes of its x row and of its A row per group (both operands use the same
-//    column permutation, which a sum does not care about), giving full 128-byte lines per row.
-//    The 8 partial 32 x rp tiles meet in LDS and are added in wave order, so the result does not
-//    depend on scheduling.  u goes to the caller's workspace as rows x rp bf16.
+//  * apply_shrink_kernel: one workgroup of 4 waves per tile of 32 tokens.  The contraction runs
+//    over the whole input width, so the waves split it by groups of 64 columns.  The MFMA operand
+//    layout puts consecutive lanes on consecutive rows, which as a global access pattern touches
+//    32 cache lines per instruction for 16 useful bytes each; instead a wave fetches its group of
+//    x (32 rows x 128 bytes) and of A (r rows x 128 bytes) with full-line accesses (8 lanes per
+//    row), parks it in a private piece of LDS and reads the operands back from there in MFMA
+//    order (row pitch 144 bytes: conflict-free 128-bit reads).  Only that wave touches its piece,
+//    so the loop has no workgroup barrier; the next group's global loads are in flight while the
+//    current one is multiplied.  The four partial 32 x rp tiles meet in LDS at the end and are
+//    added in wave order, so the result does not depend on scheduling.  u goes to the caller's
+//    workspace as rows x rp bf16 with zeros in the padded ranks.
 //
-//  * apply_expand_kernel: the same register tiling as the in-place merge with y in the place of W
-//    (rows = tokens, columns = out), B's rows as the stationary strip and u as the per-row factor:
-//    a lane owns 8 adjacent outputs of 16 token rows, 128-bit accesses to y.
+//  * apply_expand_kernel (segments longer than a few tokens): the register tiling of the
+//    in-place merge with y in the place of W (rows = tokens, columns = out): B's rows for 256
+//    outputs are the stationary strip, a wave walks down up to four 32-token tiles of one
+//    segment, u is the per-row factor, a lane owns 8 adjacent outputs of 16 token rows and
+//    accesses y with 128-bit vectors.
 //
-// HBM traffic: x once, y read and written once, the factors once per adapter (L2 serves tiles that
-// share one), u is a few KB per tile.
+//  * apply_expand_short_kernel (decode: segments of at most 4 tokens): one lane per output.  The
+//    lane's row of B is 32..128 contiguous bytes and neighbouring lanes read neighbouring rows,
+//    so the factors -- nearly all of the traffic here -- stream in fully coalesced; the few
+//    tokens' u rows are broadcast reads.  The sum runs over k in ascending order on the vector
+//    ALUs.
+//
+// HBM traffic: x once, y read and written once, the factors once per adapter and launch (L2
+// serves tiles that share one), u is a few KB per tile.
 #include "lora_device.h"
 
 namespace tidal {
 
-constexpr int kShrinkWaves = 8;
-
-__device__ __forceinline__ bf16x8 zero8() {
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    return __builtin_bit_cast(bf16x8, z);
+// Segment that owns work unit `unit`: the last one whose first unit is <= unit.  Uniform per wave.
+template <bool CHUNKS>
+__device__ __forceinline__ int find_segment(const ApplyBatch& batch, int unit) {
+    int lo = 0, hi = batch.n_segs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        const int first = CHUNKS ? batch.seg[mid].first_chunk : batch.seg[mid].first_tile;
+        if (first <= unit) lo = mid; else hi = mid - 1;
+    }
+    return lo;
 }
 
-template <bool TWO>
-__device__ __forceinline__ void shrink_accumulate(const uint16_t* __restrict__ xrow, const uint16_t* __restrict__ a0,
-                                                  const uint16_t* __restrict__ a1, bool v0, bool v1, int in, int kg,
-                                                  int wave, f32x16& c0, f32x16& c1) {
+// ---------------------------------------------------------------------------------------
+// shrink
+// ---------------------------------------------------------------------------------------
+constexpr int kShrinkWaves = 4;
+constexpr int kStagePitch = 72;                                   // bf16 per staged row: 64 + 8 of padding
+constexpr int kStageRows = 32 + 64;                               // x rows, then A rows
+constexpr int kStageBytes = kStageRows * kStagePitch * 2;         // 13,824 per wave
+constexpr int kPartBytes = kShrinkWaves * 2 * 32 * 32 * 4;        // 32,768
+constexpr int kShrinkLds = kShrinkWaves * kStageBytes > kPartBytes ? kShrinkWaves * kStageBytes : kPartBytes;
+
+__device__ __forceinline__ u32x4 zero4() {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    return z;
+}
+
+// Full-line fetch of one 64-column group: lane l takes 16 bytes at row (l / 8 + 8 i), piece l % 8.
+// XI = number of x row blocks (rows / 8 rounded up), AI likewise for the A rows.
+template <int XI, int AI>
+__device__ __forceinline__ void fetch_group(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Ar, int in,
+                                            int rows, int r, int j0, int lane, u32x4 (&xr)[4], u32x4 (&ar)[8]) {
+    const int sub = lane >> 3, piece = lane & 7;
+    const int j = j0 + 8 * piece;
+    const bool col_ok = j + 8 <= in;                              // in is a multiple of 8
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+        const int row = sub + 8 * i;
+        xr[i] = (col_ok && row < rows) ? *as_global((const u32x4*)(x + (int64_t)row * in + j)) : zero4();
+    }
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+        const int row = sub + 8 * i;
+        ar[i] = (col_ok && row < r) ? *as_global((const u32x4*)(Ar + (int64_t)row * in + j)) : zero4();
+    }
+}
+
+template <int XI, int AI>
+__device__ __forceinline__ void shrink_walk(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Ar, int in,
+                                            int rows, int r, int lane, int wave, uint16_t* stage, f32x16& c0,
+                                            f32x16& c1) {
+    constexpr bool TWO = AI > 4;
     const int groups = (in + 63) >> 6;
-    for (int g = wave; g < groups; g += kShrinkWaves) {
-        const int jb = g * 64 + 32 * kg;                        // lane's first column in this group
-        bf16x8 xv[4], av0[4], av1[4];
+    const int sub = lane >> 3, piece = lane & 7;
+    const int n = lane & 31, kg = lane >> 5;
+    uint16_t* xs = stage;
+    uint16_t* as = stage + 32 * kStagePitch;
+    // rows that are never fetched must read as zeros (ranks r..rp-1) or at least as numbers
+    for (int row = sub; row < kStageRows; row += 8) *(u32x4*)(stage + row * kStagePitch + 8 * piece) = zero4();
+
+    u32x4 xr[4], ar[8];
+    int g = wave;
+    if (g < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, g * 64, lane, xr, ar);
+    for (; g < groups; g += kShrinkWaves) {
+#pragma unroll
+        for (int i = 0; i < XI; ++i) *(u32x4*)(xs + (sub + 8 * i) * kStagePitch + 8 * piece) = xr[i];
+#pragma unroll
+        for (int i = 0; i < AI; ++i) *(u32x4*)(as + (sub + 8 * i) * kStagePitch + 8 * piece) = ar[i];
+        if (g + kShrinkWaves < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, (g + kShrinkWaves) * 64, lane, xr, ar);
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const bool ok = jb + 8 * q + 8 <= in;               // in is a multiple of 8
-            const int j = ok ? jb + 8 * q : 0;
-            const bf16x8 xl = *as_global((const bf16x8*)(xrow + j));
-            const bf16x8 al0 = *as_global((const bf16x8*)(a0 + j));
-            xv[q] = ok ? xl : zero8();
-            av0[q] = (ok && v0) ? al0 : zero8();
+            const bf16x8 xo = *(const bf16x8*)(xs + n * kStagePitch + 16 * q + 8 * kg);
+            const bf16x8 a0 = *(const bf16x8*)(as + n * kStagePitch + 16 * q + 8 * kg);
+            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, a0, c0, 0, 0, 0);
             if constexpr (TWO) {
-                const bf16x8 al1 = *as_global((const bf16x8*)(a1 + j));
-                av1[q] = (ok && v1) ? al1 : zero8();
+                const bf16x8 a1 = *(const bf16x8*)(as + (32 + n) * kStagePitch + 16 * q + 8 * kg);
+                c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, a1, c1, 0, 0, 0);
             }
         }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[q], av0[q], c0, 0, 0, 0);
-            if constexpr (TWO) c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xv[q], av1[q], c1, 0, 0, 0);
-        }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
 __global__ __launch_bounds__(64 * kShrinkWaves) void apply_shrink_kernel(const ApplyBatch batch, int in) {
-    __shared__ float part[kShrinkWaves][2][32][32];             // 64 KB: [wave][rank tile][token][rank]
-    const ApplyTile tl = batch.tile[blockIdx.x];
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kShrinkLds];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int n = lane & 31, kg = lane >> 5;
-    // A operand (M x K): token rows of x; rows past the tile repeat its last row and are dropped
-    const int tok = tl.t0 + (n < tl.rows ? n : tl.rows - 1);
-    const uint16_t* xrow = batch.x + (int64_t)tok * in;
-    // B operand (K x N): rank rows of A; ranks past r read row 0 and are zeroed
-    const bool v0 = n < tl.r, v1 = n + 32 < tl.r;
-    const uint16_t* a0 = tl.Ar + (int64_t)(v0 ? n : 0) * in;
-    const uint16_t* a1 = tl.Ar + (int64_t)(v1 ? n + 32 : 0) * in;
-    const bool two = tl.rp > 32;
+    const int si = find_segment<false>(batch, blockIdx.x);
+    const ApplySeg sg = batch.seg[si];
+    const int tile0 = sg.t0 + 32 * ((int)blockIdx.x - sg.first_tile);    // first token of this tile
+    const int rows = sg.t1 - tile0 < 32 ? sg.t1 - tile0 : 32;
+    const uint16_t* x = batch.x + (int64_t)tile0 * in;
+    uint16_t* stage = (uint16_t*)(lds + wave * kStageBytes);
 
     f32x16 c0 = {0}, c1 = {0};
-    if (two) shrink_accumulate<true>(xrow, a0, a1, v0, v1, in, kg, wave, c0, c1);
-    else shrink_accumulate<false>(xrow, a0, a1, v0, v1, in, kg, wave, c0, c1);
+    const int xi = (rows + 7) >> 3;
+    // instantiations by the number of 8-row blocks to fetch: x 1 or 4, A 2, 4 or 8
+    if (sg.rp == 16) {
+        if (xi == 1) shrink_walk<1, 2>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else shrink_walk<4, 2>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+    } else if (sg.rp == 32) {
+        if (xi == 1) shrink_walk<1, 4>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else shrink_walk<4, 4>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+    } else {
+        if (xi == 1) shrink_walk<1, 8>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else shrink_walk<4, 8>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+    }
 
     // C layout: lane holds rank column n of token rows 8*(v/4) + 4*kg + v%4
+    const int n = lane & 31, kg = lane >> 5;
+    const bool two = sg.rp > 32;
+    __syncthreads();                                              // the stages become the partial sums
+    float* part = (float*)lds;                                    // [wave][rank tile][token][rank]
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int row = 8 * (v >> 2) + 4 * kg + (v & 3);
-        part[wave][0][row][n] = c0[v];
-        if (two) part[wave][1][row][n] = c1[v];
+        part[((wave * 2 + 0) * 32 + row) * 32 + n] = c0[v];
+        if (two) part[((wave * 2 + 1) * 32 + row) * 32 + n] = c1[v];
     }
     __syncthreads();
-    uint32_t* u = (uint32_t*)(batch.u + (int64_t)tl.t0 * kApplyRankStride);
-    const int pairs_per_row = tl.rp >> 1;
-    const int pairs = tl.rows * pairs_per_row;
+    uint32_t* u = (uint32_t*)(batch.u + (int64_t)sg.t0 * kApplyRankStride + (int64_t)(tile0 - sg.t0) * sg.rp);
+    const int pairs_per_row = sg.rp >> 1;
+    const int pairs = rows * pairs_per_row;
     for (int e = threadIdx.x; e < pairs; e += 64 * kShrinkWaves) {
         const int row = e / pairs_per_row;
         const int k = 2 * (e - row * pairs_per_row);
         float lo = 0.0f, hi = 0.0f;
 #pragma unroll
-        for (int w = 0; w < kShrinkWaves; ++w) {                // fixed order: reproducible
-            lo += part[w][k >> 5][row][k & 31];
-            hi += part[w][k >> 5][row][(k & 31) + 1];
+        for (int w = 0; w < kShrinkWaves; ++w) {                  // fixed order: reproducible
+            lo += part[((w * 2 + (k >> 5)) * 32 + row) * 32 + (k & 31)];
+            hi += part[((w * 2 + (k >> 5)) * 32 + row) * 32 + (k & 31) + 1];
         }
         const f32x2 r2 = {lo, hi};
         as_global(u)[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2));
@@ -106,54 +176,123 @@ __global__ __launch_bounds__(64 * kShrinkWaves) void apply_shrink_kernel(const A
 
 hipError_t launch_apply_shrink(const ApplyBatch& b, int n_tiles, int in, hipStream_t stream) {
     if (n_tiles <= 0) return hipSuccess;
-    if (n_tiles > kMaxApplyTiles || in <= 0 || in % 8) return hipErrorInvalidValue;
+    if (b.n_segs <= 0 || b.n_segs > kMaxApplySegs || in <= 0 || in % 8) return hipErrorInvalidValue;
     hipLaunchKernelGGL(apply_shrink_kernel, dim3((unsigned)n_tiles), dim3(64 * kShrinkWaves), 0, stream, b, in);
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// expand, matrix cores
+// ---------------------------------------------------------------------------------------
 template <int KS>
-__device__ __forceinline__ void expand_tile(const ApplyBatch& batch, const ApplyTile& tl, int out, int j0, int lane) {
+__device__ __forceinline__ void expand_walk(const ApplyBatch& batch, const ApplySeg& sg, int t_begin, int out, int j0,
+                                            int lane) {
     constexpr int NT = 8;
     bf16x8 bop[NT][KS];
-    load_strip<NT, KS>(tl.Bp, out, j0, lane, bop);              // rows of B for the lane's 8 outputs
-    const uint16_t* u = batch.u + (int64_t)tl.t0 * kApplyRankStride;
-    f32x16 acc[NT];
-    delta_tile<NT, KS>(u, tl.rows, 0, lane, bop, acc);
+    load_strip<NT, KS>(sg.Bp, out, j0, lane, bop);               // rows of B for the lane's 8 outputs
     const int n = lane & 31, h = lane >> 5;
     const int jl = j0 + NT * n;
-    uint16_t* y = batch.y + (int64_t)tl.t0 * out;
-    const bool full = (tl.rows == 32) && (j0 + 32 * NT <= out);
-    uint32_t w[16][NT / 2];
-    load_block<NT>(y, tl.rows, out, 0, jl, h, full, w);
-    apply_tile<NT>(w, acc, tl.s);
-    store_block<NT>(y, tl.rows, out, 0, jl, h, full, w);
+    const bool strip_full = j0 + 32 * NT <= out;
+    const int t_end = sg.t1 < t_begin + 32 * kApplyChunkTiles ? sg.t1 : t_begin + 32 * kApplyChunkTiles;
+    for (int t = t_begin; t < t_end; t += 32) {
+        const int rows = t_end - t < 32 ? t_end - t : 32;
+        const uint16_t* u = batch.u + (int64_t)sg.t0 * kApplyRankStride + (int64_t)(t - sg.t0) * sg.rp;
+        uint16_t* y = batch.y + (int64_t)t * out;
+        const bool full = strip_full && rows == 32;
+        uint32_t w[16][NT / 2];
+        load_block<NT>(y, rows, out, 0, jl, h, full, w);
+        f32x16 acc[NT];
+        delta_tile<NT, KS>(u, rows, 0, lane, bop, acc);
+        apply_tile<NT>(w, acc, sg.s);
+        store_block<NT>(y, rows, out, 0, jl, h, full, w);
+    }
 }
 
-__global__ __launch_bounds__(256) void apply_expand_kernel(const ApplyBatch batch, int n_tiles, int out, int strips) {
+__global__ __launch_bounds__(256) void apply_expand_kernel(const ApplyBatch batch, int n_chunks, int out, int strips) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int item = blockIdx.x * 4 + wave;
-    if (item >= n_tiles * strips) return;
-    // neighbouring waves take neighbouring tiles of one strip: they share the rows of B
-    const int strip = item / n_tiles;
-    const int tile = item - strip * n_tiles;
-    const ApplyTile tl = batch.tile[tile];
+    if (item >= n_chunks * strips) return;
+    // the four waves of a workgroup take neighbouring strips of one chunk: adjacent pieces of the same y rows
+    const int chunk = item / strips;
+    const int strip = item - chunk * strips;
+    const int si = find_segment<true>(batch, chunk);
+    const ApplySeg sg = batch.seg[si];
+    const int t_begin = sg.t0 + 32 * kApplyChunkTiles * (chunk - sg.first_chunk);
     const int j0 = strip * 256;
-    switch (tl.rp) {
-        case 16: expand_tile<1>(batch, tl, out, j0, lane); break;
-        case 32: expand_tile<2>(batch, tl, out, j0, lane); break;
-        case 64: expand_tile<4>(batch, tl, out, j0, lane); break;
+    switch (sg.rp) {
+        case 16: expand_walk<1>(batch, sg, t_begin, out, j0, lane); break;
+        case 32: expand_walk<2>(batch, sg, t_begin, out, j0, lane); break;
+        case 64: expand_walk<4>(batch, sg, t_begin, out, j0, lane); break;
         default: break;
     }
 }
 
-hipError_t launch_apply_expand(const ApplyBatch& b, int n_tiles, int out, hipStream_t stream) {
-    if (n_tiles <= 0) return hipSuccess;
-    if (n_tiles > kMaxApplyTiles || out <= 0 || out % 8) return hipErrorInvalidValue;
+hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int out, hipStream_t stream) {
+    if (n_chunks <= 0) return hipSuccess;
+    if (b.n_segs <= 0 || b.n_segs > kMaxApplySegs || out <= 0 || out % 8) return hipErrorInvalidValue;
     const int strips = (out + 255) / 256;
-    const int64_t items = (int64_t)n_tiles * strips;
-    hipLaunchKernelGGL(apply_expand_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, stream, b, n_tiles, out,
+    const int64_t items = (int64_t)n_chunks * strips;
+    if (items > 0x7FFFFFF0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(apply_expand_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, stream, b, n_chunks, out,
                        strips);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// expand, few tokens per segment: one lane per output
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
+    const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = __uint_as_float(wds[e] << 16);
+        f[2 * e + 1] = __uint_as_float(wds[e] & 0xFFFF0000u);
+    }
+}
+
+__global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyBatch batch, int out, int blocks_per_seg) {
+    const int si = blockIdx.x / blocks_per_seg;
+    const int i = (blockIdx.x - si * blocks_per_seg) * 256 + threadIdx.x;
+    if (i >= out) return;
+    const ApplySeg sg = batch.seg[si];
+    const int rows = sg.t1 - sg.t0;                               // 1 .. kApplyShortRows
+    const uint16_t* u = batch.u + (int64_t)sg.t0 * kApplyRankStride;
+    const uint16_t* brow = sg.Bp + (int64_t)i * sg.rp;
+    float acc[kApplyShortRows];
+#pragma unroll
+    for (int t = 0; t < kApplyShortRows; ++t) acc[t] = 0.0f;
+    for (int k0 = 0; k0 < sg.rp; k0 += 8) {
+        float b8[8];
+        const u32x4 bv = *as_global((const u32x4*)(brow + k0));
+        unpack8(bv, b8);
+#pragma unroll
+        for (int t = 0; t < kApplyShortRows; ++t) {
+            if (t < rows) {
+                float u8[8];
+                const u32x4 uv = *as_global((const u32x4*)(u + t * sg.rp + k0));
+                unpack8(uv, u8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[t] = __builtin_fmaf(b8[e], u8[e], acc[t]);
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < kApplyShortRows; ++t) {
+        if (t < rows) {
+            TIDAL_GLOBAL uint16_t* p = as_global(batch.y + (int64_t)(sg.t0 + t) * out + i);
+            const f32x2 r2 = {__builtin_fmaf(sg.s, acc[t], __uint_as_float((uint32_t)*p << 16)), 0.0f};
+            *p = (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
+        }
+    }
+}
+
+hipError_t launch_apply_expand_short(const ApplyBatch& b, int out, hipStream_t stream) {
+    if (b.n_segs <= 0) return hipSuccess;
+    if (b.n_segs > kMaxApplySegs || out <= 0) return hipErrorInvalidValue;
+    const int blocks_per_seg = (out + 255) / 256;
+    hipLaunchKernelGGL(apply_expand_short_kernel, dim3((unsigned)(b.n_segs * blocks_per_seg)), dim3(256), 0, stream, b,
+                       out, blocks_per_seg);
     return hipGetLastError();
 }
 

@@ -908,7 +908,7 @@ extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_ada
         if (spans[i].first < spans[i - 1].second)
             return fail(TIDAL_E_INVAL, "segments overlap at token %d", spans[i].first);
 
-    std::vector<ApplyTile> tiles;
+    std::vector<ApplySeg> all;
     for (int32_t i = 0; i < n_segs; ++i) {
         const tidal_lora_segment& g = segs[i];
         if (g.adapter < 0 || g.token_end == g.token_begin || st.elems == 0) continue;
@@ -916,20 +916,18 @@ extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_ada
         if (!p->active()) continue;
         if (p->ar_off == kNoOffset) return fail(TIDAL_E_STATE, "adapter %d holds no row-major A for slot %d", g.adapter, slot);
         const char* base = adapters[g.adapter]->rec.dev;
-        for (int32_t t0 = g.token_begin; t0 < g.token_end; t0 += 32) {
-            ApplyTile tl;
-            tl.Ar = (const uint16_t*)(base + p->ar_off);
-            tl.Bp = (const uint16_t*)(base + p->bp_off);
-            tl.t0 = t0;
-            tl.rows = std::min(32, g.token_end - t0);
-            tl.s = p->alpha / (float)p->r;
-            tl.r = p->r;
-            tl.rp = p->rp;
-            tl.pad_ = 0;
-            tiles.push_back(tl);
-        }
+        ApplySeg sg;
+        memset(&sg, 0, sizeof sg);
+        sg.Ar = (const uint16_t*)(base + p->ar_off);
+        sg.Bp = (const uint16_t*)(base + p->bp_off);
+        sg.t0 = g.token_begin;
+        sg.t1 = g.token_end;
+        sg.s = p->alpha / (float)p->r;
+        sg.r = p->r;
+        sg.rp = p->rp;
+        all.push_back(sg);
     }
-    if (tiles.empty()) return TIDAL_OK;
+    if (all.empty()) return TIDAL_OK;
     if (!x || !y) return fail(TIDAL_E_INVAL, "x or y is NULL");
     if ((uintptr_t)x % 16 || (uintptr_t)y % 16) return fail(TIDAL_E_INVAL, "x and y must be 16-byte aligned");
     if (!workspace || (uintptr_t)workspace % kSlotAlign) return fail(TIDAL_E_INVAL, "workspace is NULL or not 256-byte aligned");
@@ -940,17 +938,40 @@ extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_ada
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)stream_;
     if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));   // adapter uploads
-    for (size_t at = 0; at < tiles.size(); at += kMaxApplyTiles) {
-        const int n = (int)std::min(tiles.size() - at, (size_t)kMaxApplyTiles);
-        ApplyBatch b;
-        b.x = (const uint16_t*)x;
-        b.y = (uint16_t*)y;
-        b.u = (uint16_t*)workspace;
-        memcpy(b.tile, tiles.data() + at, (size_t)n * sizeof(ApplyTile));
-        HIP_TRY(launch_apply_shrink(b, n, in, stream));
-        HIP_TRY(launch_apply_expand(b, n, out, stream));
-    }
-    return TIDAL_OK;
+
+    // One launch covers up to kMaxApplySegs segments; work units are numbered within a launch.
+    auto run = [&](const std::vector<ApplySeg>& list, int kind) -> int {
+        for (size_t at = 0; at < list.size(); at += kMaxApplySegs) {
+            const int n = (int)std::min(list.size() - at, (size_t)kMaxApplySegs);
+            ApplyBatch b;
+            memset(&b, 0, sizeof b);
+            b.x = (const uint16_t*)x;
+            b.y = (uint16_t*)y;
+            b.u = (uint16_t*)workspace;
+            b.n_segs = n;
+            int64_t tiles = 0, chunks = 0;
+            for (int k = 0; k < n; ++k) {
+                ApplySeg sg = list[at + k];
+                const int64_t len = (int64_t)sg.t1 - sg.t0;
+                sg.first_tile = (int32_t)tiles;
+                sg.first_chunk = (int32_t)chunks;
+                tiles += (len + 31) / 32;
+                chunks += (len + 32 * kApplyChunkTiles - 1) / (32 * kApplyChunkTiles);
+                b.seg[k] = sg;
+            }
+            if (kind == 0) HIP_TRY(launch_apply_shrink(b, (int)tiles, in, stream));
+            else if (kind == 1) HIP_TRY(launch_apply_expand(b, (int)chunks, out, stream));
+            else HIP_TRY(launch_apply_expand_short(b, out, stream));
+        }
+        return TIDAL_OK;
+    };
+    std::vector<ApplySeg> longs, shorts;
+    for (const ApplySeg& sg : all) (sg.t1 - sg.t0 <= kApplyShortRows ? shorts : longs).push_back(sg);
+    rc = run(all, 0);
+    if (rc) return rc;
+    rc = run(longs, 1);
+    if (rc) return rc;
+    return run(shorts, 2);
 }
 
 extern "C" int tidal_lora_detach(tidal_template* t, void* stream) {

@@ -72,28 +72,38 @@ hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream);
 hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream);
 
 // ---- unmerged adapter apply ---------------------------------------------------------------
-// One entry per tile of up to 32 consecutive tokens that share an adapter.  Adapters live in
-// separate caller-owned allocations, hence full pointers; 112 entries travel in the kernel
-// arguments, longer batches take several launches.
-struct ApplyTile {
+// One entry per run of consecutive tokens that share an adapter.  Adapters live in separate
+// caller-owned allocations, hence full pointers; 80 entries travel in the kernel arguments,
+// batches with more segments take several launches.  Work units (32-token tiles for the shrink,
+// chunks of kApplyChunkTiles tiles for the expand) are numbered through the launch; each entry
+// carries the number of its first one and the kernels find their segment by bisection.
+struct ApplySeg {
     const uint16_t* Ar;      // r x in bf16, A row-major
     const uint16_t* Bp;      // out x rp bf16, zero padded
-    int32_t t0, rows;        // first token row, number of token rows (1..32)
+    int32_t t0, t1;          // token rows [t0, t1)
     float s;                 // alpha / r
     int32_t r, rp;           // true and padded rank
+    int32_t first_tile;      // shrink work units before this segment
+    int32_t first_chunk;     // expand work units before this segment
     int32_t pad_;
 };
-constexpr int kMaxApplyTiles = 112;
+constexpr int kMaxApplySegs = 80;
 constexpr int kApplyRankStride = 64;   // workspace elements reserved per token
+constexpr int kApplyChunkTiles = 4;    // 32-token tiles a wave of the expand kernel walks per strip
+constexpr int kApplyShortRows = 4;     // segments up to this many tokens take the vector-ALU expand
 struct ApplyBatch {
     const uint16_t* x;       // n_tokens x in
     uint16_t* y;             // n_tokens x out
-    uint16_t* u;             // workspace: tile at u + t0 * kApplyRankStride, rows x rp bf16
-    ApplyTile tile[kMaxApplyTiles];   // 3584 bytes
+    uint16_t* u;             // workspace: token t's rank-space row at u + t0 * kApplyRankStride + (t - t0) * rp
+    int32_t n_segs, pad_;
+    ApplySeg seg[kMaxApplySegs];   // 3840 bytes
 };
-// u = bf16(A x) for every tile, then y += s * B u.
+// u = bf16(A x) for every segment of the batch (n_tiles = total 32-token tiles)
 hipError_t launch_apply_shrink(const ApplyBatch& b, int n_tiles, int in, hipStream_t stream);
-hipError_t launch_apply_expand(const ApplyBatch& b, int n_tiles, int out, hipStream_t stream);
+// y += s * B u: matrix-core kernel for long segments (n_chunks = total chunks), vector kernel
+// for segments of at most kApplyShortRows tokens
+hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int out, hipStream_t stream);
+hipError_t launch_apply_expand_short(const ApplyBatch& b, int out, hipStream_t stream);
 
 inline int padded_rank(int r) { return r <= 0 ? 0 : (r <= 16 ? 16 : (r <= 32 ? 32 : 64)); }
 

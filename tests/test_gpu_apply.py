@@ -115,6 +115,23 @@ def test_many_single_token_requests_span_several_launches(orc):
         check(orc, items, segs, X, Y, got)
 
 
+def test_segment_lengths_around_the_kernel_boundaries(orc):
+    """4 | 5 tokens: vector and matrix-core expand; 128 | 129: one and two chunks of four tiles;
+    more than 80 longer segments: several launches of the matrix-core kernels."""
+    rng = np.random.default_rng(15)
+    with Template([(320, 192)]) as T:
+        items, handles = make_adapters(T, rng, 0, [16, 40, 1], [32.0, 80.0, 2.0])
+        lens = [4, 5, 128, 129, 31, 32, 2, 8, 9] + [5] * 90
+        segs, t = [], 0
+        for i, n in enumerate(lens):
+            segs.append((i % 3, t, t + n))
+            t += n + (i % 2)                              # every other segment is followed by a free token
+        X = bf16_bits(rng, (t, 192), 1.0)
+        Y = bf16_bits(rng, (t, 320), 1.0)
+        got = run_apply(T, 0, handles, segs, X, Y)
+        check(orc, items, segs, X, Y, got)
+
+
 def test_long_prompt_one_adapter_and_merged_weights_untouched(orc):
     rng = np.random.default_rng(13)
     with Template([(256, 1024)]) as T:
