@@ -353,12 +353,12 @@ def bench_apply(args):
     32 layers, one call per layer, so that a pass touches 32 distinct sets of factors and
     activations (more than the 256 MB Infinity Cache holds for the larger batches).  A pool of 32
     adapters with ranks {8, 16, 32, 64} and Zipf(1.1) popularity, as in the churn configuration."""
-    layers, hidden = 32, 4096
+    layers, hidden = args.layers, 4096
     ch = wl_mod.adapter_churn()
     rng = np.random.default_rng(0)
     shapes = [(hidden, hidden)] * layers
     T = hz.DeviceTemplate(shapes, max_adapter_bytes=0)
-    out = {"config": "apply_q_proj_4096_x32_layers_pool32", "cases": []}
+    out = {"config": "apply_q_proj_4096_x%d_layers_pool32" % layers, "cases": []}
     keep, handles = [], []
     try:
         host = {}
@@ -400,11 +400,15 @@ def bench_apply(args):
             factor_bytes = sum(2 * (ch.ranks[a] * hidden + hidden * max(16, 1 << (ch.ranks[a] - 1).bit_length())) for a in used)
             alg = n * hidden * 2 + n * hidden * 4 + factor_bytes       # x once, y read + written, factors once
             best = None
+            aarr, sarr = tb.lora_apply_arrays(handles, segs)          # marshalled once, as a server would
+            xp = [t_.data_ptr() for t_ in X]
+            yp = [t_.data_ptr() for t_ in Y]
+            wp, sp = ws.data_ptr(), T.compute_stream.cuda_stream
             for rep in range(args.reps + 1):
                 e0, e1 = ev(), ev()
                 e0.record(T.compute_stream)
                 for l in range(layers):
-                    tb.tidal_lora_apply(T.h, l, handles, segs, X[l], Y[l], n, ws, nb, T.compute_stream)
+                    tb.tidal_lora_apply(T.h, l, aarr, sarr, xp[l], yp[l], n, wp, nb, sp)
                 e1.record(T.compute_stream)
                 T.sync()
                 ms = e0.elapsed_time(e1) / layers
@@ -428,6 +432,7 @@ def main():
     ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply"])
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
+    ap.add_argument("--layers", type=int, default=32, help="apply: distinct layers (sets of factors and activations) per pass")
     ap.add_argument("--case", default="", help="apply: only cases whose name contains this")
     args = ap.parse_args()
     assert torch.cuda.is_available(), "needs a GPU (there is no CPU path)"

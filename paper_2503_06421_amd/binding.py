@@ -313,15 +313,24 @@ def tidal_lora_apply_workspace_bytes(n_tokens: int) -> int:
     return lib().tidal_lora_apply_workspace_bytes(n_tokens)
 
 
-def tidal_lora_apply(t, slot: int, adapters, segments, x, y, n_tokens: int, workspace, workspace_bytes: int,
-                     stream=None) -> None:
-    """segments: iterable of (adapter index, token_begin, token_end)."""
+def lora_apply_arrays(adapters, segments):
+    """ctypes arrays for tidal_lora_apply, for callers that reuse one batch layout many times."""
     adapters = list(adapters)
     segments = list(segments)
     aarr = (c_void_p * max(1, len(adapters)))(*adapters)
     sarr = (tidal_lora_segment * max(1, len(segments)))(*[tidal_lora_segment(a, b, e) for a, b, e in segments])
-    _check(lib().tidal_lora_apply(t, slot, aarr, len(adapters), sarr, len(segments), device_ptr(x), device_ptr(y),
-                                  n_tokens, device_ptr(workspace), workspace_bytes, stream_ptr(stream)))
+    return (aarr, len(adapters)), (sarr, len(segments))
+
+
+def tidal_lora_apply(t, slot: int, adapters, segments, x, y, n_tokens: int, workspace, workspace_bytes: int,
+                     stream=None) -> None:
+    """segments: iterable of (adapter index, token_begin, token_end); or pass the two values of
+    lora_apply_arrays() as adapters and segments."""
+    if not (isinstance(adapters, tuple) and isinstance(segments, tuple) and len(segments) == 2
+            and isinstance(segments[0], ctypes.Array)):
+        adapters, segments = lora_apply_arrays(adapters, segments)
+    _check(lib().tidal_lora_apply(t, slot, adapters[0], adapters[1], segments[0], segments[1], device_ptr(x),
+                                  device_ptr(y), n_tokens, device_ptr(workspace), workspace_bytes, stream_ptr(stream)))
 
 
 def _slot_list(slots):

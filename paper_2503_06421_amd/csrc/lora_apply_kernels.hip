@@ -6,6 +6,9 @@
 //     u[t] = bf16( A x[t] ),      y[t] <- bf16( y[t] + s * B u[t] ),      s = alpha / r
 // with fp32 accumulation.  A batch is a list of segments (runs of token rows with one adapter).
 //
+// Segments of more than 4 tokens (prompts) run on the matrix cores, shorter ones (decode steps),
+// where nearly all traffic is the factors themselves, on the vector ALUs:
+//
 //  * apply_shrink_kernel: one workgroup of 4 waves per tile of 32 tokens.  The contraction runs
 //    over the whole input width, so the waves split it by groups of 64 columns.  The MFMA operand
 //    layout puts consecutive lanes on consecutive rows, which as a global access pattern touches
@@ -18,13 +21,16 @@
 //    added in wave order, so the result does not depend on scheduling.  u goes to the caller's
 //    workspace as rows x rp bf16 with zeros in the padded ranks.
 //
-//  * apply_expand_kernel (segments longer than a few tokens): the register tiling of the
+//  * apply_expand_kernel: the register tiling of the
 //    in-place merge with y in the place of W (rows = tokens, columns = out): B's rows for 256
-//    outputs are the stationary strip, a wave walks down up to four 32-token tiles of one
-//    segment, u is the per-row factor, a lane owns 8 adjacent outputs of 16 token rows and
+//    outputs are the stationary strip, a wave walks down one to four 32-token tiles of one
+//    segment (fewer when the batch is small, so that every CU has work), u is the per-row factor, a lane owns 8 adjacent outputs of 16 token rows and
 //    accesses y with 128-bit vectors.
 //
-//  * apply_expand_short_kernel (decode: segments of at most 4 tokens): one lane per output.  The
+//  * apply_shrink_short_kernel: one wave per rank row, lanes along the input width (1 KB per
+//    wave-wide load), one cross-lane reduction per token at the end.
+//
+//  * apply_expand_short_kernel: one lane per output.  The
 //    lane's row of B is 32..128 contiguous bytes and neighbouring lanes read neighbouring rows,
 //    so the factors -- nearly all of the traffic here -- stream in fully coalesced; the few
 //    tokens' u rows are broadcast reads.  The sum runs over k in ascending order on the vector
@@ -36,16 +42,13 @@
 
 namespace tidal {
 
-// Segment that owns work unit `unit`: the last one whose first unit is <= unit.  Uniform per wave.
-template <bool CHUNKS>
+// Segment that owns work unit `unit`: the number of later segments whose first unit is <= unit.
+// Uniform per wave; the reads do not depend on each other.
 __device__ __forceinline__ int find_segment(const ApplyBatch& batch, int unit) {
-    int lo = 0, hi = batch.n_segs - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        const int first = CHUNKS ? batch.seg[mid].first_chunk : batch.seg[mid].first_tile;
-        if (first <= unit) lo = mid; else hi = mid - 1;
-    }
-    return lo;
+    int si = 0;
+#pragma unroll
+    for (int k = 1; k < kMaxApplySegs; ++k) si += batch.first[k] <= unit ? 1 : 0;
+    return si;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -83,40 +86,68 @@ __device__ __forceinline__ void fetch_group(const uint16_t* __restrict__ x, cons
     }
 }
 
+// One group: park the fetched registers in the wave's stage, multiply from there.
+template <int XI, int AI>
+__device__ __forceinline__ void shrink_group(uint16_t* xs, uint16_t* as, int lane, const u32x4 (&xr)[4],
+                                             const u32x4 (&ar)[8], f32x16& c0, f32x16& c1) {
+    constexpr bool TWO = AI > 4;
+    const int sub = lane >> 3, piece = lane & 7;
+    const int n = lane & 31, kg = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < XI; ++i) *(u32x4*)(xs + (sub + 8 * i) * kStagePitch + 8 * piece) = xr[i];
+#pragma unroll
+    for (int i = 0; i < AI; ++i) *(u32x4*)(as + (sub + 8 * i) * kStagePitch + 8 * piece) = ar[i];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const bf16x8 xo = *(const bf16x8*)(xs + n * kStagePitch + 16 * q + 8 * kg);
+        const bf16x8 a0 = *(const bf16x8*)(as + n * kStagePitch + 16 * q + 8 * kg);
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, a0, c0, 0, 0, 0);
+        if constexpr (TWO) {
+            const bf16x8 a1 = *(const bf16x8*)(as + (32 + n) * kStagePitch + 16 * q + 8 * kg);
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, a1, c1, 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// A single workgroup sees one load latency per group unless several groups are in flight: three
+// groups' worth of registers rotate (two at 64 ranks, where a group is 12 vectors per lane).
 template <int XI, int AI>
 __device__ __forceinline__ void shrink_walk(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Ar, int in,
                                             int rows, int r, int lane, int wave, uint16_t* stage, f32x16& c0,
                                             f32x16& c1) {
-    constexpr bool TWO = AI > 4;
+    constexpr bool DEEP = (XI + AI) <= 8;
+    constexpr int W = kShrinkWaves;
     const int groups = (in + 63) >> 6;
     const int sub = lane >> 3, piece = lane & 7;
-    const int n = lane & 31, kg = lane >> 5;
     uint16_t* xs = stage;
     uint16_t* as = stage + 32 * kStagePitch;
     // rows that are never fetched must read as zeros (ranks r..rp-1) or at least as numbers
     for (int row = sub; row < kStageRows; row += 8) *(u32x4*)(stage + row * kStagePitch + 8 * piece) = zero4();
 
-    u32x4 xr[4], ar[8];
+    u32x4 x0[4], a0[8], x1[4], a1[8], x2[4], a2[8];
     int g = wave;
-    if (g < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, g * 64, lane, xr, ar);
-    for (; g < groups; g += kShrinkWaves) {
-#pragma unroll
-        for (int i = 0; i < XI; ++i) *(u32x4*)(xs + (sub + 8 * i) * kStagePitch + 8 * piece) = xr[i];
-#pragma unroll
-        for (int i = 0; i < AI; ++i) *(u32x4*)(as + (sub + 8 * i) * kStagePitch + 8 * piece) = ar[i];
-        if (g + kShrinkWaves < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, (g + kShrinkWaves) * 64, lane, xr, ar);
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const bf16x8 xo = *(const bf16x8*)(xs + n * kStagePitch + 16 * q + 8 * kg);
-            const bf16x8 a0 = *(const bf16x8*)(as + n * kStagePitch + 16 * q + 8 * kg);
-            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, a0, c0, 0, 0, 0);
-            if constexpr (TWO) {
-                const bf16x8 a1 = *(const bf16x8*)(as + (32 + n) * kStagePitch + 16 * q + 8 * kg);
-                c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xo, a1, c1, 0, 0, 0);
+    if (g < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, g * 64, lane, x0, a0);
+    if (g + W < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, (g + W) * 64, lane, x1, a1);
+    if constexpr (DEEP) {
+        if (g + 2 * W < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, (g + 2 * W) * 64, lane, x2, a2);
+    }
+    constexpr int D = DEEP ? 3 : 2;
+    for (; g < groups; g += D * W) {
+        shrink_group<XI, AI>(xs, as, lane, x0, a0, c0, c1);
+        if (g + D * W < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, (g + D * W) * 64, lane, x0, a0);
+        if (g + W < groups) {
+            shrink_group<XI, AI>(xs, as, lane, x1, a1, c0, c1);
+            if (g + (D + 1) * W < groups) fetch_group<XI, AI>(x, Ar, in, rows, r, (g + (D + 1) * W) * 64, lane, x1, a1);
+        }
+        if constexpr (DEEP) {
+            if (g + 2 * W < groups) {
+                shrink_group<XI, AI>(xs, as, lane, x2, a2, c0, c1);
+                if (g + (D + 2) * W < groups)
+                    fetch_group<XI, AI>(x, Ar, in, rows, r, (g + (D + 2) * W) * 64, lane, x2, a2);
             }
         }
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -124,9 +155,9 @@ __global__ __launch_bounds__(64 * kShrinkWaves) void apply_shrink_kernel(const A
     __shared__ __attribute__((aligned(16))) uint8_t lds[kShrinkLds];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int si = find_segment<false>(batch, blockIdx.x);
+    const int si = find_segment(batch, blockIdx.x);
     const ApplySeg sg = batch.seg[si];
-    const int tile0 = sg.t0 + 32 * ((int)blockIdx.x - sg.first_tile);    // first token of this tile
+    const int tile0 = sg.t0 + 32 * ((int)blockIdx.x - batch.first[si]);    // first token of this tile
     const int rows = sg.t1 - tile0 < 32 ? sg.t1 - tile0 : 32;
     const uint16_t* x = batch.x + (int64_t)tile0 * in;
     uint16_t* stage = (uint16_t*)(lds + wave * kStageBytes);
@@ -181,19 +212,87 @@ hipError_t launch_apply_shrink(const ApplyBatch& b, int n_tiles, int in, hipStre
     return hipGetLastError();
 }
 
+__device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
+    const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = __uint_as_float(wds[e] << 16);
+        f[2 * e + 1] = __uint_as_float(wds[e] & 0xFFFF0000u);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// shrink, few tokens per segment: one wave per rank row
+// ---------------------------------------------------------------------------------------
+// A wave owns rank row k of one segment: its lanes stride along the input width in 16-byte
+// pieces (1 KB per wave-wide load, fully coalesced), multiply with the segment's x rows and
+// reduce across lanes once per token at the end.  Four rank rows per workgroup, so a decode
+// batch of 64 requests at rank 16 is 256 workgroups whose loads are all independent.
+__global__ __launch_bounds__(256) void apply_shrink_short_kernel(const ApplyBatch batch, int in) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int si = blockIdx.x >> 4;                               // 16 workgroups per segment: 64 rank rows
+    const int k = ((blockIdx.x & 15) << 2) + wave;
+    const ApplySeg sg = batch.seg[si];
+    if (k >= sg.rp) return;
+    const int rows = sg.t1 - sg.t0;                               // 1 .. kApplyShortRows
+    float acc[kApplyShortRows];
+#pragma unroll
+    for (int t = 0; t < kApplyShortRows; ++t) acc[t] = 0.0f;
+    if (k < sg.r) {
+        const uint16_t* arow = sg.Ar + (int64_t)k * in;
+        const uint16_t* x = batch.x + (int64_t)sg.t0 * in;
+#pragma unroll 8
+        for (int j = 8 * lane; j < in; j += 512) {               // in is a multiple of 8
+            float a8[8];
+            const u32x4 av = *as_global((const u32x4*)(arow + j));
+            unpack8(av, a8);
+#pragma unroll
+            for (int t = 0; t < kApplyShortRows; ++t) {
+                if (t < rows) {
+                    float x8[8];
+                    const u32x4 xv = *as_global((const u32x4*)(x + (int64_t)t * in + j));
+                    unpack8(xv, x8);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[t] = __builtin_fmaf(a8[e], x8[e], acc[t]);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kApplyShortRows; ++t)
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) acc[t] += __shfl_xor(acc[t], off, 64);
+    }
+    if (lane < rows) {                                            // lane t stores token t's value (zero for padded ranks)
+        float v = acc[0];
+#pragma unroll
+        for (int t = 1; t < kApplyShortRows; ++t) v = lane == t ? acc[t] : v;
+        const f32x2 r2 = {v, 0.0f};
+        as_global(batch.u)[(int64_t)sg.t0 * kApplyRankStride + lane * sg.rp + k] =
+            (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
+    }
+}
+
+hipError_t launch_apply_shrink_short(const ApplyBatch& b, int in, hipStream_t stream) {
+    if (b.n_segs <= 0) return hipSuccess;
+    if (b.n_segs > kMaxApplySegs || in <= 0 || in % 8) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(apply_shrink_short_kernel, dim3((unsigned)(b.n_segs * 16)), dim3(256), 0, stream, b, in);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------
 // expand, matrix cores
 // ---------------------------------------------------------------------------------------
 template <int KS>
-__device__ __forceinline__ void expand_walk(const ApplyBatch& batch, const ApplySeg& sg, int t_begin, int out, int j0,
-                                            int lane) {
+__device__ __forceinline__ void expand_walk(const ApplyBatch& batch, const ApplySeg& sg, int t_begin, int chunk_rows,
+                                            int out, int j0, int lane) {
     constexpr int NT = 8;
     bf16x8 bop[NT][KS];
     load_strip<NT, KS>(sg.Bp, out, j0, lane, bop);               // rows of B for the lane's 8 outputs
     const int n = lane & 31, h = lane >> 5;
     const int jl = j0 + NT * n;
     const bool strip_full = j0 + 32 * NT <= out;
-    const int t_end = sg.t1 < t_begin + 32 * kApplyChunkTiles ? sg.t1 : t_begin + 32 * kApplyChunkTiles;
+    const int t_end = sg.t1 < t_begin + chunk_rows ? sg.t1 : t_begin + chunk_rows;
     for (int t = t_begin; t < t_end; t += 32) {
         const int rows = t_end - t < 32 ? t_end - t : 32;
         const uint16_t* u = batch.u + (int64_t)sg.t0 * kApplyRankStride + (int64_t)(t - sg.t0) * sg.rp;
@@ -208,7 +307,9 @@ __device__ __forceinline__ void expand_walk(const ApplyBatch& batch, const Apply
     }
 }
 
-__global__ __launch_bounds__(256) void apply_expand_kernel(const ApplyBatch batch, int n_chunks, int out, int strips) {
+template <int KS>
+__global__ __launch_bounds__(256) void apply_expand_kernel(const ApplyBatch batch, int n_chunks, int chunk_rows, int out,
+                                                           int strips) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int item = blockIdx.x * 4 + wave;
@@ -216,41 +317,37 @@ __global__ __launch_bounds__(256) void apply_expand_kernel(const ApplyBatch batc
     // the four waves of a workgroup take neighbouring strips of one chunk: adjacent pieces of the same y rows
     const int chunk = item / strips;
     const int strip = item - chunk * strips;
-    const int si = find_segment<true>(batch, chunk);
+    const int si = find_segment(batch, chunk);
     const ApplySeg sg = batch.seg[si];
-    const int t_begin = sg.t0 + 32 * kApplyChunkTiles * (chunk - sg.first_chunk);
-    const int j0 = strip * 256;
-    switch (sg.rp) {
-        case 16: expand_walk<1>(batch, sg, t_begin, out, j0, lane); break;
-        case 32: expand_walk<2>(batch, sg, t_begin, out, j0, lane); break;
-        case 64: expand_walk<4>(batch, sg, t_begin, out, j0, lane); break;
-        default: break;
-    }
+    const int t_begin = sg.t0 + chunk_rows * (chunk - batch.first[si]);
+    expand_walk<KS>(batch, sg, t_begin, chunk_rows, out, strip * 256, lane);
 }
 
-hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int out, hipStream_t stream) {
+// All segments of the batch have the padded rank rp.
+hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int chunk_tiles, int out, int rp,
+                               hipStream_t stream) {
     if (n_chunks <= 0) return hipSuccess;
-    if (b.n_segs <= 0 || b.n_segs > kMaxApplySegs || out <= 0 || out % 8) return hipErrorInvalidValue;
+    if (b.n_segs <= 0 || b.n_segs > kMaxApplySegs || out <= 0 || out % 8 || chunk_tiles < 1) return hipErrorInvalidValue;
+    const int chunk_rows = 32 * chunk_tiles;
     const int strips = (out + 255) / 256;
     const int64_t items = (int64_t)n_chunks * strips;
     if (items > 0x7FFFFFF0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(apply_expand_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, stream, b, n_chunks, out,
-                       strips);
+    const dim3 grid((unsigned)((items + 3) / 4));
+    switch (rp) {
+        case 16: hipLaunchKernelGGL(apply_expand_kernel<1>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, out,
+                                    strips); break;
+        case 32: hipLaunchKernelGGL(apply_expand_kernel<2>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, out,
+                                    strips); break;
+        case 64: hipLaunchKernelGGL(apply_expand_kernel<4>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, out,
+                                    strips); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------
 // expand, few tokens per segment: one lane per output
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
-    const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        f[2 * e] = __uint_as_float(wds[e] << 16);
-        f[2 * e + 1] = __uint_as_float(wds[e] & 0xFFFF0000u);
-    }
-}
-
 __global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyBatch batch, int out, int blocks_per_seg) {
     const int si = blockIdx.x / blocks_per_seg;
     const int i = (blockIdx.x - si * blocks_per_seg) * 256 + threadIdx.x;
@@ -259,9 +356,13 @@ __global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyBatc
     const int rows = sg.t1 - sg.t0;                               // 1 .. kApplyShortRows
     const uint16_t* u = batch.u + (int64_t)sg.t0 * kApplyRankStride;
     const uint16_t* brow = sg.Bp + (int64_t)i * sg.rp;
-    float acc[kApplyShortRows];
+    float acc[kApplyShortRows], yv[kApplyShortRows];
 #pragma unroll
-    for (int t = 0; t < kApplyShortRows; ++t) acc[t] = 0.0f;
+    for (int t = 0; t < kApplyShortRows; ++t) {
+        acc[t] = 0.0f;
+        yv[t] = 0.0f;
+        if (t < rows) yv[t] = __uint_as_float((uint32_t)as_global(batch.y)[(int64_t)(sg.t0 + t) * out + i] << 16);
+    }
     for (int k0 = 0; k0 < sg.rp; k0 += 8) {
         float b8[8];
         const u32x4 bv = *as_global((const u32x4*)(brow + k0));
@@ -280,9 +381,9 @@ __global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyBatc
 #pragma unroll
     for (int t = 0; t < kApplyShortRows; ++t) {
         if (t < rows) {
-            TIDAL_GLOBAL uint16_t* p = as_global(batch.y + (int64_t)(sg.t0 + t) * out + i);
-            const f32x2 r2 = {__builtin_fmaf(sg.s, acc[t], __uint_as_float((uint32_t)*p << 16)), 0.0f};
-            *p = (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
+            const f32x2 r2 = {__builtin_fmaf(sg.s, acc[t], yv[t]), 0.0f};
+            as_global(batch.y)[(int64_t)(sg.t0 + t) * out + i] =
+                (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
         }
     }
 }

@@ -940,7 +940,7 @@ extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_ada
     if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));   // adapter uploads
 
     // One launch covers up to kMaxApplySegs segments; work units are numbered within a launch.
-    auto run = [&](const std::vector<ApplySeg>& list, int kind) -> int {
+    auto run = [&](const std::vector<ApplySeg>& list, int kind, int rp) -> int {
         for (size_t at = 0; at < list.size(); at += kMaxApplySegs) {
             const int n = (int)std::min(list.size() - at, (size_t)kMaxApplySegs);
             ApplyBatch b;
@@ -950,28 +950,46 @@ extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_ada
             b.u = (uint16_t*)workspace;
             b.n_segs = n;
             int64_t tiles = 0, chunks = 0;
+            for (int k = 0; k < n; ++k) tiles += ((int64_t)list[at + k].t1 - list[at + k].t0 + 31) / 32;
+            // tiles a wave walks per strip of B: long walks amortise the strip, short ones keep
+            // small batches spread over the chip (aim: >= 4096 waves)
+            const int64_t strips = (out + 255) / 256;
+            const int ct = (int)std::max<int64_t>(1, std::min<int64_t>(kApplyChunkTiles, tiles * strips / 4096));
+            tiles = 0;
+            for (int k = 0; k < kMaxApplySegs; ++k) b.first[k] = 0x7FFFFFFF;
             for (int k = 0; k < n; ++k) {
-                ApplySeg sg = list[at + k];
+                const ApplySeg& sg = list[at + k];
                 const int64_t len = (int64_t)sg.t1 - sg.t0;
-                sg.first_tile = (int32_t)tiles;
-                sg.first_chunk = (int32_t)chunks;
+                b.first[k] = (int32_t)(kind == 1 ? chunks : tiles);
                 tiles += (len + 31) / 32;
-                chunks += (len + 32 * kApplyChunkTiles - 1) / (32 * kApplyChunkTiles);
+                chunks += (len + 32 * ct - 1) / (32 * ct);
                 b.seg[k] = sg;
             }
             if (kind == 0) HIP_TRY(launch_apply_shrink(b, (int)tiles, in, stream));
-            else if (kind == 1) HIP_TRY(launch_apply_expand(b, (int)chunks, out, stream));
+            else if (kind == 1) HIP_TRY(launch_apply_expand(b, (int)chunks, ct, out, rp, stream));
+            else if (kind == 2) HIP_TRY(launch_apply_shrink_short(b, in, stream));
             else HIP_TRY(launch_apply_expand_short(b, out, stream));
         }
         return TIDAL_OK;
     };
-    std::vector<ApplySeg> longs, shorts;
-    for (const ApplySeg& sg : all) (sg.t1 - sg.t0 <= kApplyShortRows ? shorts : longs).push_back(sg);
-    rc = run(all, 0);
+    std::vector<ApplySeg> longs, shorts, by_rank[3];
+    for (const ApplySeg& sg : all) {
+        if (sg.t1 - sg.t0 <= kApplyShortRows) {
+            shorts.push_back(sg);
+        } else {
+            longs.push_back(sg);
+            by_rank[sg.rp == 16 ? 0 : (sg.rp == 32 ? 1 : 2)].push_back(sg);
+        }
+    }
+    rc = run(longs, 0, 0);
     if (rc) return rc;
-    rc = run(longs, 1);
+    rc = run(shorts, 2, 0);
     if (rc) return rc;
-    return run(shorts, 2);
+    for (int g = 0; g < 3; ++g) {
+        rc = run(by_rank[g], 1, 16 << g);
+        if (rc) return rc;
+    }
+    return run(shorts, 3, 0);
 }
 
 extern "C" int tidal_lora_detach(tidal_template* t, void* stream) {

@@ -75,34 +75,36 @@ hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream);
 // One entry per run of consecutive tokens that share an adapter.  Adapters live in separate
 // caller-owned allocations, hence full pointers; 80 entries travel in the kernel arguments,
 // batches with more segments take several launches.  Work units (32-token tiles for the shrink,
-// chunks of kApplyChunkTiles tiles for the expand) are numbered through the launch; each entry
-// carries the number of its first one and the kernels find their segment by bisection.
+// chunks of one to kApplyChunkTiles tiles for the expand) are numbered through the launch; first[k]
+// is the number of segment k's first one (INT32_MAX past the last segment).  The kernels count
+// the entries <= their unit: one independent read of a compact array instead of a bisection,
+// whose dependent reads of the kernel arguments would cost more than a small batch's work.
 struct ApplySeg {
     const uint16_t* Ar;      // r x in bf16, A row-major
     const uint16_t* Bp;      // out x rp bf16, zero padded
     int32_t t0, t1;          // token rows [t0, t1)
     float s;                 // alpha / r
     int32_t r, rp;           // true and padded rank
-    int32_t first_tile;      // shrink work units before this segment
-    int32_t first_chunk;     // expand work units before this segment
     int32_t pad_;
 };
 constexpr int kMaxApplySegs = 80;
 constexpr int kApplyRankStride = 64;   // workspace elements reserved per token
-constexpr int kApplyChunkTiles = 4;    // 32-token tiles a wave of the expand kernel walks per strip
+constexpr int kApplyChunkTiles = 4;    // most 32-token tiles a wave of the expand kernel walks per strip
 constexpr int kApplyShortRows = 4;     // segments up to this many tokens take the vector-ALU expand
 struct ApplyBatch {
     const uint16_t* x;       // n_tokens x in
     uint16_t* y;             // n_tokens x out
     uint16_t* u;             // workspace: token t's rank-space row at u + t0 * kApplyRankStride + (t - t0) * rp
     int32_t n_segs, pad_;
-    ApplySeg seg[kMaxApplySegs];   // 3840 bytes
+    int32_t first[kMaxApplySegs];
+    ApplySeg seg[kMaxApplySegs];   // 3200 bytes
 };
-// u = bf16(A x) for every segment of the batch (n_tiles = total 32-token tiles)
+// Segments longer than kApplyShortRows tokens take the matrix-core kernels: u = bf16(A x)
+// (n_tiles = total 32-token tiles), then y += s * B u (n_chunks = total chunks; all segments of
+// that launch share the padded rank rp).  Shorter ones take the vector-ALU pair.
 hipError_t launch_apply_shrink(const ApplyBatch& b, int n_tiles, int in, hipStream_t stream);
-// y += s * B u: matrix-core kernel for long segments (n_chunks = total chunks), vector kernel
-// for segments of at most kApplyShortRows tokens
-hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int out, hipStream_t stream);
+hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int chunk_tiles, int out, int rp, hipStream_t stream);
+hipError_t launch_apply_shrink_short(const ApplyBatch& b, int in, hipStream_t stream);
 hipError_t launch_apply_expand_short(const ApplyBatch& b, int out, hipStream_t stream);
 
 inline int padded_rank(int r) { return r <= 0 ? 0 : (r <= 16 ? 16 : (r <= 32 ? 32 : 64)); }
