@@ -187,6 +187,33 @@ void orc_lora_merge_f32(float* W, int64_t out, int64_t in, const uint16_t* A,
     }
 }
 
+/* Cold start with the adapter known at load time: the slot is written once, straight from the
+ * host-precision source,
+ *     slot[i][j] = bf16( f32(src[i][j]) + (alpha/r) * sum_k B[i][k] A[k][j] )
+ * (same fp32 chain, ONE rounding instead of the two of "convert, then merge").  The dynamic part
+ * of initialisation (Sec. 5.2, adaptive template state reusing) folded into the static load.
+ * r == 0 or alpha == 0: plain conversion. */
+void orc_materialize_merge_slot(const void* src, int dtype, int64_t out, int64_t in, const uint16_t* A,
+                                const uint16_t* B, int32_t r, float alpha, uint16_t* slot) {
+    int64_t i, j;
+    float s;
+    if (r == 0 || alpha == 0.0f) {
+        orc_convert_to_bf16(src, dtype, out * in, slot);
+        return;
+    }
+    s = alpha / (float)r;
+    for (i = 0; i < out; ++i) {
+        for (j = 0; j < in; ++j) {
+            float w;
+            int64_t e = i * in + j;
+            if (dtype == ORC_F32) w = ((const float*)src)[e];
+            else if (dtype == ORC_F16) w = bits_to_float(orc_f16_bits_to_f32_bits(((const uint16_t*)src)[e]));
+            else w = bf16_to_float(((const uint16_t*)src)[e]);
+            slot[e] = float_to_bf16(fmaf(s, lora_dot(A, B, in, r, i, j), w));
+        }
+    }
+}
+
 /* Swap = unmerge the old adapter, store, then merge the new one (two roundings). */
 void orc_lora_swap_bf16(uint16_t* W, int64_t out, int64_t in,
                         const uint16_t* A_old, const uint16_t* B_old, int32_t r_old, float alpha_old,

@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.orc_resident_prefix.argtypes = [vp, vp, i32, ctypes.c_uint64]
         L.orc_slot_checksum.restype = ctypes.c_uint64
         L.orc_slot_checksum.argtypes = [vp, i64, i32]
+        L.orc_materialize_merge_slot.restype = None
+        L.orc_materialize_merge_slot.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp, i32, f32, vp]
         L.orc_lora_apply.restype = None
         L.orc_lora_apply.argtypes = [vp, vp, i64, i64, vp, vp, i32, f32, i64, i64]
         _lib = L
@@ -196,3 +198,15 @@ def lora_apply(X: np.ndarray, Y: np.ndarray, A: np.ndarray, B: np.ndarray, alpha
     assert A.shape == (r, X.shape[1]) and B.shape == (Y.shape[1], r) and X.shape[0] == Y.shape[0]
     assert 0 <= t0 <= t1 <= X.shape[0]
     lib().orc_lora_apply(_ptr(X), _ptr(Y), X.shape[1], Y.shape[1], _ptr(A), _ptr(B), r, float(alpha), t0, t1)
+
+
+def materialize_merge(src: np.ndarray, A: np.ndarray, B: np.ndarray, alpha: float) -> np.ndarray:
+    """bf16( f32(src) + (alpha/r) B A ) with one rounding; src (out, in) fp32 / fp16 / uint16 bf16 bits."""
+    src = np.ascontiguousarray(src)
+    r = A.shape[0]
+    out, inn = src.shape
+    assert A.dtype == np.uint16 and B.dtype == np.uint16 and A.shape == (r, inn) and B.shape == (out, r)
+    assert A.flags.c_contiguous and B.flags.c_contiguous
+    slot = np.empty((out, inn), np.uint16)
+    lib().orc_materialize_merge_slot(_ptr(src), dtype_code(src), out, inn, _ptr(A), _ptr(B), r, float(alpha), _ptr(slot))
+    return slot

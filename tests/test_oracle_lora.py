@@ -273,3 +273,48 @@ def test_slot_checksum_closed_form(orc):
     assert orc.slot_checksum(np.full(3, 0xFFFF, np.uint16), 2) == 6 * 0xFFFF
     big = np.full(1 << 20, 0xFFFF, np.uint16)
     assert orc.slot_checksum(big, 1 << 20) == ((1 << 20) * 0xFFFF * (1 << 20)) % (1 << 64)
+
+
+# ---- materialise with the adapter folded in: one rounding from the host-precision source --------------
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_materialize_merge_is_the_fp32_merge_rounded_once(orc, dtype):
+    """Composition of two pinned pieces: the fp32-storage merge (float64 brute force above) and
+    the RNE narrowing (exhaustive pins): slot == bf16(merge_f32(widen(src)))."""
+    rng = np.random.default_rng(21)
+    out, inn, r, alpha = 9, 14, 5, 10.0
+    src = rng.normal(0, 0.5, (out, inn)).astype(dtype)
+    A = bf16_trunc(rng.normal(0, 0.3, (r, inn)))
+    B = bf16_trunc(rng.normal(0, 0.3, (out, r)))
+    got = orc.materialize_merge(src, to_bits(A), to_bits(B), alpha)
+    W = src.astype(np.float32)                       # fp16 -> fp32 is exact
+    orc.lora_merge(W, to_bits(A), to_bits(B), alpha, +1)
+    assert np.array_equal(got, orc.convert_to_bf16(W))
+    # and against float64: a single rounding of the exact value, up to the fp32 chain's error
+    exact = src.astype(np.float64) + (alpha / r) * (B.astype(np.float64) @ A.astype(np.float64))
+    mag = np.abs(src.astype(np.float64)) + (alpha / r) * (np.abs(B).astype(np.float64) @ np.abs(A).astype(np.float64))
+    assert np.all(np.abs(from_bits(got).astype(np.float64) - exact) <= 0.5 * ulp_bf16(exact) * 1.001 + 2e-6 * mag)
+
+
+def test_materialize_merge_rounds_once_where_two_roundings_differ(orc):
+    """src = 1 + 2^-9 + 2^-14 (fp32): converting first gives bf16(1.0 + ...) = 1.0 and loses the
+    tail; adding delta = 2^-9 afterwards gives 1 + 2^-9, below half an ulp -> 1.0.  The single rounding sees
+    1 + 2^-8 + 2^-14 and must round UP to 1 + 2^-7."""
+    src = np.array([[1.0 + 2.0 ** -9 + 2.0 ** -14]], np.float32)
+    A = to_bits(np.array([[2.0 ** -9]], np.float32))
+    B = to_bits(np.array([[1.0]], np.float32))
+    fused = orc.materialize_merge(src, A, B, 1.0)
+    assert from_bits(fused)[0, 0] == np.float32(1.0 + 2.0 ** -7)
+    two_step = orc.convert_to_bf16(src)
+    orc.lora_merge(two_step, A, B, 1.0, +1)
+    assert from_bits(two_step)[0, 0] == np.float32(1.0)
+    # short circuits are plain conversions
+    assert np.array_equal(orc.materialize_merge(src, A, B, 0.0), orc.convert_to_bf16(src))
+    assert np.array_equal(orc.materialize_merge(src, A[:0], B[:, :0], 4.0), orc.convert_to_bf16(src))
+    # bf16 source: identical to the in-place merge
+    sb = to_bits(bf16_trunc(np.array([[0.75, -3.0]], np.float32)))
+    A2 = to_bits(bf16_trunc(np.array([[0.5, 0.25]], np.float32)))
+    B2 = to_bits(np.array([[1.5]], np.float32))
+    w = sb.copy()
+    orc.lora_merge(w, A2, B2, 2.0, +1)
+    assert np.array_equal(orc.materialize_merge(sb, A2, B2, 2.0), w)
