@@ -196,6 +196,23 @@ int tidal_lora_attach(tidal_template* t, const tidal_lora_target* targets /* [ho
 int tidal_lora_swap(tidal_template* t, const tidal_lora_target* targets_new /* [host] */,
                     int32_t n_targets, void* stream);
 
+/* Cold start of a function whose adapter is known while its weights stream in:
+ * tidal_materialize and tidal_lora_attach in one pass.  The dynamic part of initialisation
+ * (Sec. 5.2, adaptive template state reusing) is folded into the load: every targeted slot is
+ * written once, straight from the staged fp32 / fp16 source,
+ *     slot[i][j] = bf16( f32(src[i][j]) + (alpha/r) * sum_k f32(B[i][k]) * f32(A[k][j]) ),
+ * ONE rounding from the host-precision source (convert-then-attach rounds twice) and no
+ * separate read-modify-write pass; a bf16 source is exact in its slot already and is merged in
+ * place after its copy (the same single rounding).  Slots not targeted are converted as by
+ * tidal_materialize.  Afterwards the adapter counts as attached (swap / detach work as after
+ * tidal_lora_attach; detach leaves the slot within the merge-unmerge bound of bf16(src)).
+ * Every active target's slot must be among the sources (TIDAL_E_INVAL); if an adapter is
+ * already attached the sources must cover all its slots (TIDAL_E_STATE otherwise).  Other
+ * errors as for the two calls.  The factors are uploaded on compute_stream first. */
+int tidal_materialize_attach(tidal_template* t, const tidal_src* srcs /* [host] */, int32_t n_src,
+                             const tidal_lora_target* targets /* [host] */, int32_t n_targets,
+                             void* copy_stream, void* compute_stream);
+
 /* Subtract the attached adapter's delta (same packed bf16 copy that was merged). */
 int tidal_lora_detach(tidal_template* t, void* stream);
 

@@ -26,7 +26,7 @@ TIDAL_FLAG_NO_COPY_MERGE = 32
 
 EXPORTS = [
     "tidal_config_default", "tidal_template_required_bytes", "tidal_template_create", "tidal_materialize",
-    "tidal_materialize_plan", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
+    "tidal_materialize_plan", "tidal_materialize_attach", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
     "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_lora_apply_workspace_bytes", "tidal_lora_apply",
     "tidal_fork_required_bytes", "tidal_fork_create",
@@ -105,6 +105,7 @@ def lib() -> ctypes.CDLL:
     L.tidal_template_create.argtypes = [POINTER(tidal_slot_desc), c_int32, vp, c_size_t, POINTER(tidal_config),
                                         POINTER(vp)]
     L.tidal_materialize.argtypes = [vp, POINTER(tidal_src), c_int32, vp, vp]
+    L.tidal_materialize_attach.argtypes = [vp, POINTER(tidal_src), c_int32, POINTER(tidal_lora_target), c_int32, vp, vp]
     L.tidal_materialize_plan.restype = c_int32
     L.tidal_materialize_plan.argtypes = [vp, POINTER(tidal_src), c_int32, c_int32, POINTER(tidal_copy_piece), c_int32]
     for name in ("tidal_lora_attach", "tidal_lora_swap"):
@@ -261,6 +262,12 @@ def tidal_template_create(shapes, dev_arena, arena_bytes: int, cfg: tidal_config
 def tidal_materialize(t, srcs, copy_stream=None, compute_stream=None) -> None:
     arr, n = _src_array(srcs)
     _check(lib().tidal_materialize(t, arr, n, stream_ptr(copy_stream), stream_ptr(compute_stream)))
+
+
+def tidal_materialize_attach(t, srcs, targets, copy_stream=None, compute_stream=None) -> None:
+    arr, n = _src_array(srcs)
+    tarr, tn = _target_array(targets)
+    _check(lib().tidal_materialize_attach(t, arr, n, tarr, tn, stream_ptr(copy_stream), stream_ptr(compute_stream)))
 
 
 def tidal_materialize_plan(t, srcs, assume_pinned: int = 1):

@@ -19,7 +19,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtidal.so")
 
 SOURCES = ["tidal.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip", "lora_lds_kernel.hip",
-           "lora_apply_kernels.hip"]
+           "lora_apply_kernels.hip", "convert_merge_kernel.hip"]
 # per-file extras: the LDS swap kernel wants its MFMA results in VGPRs (see the file's header)
 EXTRA_FLAGS = {"lora_lds_kernel.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 HEADERS = [os.path.join(ROOT, "include", "tidal.h"), os.path.join(CSRC, "tidal_internal.h"),
@@ -56,7 +56,7 @@ def _compile(src: str, force: bool) -> str:
 
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
     if force or _stale(LIB, objs):
         tmp = LIB + ".tmp%d" % os.getpid()

@@ -417,18 +417,23 @@ struct Pipeline {
 
 }  // namespace
 
-extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32_t n_src, void* copy_stream,
-                                 void* compute_stream) {
-    std::vector<SourceInfo> infos;
-    int rc = gather_sources(t, srcs, n_src, 0, &infos);
-    if (rc) return rc;
-    bool clears = false;
-    rc = check_rematerialise(t, infos, &clears);
-    if (rc) return rc;
+static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterRec* newer, hipStream_t stream);
+
+// The streaming loop.  `fuse` (optional): an adapter already packed on the device whose delta is
+// added to its targets' slots while they are written (one rounding from the source).
+static int materialize_impl(tidal_template* t, std::vector<SourceInfo>& infos, bool clears, void* copy_stream,
+                            void* compute_stream, const AdapterRec* fuse) {
     if (infos.empty()) return TIDAL_OK;
-    rc = ensure_device(t);
+    int rc = ensure_device(t);
     if (rc) return rc;
     for (SourceInfo& s : infos) s.pinned = s.elems > 0 && host_is_pinned(s.host);
+    std::vector<const PackedTarget*> fused_of(t->slots.size(), nullptr);
+    if (fuse)
+        for (const PackedTarget& p : fuse->targets)
+            if (p.active() && t->slots[p.slot].elems > 0) fused_of[p.slot] = &p;
+    const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
+    AdapterRec direct;                 // targets whose bf16 source goes straight into the slot: merged afterwards
+    if (fuse) direct.dev = fuse->dev;
 
     std::vector<Piece> plan;
     plan_copies(infos, t->cfg, kMaxConvertSeg, &plan);
@@ -461,15 +466,26 @@ extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32
         if (rc) return rc;
         ConvertBatch batch;
         int nseg = 0;
+        std::vector<FusedPiece> fused;
         for (size_t k = i; k < j; ++k) {
             const Piece& p = plan[k];
             char* slot_dst = slot_ptr(t, p.slot) + 2 * p.elem_offset;
             char* dst = p.staged ? t->arena + t->lay.staging[b] + p.buf_offset : slot_dst;
             rc = pl.put(p.gathered, b, p.buf_offset, p.host, (size_t)p.src_bytes, dst);
             if (rc) return rc;
-            if (p.staged) {
+            const PackedTarget* ft = fused_of[p.slot];
+            if (p.staged && ft) {
+                const SlotState& st = t->slots[p.slot];
+                fused.push_back(FusedPiece{dst, (uint16_t*)slot_ptr(t, p.slot), (const uint16_t*)(fuse->dev + ft->at_off),
+                                           (const uint16_t*)(fuse->dev + ft->bp_off), p.elem_offset, p.elems,
+                                           (int32_t)st.rows, (int32_t)st.cols, p.dtype, ft->r, ft->rp,
+                                           ft->alpha / (float)ft->r});
+                t->stats.converted_elems += (uint64_t)p.elems;
+            } else if (p.staged) {
                 batch.seg[nseg++] = ConvertSegment{dst, slot_dst, p.elems, p.dtype, 0};
                 t->stats.converted_elems += (uint64_t)p.elems;
+            } else if (ft && p.elem_offset == 0) {
+                direct.targets.push_back(*ft);
             }
         }
         rc = pl.copies_done(b, need_bounce, need_staging);
@@ -479,6 +495,7 @@ extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32
             rc = timing_begin(t, pl.compute, &t0);
             if (rc) return rc;
             HIP_TRY(launch_convert(batch, nseg, pl.compute));
+            for (const FusedPiece& fp : fused) HIP_TRY(launch_convert_merge(fp, ordered, pl.compute));
             rc = timing_end(t, pl.compute, t0, false);
             if (rc) return rc;
             rc = pl.consumed(b);
@@ -505,6 +522,12 @@ extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32
     HIP_TRY(hipEventRecord(t->ev_last_compute, pl.compute));
     t->last_compute_rec = true;
     for (const SourceInfo& s : infos) t->slots[s.slot].materialised = true;
+    if (!direct.targets.empty()) {
+        // bf16 sources are exact in the slot already: the in-place merge is the same single rounding
+        rc = launch_rmw(t, nullptr, &direct, pl.compute);
+        if (rc) return rc;
+        HIP_TRY(hipEventRecord(t->ev_last_compute, pl.compute));
+    }
     if (clears) {
         if (t->cur_resident) t->cur_resident->attached = false;
         t->attached = false;
@@ -513,6 +536,17 @@ extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32
         t->cur.targets.clear();
     }
     return TIDAL_OK;
+}
+
+extern "C" int tidal_materialize(tidal_template* t, const tidal_src* srcs, int32_t n_src, void* copy_stream,
+                                 void* compute_stream) {
+    std::vector<SourceInfo> infos;
+    int rc = gather_sources(t, srcs, n_src, 0, &infos);
+    if (rc) return rc;
+    bool clears = false;
+    rc = check_rematerialise(t, infos, &clears);
+    if (rc) return rc;
+    return materialize_impl(t, infos, clears, copy_stream, compute_stream, nullptr);
 }
 
 extern "C" int tidal_template_slot_wait(tidal_template* t, int32_t slot, void* stream) {
@@ -825,6 +859,42 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
     if (rc) return rc;
     AdapterRec old = t->cur;
     rc = do_swap_launch(t, swap ? &old : nullptr, &rec, (hipStream_t)stream);
+    if (rc) return rc;
+    set_attached(t, rec, nullptr, region);
+    return TIDAL_OK;
+}
+
+extern "C" int tidal_materialize_attach(tidal_template* t, const tidal_src* srcs, int32_t n_src,
+                                        const tidal_lora_target* targets, int32_t n_targets, void* copy_stream,
+                                        void* compute_stream) {
+    std::vector<SourceInfo> infos;
+    int rc = gather_sources(t, srcs, n_src, 0, &infos);
+    if (rc) return rc;
+    AdapterRec rec;
+    rc = validate_targets(t, targets, n_targets, true, &rec);
+    if (rc) return rc;
+    bool clears = false;
+    rc = check_rematerialise(t, infos, &clears);
+    if (rc) return rc;
+    if (t->attached && !clears)
+        return fail(TIDAL_E_STATE, "an adapter is attached and this call does not re-materialise its slots");
+    std::vector<char> covered(t->slots.size(), 0);
+    for (const SourceInfo& s : infos) covered[s.slot] = 1;
+    for (const PackedTarget& p : rec.targets)
+        if (p.active() && t->slots[p.slot].elems > 0 && !covered[p.slot])
+            return fail(TIDAL_E_INVAL, "LoRA target slot %d is not among the sources", p.slot);
+    if (rec.bytes > t->cfg.max_adapter_bytes)
+        return fail(TIDAL_E_NOMEM, "packed adapter needs %zu bytes, max_adapter_bytes is %zu", rec.bytes,
+                    t->cfg.max_adapter_bytes);
+    rc = ensure_device(t);
+    if (rc) return rc;
+    const int region = (t->cur_region == 0) ? 1 : 0;
+    rec.dev = t->arena + t->lay.adapter_region[region];
+    // the factors go first, on the compute stream, where the kernels that read them run
+    if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent((hipStream_t)compute_stream, t->ev_last_lora, 0));
+    rc = upload_adapter(t, targets, rec, (hipStream_t)compute_stream);
+    if (rc) return rc;
+    rc = materialize_impl(t, infos, clears, copy_stream, compute_stream, &rec);
     if (rc) return rc;
     set_attached(t, rec, nullptr, region);
     return TIDAL_OK;

@@ -71,6 +71,20 @@ struct LoraGroup {
 hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream);
 hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream);
 
+// ---- materialisation with the adapter folded in --------------------------------------------
+// One staged piece (elements [e0, e0 + n) of a slot, in the source's dtype) of a LoRA target.
+struct FusedPiece {
+    const void* src;         // device staging: the piece in its host dtype (fp32 or fp16)
+    uint16_t* slot;          // slot base: out x in bf16
+    const uint16_t* At;      // in x rp
+    const uint16_t* Bp;      // out x rp
+    int64_t e0, n;
+    int32_t out, in, dtype, r, rp;
+    float s;                 // alpha / r
+};
+// slot[e] = bf16(f32(src[e - e0]) + s * (B A)[e]) for the piece; ordered: k-ascending FMA chain
+hipError_t launch_convert_merge(const FusedPiece& p, bool ordered, hipStream_t stream);
+
 // ---- unmerged adapter apply ---------------------------------------------------------------
 // One entry per run of consecutive tokens that share an adapter.  Adapters live in separate
 // caller-owned allocations, hence full pointers; 80 entries travel in the kernel arguments,
