@@ -1,7 +1,7 @@
 """Measurements of the other workload configurations (bench.py at the repository root times the
 Llama2-7B-shaped headline workload).
 
-    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging|apply
+    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging|apply|coldstart
 
 Each prints one JSON line.  Kernel times come from the library's HIP events around each launch
 (TIDAL_FLAG_KERNEL_TIMING); call-level times from events on the compute stream.
@@ -160,6 +160,46 @@ def bench_stack(args, wl, pool_limit=None):
             "attach_ms_per_invocation": round(att_ms, 3), "attach_kernel_ms": round(k_ms, 4),
             "attach_launches": att[-1][2], "lora_algorithmic_GB": round(b / 1e9, 3),
             "lora_kernel_GBps": round(b / k_ms / 1e6, 1), "frac_of_hbm_peak": round(b / k_ms / 1e6 / HBM_PEAK, 4)})
+    finally:
+        T.close()
+    return out
+
+
+def bench_coldstart(args):
+    """Cold start of the Llama2-7B-shaped function with its adapter known at load time: the load
+    followed by an attach, against tidal_materialize_attach, which folds the adapter into the
+    conversion (one rounding from the fp16 source, no read-modify-write pass)."""
+    wl = wl_mod.llama2_7b()
+    pool = hz.HostPool(wl)
+    items, keep = hz.pinned_adapter(wl, 0)
+    T = hz.DeviceTemplate(wl.shapes, max_adapter_bytes=hz.packed_adapter_bytes(wl), flags=tb.TIDAL_FLAG_KERNEL_TIMING)
+    out = {"config": wl.name + "_coldstart", "source_GB": round(wl.source_bytes / 1e9, 3)}
+    try:
+        srcs = pool.sources()
+        tg = tb.targets_from_arrays(items)
+        res = {"two_calls": [], "fused": []}
+        for rep in range(args.reps + 1):
+            for mode in ("two_calls", "fused"):
+                tb.tidal_reset_stats(T.h)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                if mode == "fused":
+                    tb.tidal_materialize_attach(T.h, srcs, tg, T.copy_stream, T.compute_stream)
+                else:
+                    tb.tidal_materialize(T.h, srcs, T.copy_stream, T.compute_stream)
+                    tb.tidal_lora_attach(T.h, tg, T.compute_stream)
+                T.sync()
+                ms = (time.perf_counter() - t0) * 1e3
+                st = tb.tidal_get_stats(T.h)
+                log("rep %d %s: %.2f ms (convert kernels %.2f ms, LoRA kernels %.3f ms, %d LoRA launches)" %
+                    (rep, mode, ms, st["convert_kernel_ms"], st["lora_kernel_ms"], st["lora_launches"]))
+                if rep > 0:
+                    res[mode].append((ms, st["convert_kernel_ms"], st["lora_kernel_ms"]))
+        for mode, r in res.items():
+            out[mode] = {"ms": round(float(np.median([x[0] for x in r])), 2),
+                         "GBps": round(wl.source_bytes / float(np.median([x[0] for x in r])) / 1e6, 2),
+                         "convert_kernel_ms": round(float(np.median([x[1] for x in r])), 2),
+                         "lora_kernel_ms": round(float(np.median([x[2] for x in r])), 3)}
     finally:
         T.close()
     return out
@@ -429,7 +469,7 @@ def bench_apply(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply"])
+    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply", "coldstart"])
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
     ap.add_argument("--layers", type=int, default=32, help="apply: distinct layers (sets of factors and activations) per pass")
@@ -449,6 +489,8 @@ def main():
         out = bench_merging(args)
     elif args.config == "apply":
         out = bench_apply(args)
+    elif args.config == "coldstart":
+        out = bench_coldstart(args)
     else:
         out = bench_churn(args)
     print(json.dumps(out), flush=True)
