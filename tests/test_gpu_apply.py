@@ -175,3 +175,25 @@ def test_apply_rejects_bad_arguments():
         bad(tb.TIDAL_E_NOMEM, T.h, 0, handles, [(0, 0, 4)], X, Y, 8, ws, nb - 1)               # workspace
         torch.cuda.synchronize()
         assert np.array_equal(host(Y), y0)                                                     # nothing ran
+
+
+@pytest.mark.parametrize("seed", [101, 102, 103])
+def test_random_batches(orc, seed):
+    """Seeded random mixes of prompts and decode steps, ranks and gaps."""
+    rng = np.random.default_rng(seed)
+    out, inn = int(rng.choice([136, 264, 512])), int(rng.choice([72, 200, 448]))
+    with Template([(out, inn)]) as T:
+        ranks = [int(r) for r in rng.choice([1, 2, 7, 8, 16, 17, 32, 48, 64], size=5)]
+        items, handles = make_adapters(T, rng, 0, ranks, [2.0 * r for r in ranks])
+        segs, t = [], 0
+        for _ in range(int(rng.integers(20, 120))):
+            n = int(rng.choice([1, 1, 1, 2, 3, 4, 5, 6, 31, 32, 33, 64, 100, 130]))
+            if rng.random() < 0.15:
+                t += int(rng.integers(1, 4))              # tokens without an adapter
+            segs.append((int(rng.integers(-1, 5)), t, t + n))
+            t += n
+        order = rng.permutation(len(segs))
+        X = bf16_bits(rng, (t, inn), 1.0)
+        Y = bf16_bits(rng, (t, out), 1.0)
+        got = run_apply(T, 0, handles, [segs[i] for i in order], X, Y)
+        check(orc, items, segs, X, Y, got)

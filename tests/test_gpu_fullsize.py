@@ -6,7 +6,9 @@ Llama2-7B-shaped stack (13.48 GB fp16 -> bf16, r=16 on q and v of 32 layers):
   * after attach and after swap, three 64-row bands (top, a ragged middle, bottom) of every
     targeted slot are recomputed by the oracle from the GPU's previous state and compared
     within 2^-7 * max|W| (and one bf16 ulp per element),
-  * every untargeted slot must be bit-identical to its materialised state (compared on device).
+  * every untargeted slot must be bit-identical to its materialised state (compared on device),
+  * a second cold start with the adapter folded into the load (tidal_materialize_attach) is
+    checked on the same bands against the oracle's one-rounding result from the fp16 source.
 """
 import numpy as np
 import pytest
@@ -115,6 +117,26 @@ def test_llama2_7b_shaped_materialize_attach_swap(orc):
         assert st["lora_launches"] == 2 and st["rmw_elems"] == 2 * wl.lora_w_elements
         # 201 chunks of 64 MiB for the stack; an adapter upload packs at most 32 factors per chunk
         assert st["chunks"] == -(-wl.source_bytes // (64 << 20)) + 2 * (2 * len(wl.lora_slots) // 32)
+
+        # cold start again, adapter 0 folded into the load (re-materialising resets the template)
+        tb.tidal_materialize_attach(T, [(i, wl.host_dtype, tb.host_ptr(v)) for i, v in enumerate(views)],
+                                    tb.targets_from_arrays(ads[0]), copy_s, comp_s)
+        tb.tidal_template_sync(T)
+        torch.cuda.synchronize()
+        worst = 0.0
+        for idx, s in enumerate(wl.lora_slots):
+            _, al, A, B = ads[0][idx]
+            for b in bands:
+                want = orc.materialize_merge(views[s][b[0]:b[1]], orc.convert_to_bf16(A), orc.convert_to_bf16(B[b[0]:b[1]]), al)
+                got = host_rows(s, *b)
+                g, w = f32(got), f32(want)
+                assert np.max(np.abs(g - w)) <= 2.0 ** -7 * np.max(np.abs(w)), ("fused", s, b)
+                assert np.mean(got != want) < 2e-3, ("fused", s, b)
+                assert np.mean(got != orc.convert_to_bf16(views[s][b[0]:b[1]])) > 0.3, ("fused", s, b)
+                worst = max(worst, float(np.max(np.abs(g - w)) / np.max(np.abs(w))))
+        print("fused cold start: %d bands checked, worst max-abs-err / max|W| = %.3g" % (len(prev), worst), flush=True)
+        untouched()
+        assert tb.tidal_get_stats(T)["lora_launches"] == 2                     # no read-modify-write pass was added
     finally:
         torch.cuda.synchronize()
         tb.tidal_template_destroy(T)
