@@ -119,10 +119,12 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     return hipGetLastError();
 }
 
-// A strips stay in registers below this many 16-rank steps in total (measured: >= 6.0 TB/s for
-// every rank pair but 64 -> 64); from it on they are staged in LDS by a kernel built in its own
-// translation unit (64 -> 64: 6.4 instead of 4.7 TB/s).
+// A strips stay in registers except where one side has 64 ranks and the other 64 or at most 16:
+// there they are staged in LDS by a kernel built in its own translation unit (measured on
+// 128 x 4096^2: 64 -> 64 6.4 instead of 4.7 TB/s, 64 <-> 8/16 about 3 % more, 64 <-> 32 about 4 %
+// less, hence not used there).
 hipError_t launch_lora_mfma_lds(const LoraGroup& g, hipStream_t stream);
+bool lora_mfma_lds_available(int rp_old, int rp_new);
 constexpr int kLdsFromSteps = 8;
 
 template <int NT, int KS0, int KS1>
@@ -134,8 +136,8 @@ static hipError_t launch_mfma_pick(const LoraGroup& g, hipStream_t stream, int u
             if (g.fork) return launch_mfma_inst<NT, 0, KS1, true>(g, stream);
         }
         if (g.fork) return hipErrorInvalidValue;
-        if (use_lds < 0) use_lds = (KS0 + KS1 >= kLdsFromSteps) ? 1 : 0;
-        if (use_lds && NT == 8 && KS0 == 4 && KS1 == 4) return launch_lora_mfma_lds(g, stream);
+        if (use_lds < 0) use_lds = (KS0 + KS1 >= kLdsFromSteps || (KS0 == 4 && KS1 == 1) || (KS0 == 1 && KS1 == 4)) ? 1 : 0;
+        if (use_lds && NT == 8 && lora_mfma_lds_available(16 * KS0, 16 * KS1)) return launch_lora_mfma_lds(g, stream);
         return launch_mfma_inst<NT, KS0, KS1>(g, stream);
     }
 }

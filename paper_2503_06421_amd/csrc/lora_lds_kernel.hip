@@ -1,4 +1,4 @@
-// LoRA fused swap for the largest ranks (64 -> 64): A strips staged in LDS.  gfx950 only.
+// LoRA fused swap where one adapter has 64 ranks: A strips staged in LDS.  gfx950 only.
 //
 // This file is compiled with -mllvm -amdgpu-mfma-vgpr-form: the MFMA results land in ordinary
 // VGPRs, which saves one accumulator-read instruction per element and, here, lets two waves
@@ -117,8 +117,16 @@ static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
 }
 
 
+bool lora_mfma_lds_available(int rp_old, int rp_new) {
+    return (rp_old == 64 && rp_new >= 16) || (rp_new == 64 && rp_old >= 16);
+}
+
 hipError_t launch_lora_mfma_lds(const LoraGroup& g, hipStream_t stream) {
     if (g.rp_old == 64 && g.rp_new == 64) return launch_mfma_lds_inst<8, 4, 4>(g, stream);
+    if (g.rp_old == 64 && g.rp_new == 32) return launch_mfma_lds_inst<8, 4, 2>(g, stream);
+    if (g.rp_old == 64 && g.rp_new == 16) return launch_mfma_lds_inst<8, 4, 1>(g, stream);
+    if (g.rp_old == 32 && g.rp_new == 64) return launch_mfma_lds_inst<8, 2, 4>(g, stream);
+    if (g.rp_old == 16 && g.rp_new == 64) return launch_mfma_lds_inst<8, 1, 4>(g, stream);
     return hipErrorInvalidValue;
 }
 

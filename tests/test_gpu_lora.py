@@ -295,3 +295,30 @@ def test_single_linear_full_size_attach_then_swap(orc, G, flags):
         back = f32(T.slot(0)).astype(np.float64)
         w0 = f32(orc.convert_to_bf16(x)).astype(np.float64)
         assert np.max(np.abs(back - w0)) <= 2.0 ** -7 * np.max(np.abs(w0))
+
+
+@pytest.mark.parametrize("r_old", [8, 16, 32, 64])
+@pytest.mark.parametrize("r_new", [8, 16, 32, 64])
+def test_every_rank_pair_fused_swap(orc, G, r_old, r_new):
+    """Each (old, new) padded-rank pair is its own kernel instantiation (some stage the A strips
+    in LDS): against the oracle, and bit for bit against the two-pass swap, on a ragged shape."""
+    out, inn = 150, 530
+    W, A0, B0 = make_problem(50 + r_old, out, inn, r_old, wscale=0.05, ascale=0.05)
+    _, A1, B1 = make_problem(90 + r_new, out, inn, r_new, wscale=0.05, ascale=0.05)
+    res = []
+    for extra in (0, tb.TIDAL_FLAG_TWO_PASS_SWAP):
+        with G.Template([(out, inn)], max_adapter_bytes=1 << 20, flags=extra) as T:
+            T.materialize({0: W})
+            T.attach([(0, 2.0 * r_old, A0, B0)])
+            before = T.slot(0)
+            T.swap([(0, 2.0 * r_new, A1, B1)])
+            res.append(T.slot(0))
+    assert np.array_equal(res[0], res[1])
+    want = before.copy()
+    orc.lora_swap(want, *oracle_adapter(orc, A0, B0), 2.0 * r_old, *oracle_adapter(orc, A1, B1), 2.0 * r_new)
+    # two roundings: where the intermediate W - delta_old is larger than the final value, a one-ulp
+    # difference there is several ulps of the result, so only the tensor-level bound applies
+    g, w = f32(res[0]).astype(np.float64), f32(want).astype(np.float64)
+    assert np.max(np.abs(g - w)) <= TOL * np.max(np.abs(w))
+    assert np.mean(res[0] != want) < 5e-3
+    assert np.mean(res[0] != before) > 0.5
