@@ -258,6 +258,17 @@ int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_adapter* const
                      int32_t n_adapters, const tidal_lora_segment* segments /* [host] */, int32_t n_segments,
                      const void* x /* [device] */, void* y /* [device] in/out */, int32_t n_tokens,
                      void* workspace /* [device] */, size_t workspace_bytes, void* stream);
+/* The same for several target slots that read the same x (the query, key and value projections
+ * of a layer) in one set of launches: ys[k] is the output of slots[k] (n_tokens x rows of that
+ * slot).  The slots must have the same number of input columns and every adapter must target
+ * all of them; the workspace must hold tidal_lora_apply_workspace_bytes(n_tokens * n_slots).
+ * Results are identical to one tidal_lora_apply per slot; small batches, whose kernels are
+ * bound by launch and latency rather than bandwidth, cost about the same as a single call. */
+int tidal_lora_apply_multi(tidal_template* t, const int32_t* slots /* [host] */, int32_t n_slots,
+                           const tidal_adapter* const* adapters /* [host] */, int32_t n_adapters,
+                           const tidal_lora_segment* segments /* [host] */, int32_t n_segments,
+                           const void* x /* [device] */, void* const* ys /* [host] array of [device] in/out */,
+                           int32_t n_tokens, void* workspace /* [device] */, size_t workspace_bytes, void* stream);
 
 /* Copy-on-write forks (Sec. 1: a template must stay request-agnostic, "a copy-on-write
  * mechanism is critical for safe template sharing"; Sec. 5.2: a write to a forked weight goes

@@ -28,7 +28,7 @@ EXPORTS = [
     "tidal_config_default", "tidal_template_required_bytes", "tidal_template_create", "tidal_materialize",
     "tidal_materialize_plan", "tidal_materialize_attach", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
-    "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_lora_apply_workspace_bytes", "tidal_lora_apply",
+    "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_lora_apply_workspace_bytes", "tidal_lora_apply", "tidal_lora_apply_multi",
     "tidal_fork_required_bytes", "tidal_fork_create",
     "tidal_fork_apply", "tidal_fork_slot_ptr", "tidal_fork_destroy", "tidal_template_slot_ptr",
     "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
@@ -121,6 +121,8 @@ def lib() -> ctypes.CDLL:
     L.tidal_lora_apply_workspace_bytes.argtypes = [c_int32]
     L.tidal_lora_apply.argtypes = [vp, c_int32, POINTER(vp), c_int32, POINTER(tidal_lora_segment), c_int32, vp, vp,
                                    c_int32, vp, c_size_t, vp]
+    L.tidal_lora_apply_multi.argtypes = [vp, POINTER(c_int32), c_int32, POINTER(vp), c_int32, POINTER(tidal_lora_segment),
+                                         c_int32, vp, POINTER(vp), c_int32, vp, c_size_t, vp]
     L.tidal_fork_required_bytes.restype = c_size_t
     L.tidal_fork_required_bytes.argtypes = [vp, POINTER(c_int32), c_int32]
     L.tidal_fork_create.argtypes = [vp, POINTER(c_int32), c_int32, vp, c_size_t, POINTER(vp)]
@@ -338,6 +340,20 @@ def tidal_lora_apply(t, slot: int, adapters, segments, x, y, n_tokens: int, work
         adapters, segments = lora_apply_arrays(adapters, segments)
     _check(lib().tidal_lora_apply(t, slot, adapters[0], adapters[1], segments[0], segments[1], device_ptr(x),
                                   device_ptr(y), n_tokens, device_ptr(workspace), workspace_bytes, stream_ptr(stream)))
+
+
+def tidal_lora_apply_multi(t, slots, adapters, segments, x, ys, n_tokens: int, workspace, workspace_bytes: int,
+                           stream=None) -> None:
+    """Several target slots reading the same x; ys: one output per slot."""
+    if not (isinstance(adapters, tuple) and isinstance(segments, tuple) and len(segments) == 2
+            and isinstance(segments[0], ctypes.Array)):
+        adapters, segments = lora_apply_arrays(adapters, segments)
+    slots = list(slots)
+    sl = (c_int32 * max(1, len(slots)))(*slots)
+    yarr = (c_void_p * max(1, len(slots)))(*[device_ptr(y) for y in ys])
+    _check(lib().tidal_lora_apply_multi(t, sl, len(slots), adapters[0], adapters[1], segments[0], segments[1],
+                                        device_ptr(x), yarr, n_tokens, device_ptr(workspace), workspace_bytes,
+                                        stream_ptr(stream)))
 
 
 def _slot_list(slots):

@@ -36,19 +36,50 @@
 //    tokens' u rows are broadcast reads.  The sum runs over k in ascending order on the vector
 //    ALUs.
 //
-// HBM traffic: x once, y read and written once, the factors once per adapter and launch (L2
+// A call may cover up to 4 target slots that read the same x (the query, key and value
+// projections of a layer).
+//
+// HBM traffic: x once per slot, y read and written once, the factors once per adapter and launch (L2
 // serves tiles that share one), u is a few KB per tile.
 #include "lora_device.h"
 
 namespace tidal {
 
-// Segment that owns work unit `unit`: the number of later segments whose first unit is <= unit.
+// Entry that owns work unit `unit`: the number of later entries whose first unit is <= unit.
 // Uniform per wave; the reads do not depend on each other.
-__device__ __forceinline__ int find_segment(const ApplyBatch& batch, int unit) {
+__device__ __forceinline__ int find_entry(const ApplyLongBatch& batch, int unit) {
     int si = 0;
 #pragma unroll
-    for (int k = 1; k < kMaxApplySegs; ++k) si += batch.first[k] <= unit ? 1 : 0;
+    for (int k = 1; k < kMaxApplyLong; ++k) si += batch.first[k] <= unit ? 1 : 0;
     return si;
+}
+
+// One (short segment, slot) pair with its tables resolved.
+struct ApplyEntry {
+    const uint16_t* Ar;
+    const uint16_t* Bp;
+    uint16_t* y;
+    int t0, rows;
+    float s;
+    int r, rp, out;
+    uint32_t u_tok;
+};
+__device__ __forceinline__ ApplyEntry resolve(const ApplyShortBatch& batch, int si, int slot) {
+    const ApplyShortSeg g = batch.seg[si];
+    const ApplyFactor f = batch.fac[g.fac + slot];
+    const ApplySlot sl = batch.slot[slot];
+    ApplyEntry e;
+    e.Ar = (const uint16_t*)(batch.adapter_base + (size_t)f.ar * kLoraUnit);
+    e.Bp = (const uint16_t*)(batch.adapter_base + (size_t)f.bp * kLoraUnit);
+    e.y = sl.y;
+    e.t0 = g.t0;
+    e.rows = g.rows;
+    e.s = f.s;
+    e.r = f.r;
+    e.rp = f.rp;
+    e.out = sl.out;
+    e.u_tok = sl.u_tok;
+    return e;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -151,13 +182,13 @@ __device__ __forceinline__ void shrink_walk(const uint16_t* __restrict__ x, cons
     }
 }
 
-__global__ __launch_bounds__(64 * kShrinkWaves) void apply_shrink_kernel(const ApplyBatch batch, int in) {
+__global__ __launch_bounds__(64 * kShrinkWaves) void apply_shrink_kernel(const ApplyLongBatch batch, int in) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[kShrinkLds];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int si = find_segment(batch, blockIdx.x);
-    const ApplySeg sg = batch.seg[si];
-    const int tile0 = sg.t0 + 32 * ((int)blockIdx.x - batch.first[si]);    // first token of this tile
+    const int si = find_entry(batch, blockIdx.x);
+    const ApplyLongEntry sg = batch.e[si];
+    const int tile0 = sg.t0 + 32 * ((int)blockIdx.x - batch.first[si]);   // first token of this tile
     const int rows = sg.t1 - tile0 < 32 ? sg.t1 - tile0 : 32;
     const uint16_t* x = batch.x + (int64_t)tile0 * in;
     uint16_t* stage = (uint16_t*)(lds + wave * kStageBytes);
@@ -188,7 +219,7 @@ __global__ __launch_bounds__(64 * kShrinkWaves) void apply_shrink_kernel(const A
         if (two) part[((wave * 2 + 1) * 32 + row) * 32 + n] = c1[v];
     }
     __syncthreads();
-    uint32_t* u = (uint32_t*)(batch.u + (int64_t)sg.t0 * kApplyRankStride + (int64_t)(tile0 - sg.t0) * sg.rp);
+    uint32_t* u = (uint32_t*)(batch.u + ((int64_t)sg.u_tok + sg.t0) * kApplyRankStride + (int64_t)(tile0 - sg.t0) * sg.rp);
     const int pairs_per_row = sg.rp >> 1;
     const int pairs = rows * pairs_per_row;
     for (int e = threadIdx.x; e < pairs; e += 64 * kShrinkWaves) {
@@ -205,9 +236,9 @@ __global__ __launch_bounds__(64 * kShrinkWaves) void apply_shrink_kernel(const A
     }
 }
 
-hipError_t launch_apply_shrink(const ApplyBatch& b, int n_tiles, int in, hipStream_t stream) {
+hipError_t launch_apply_shrink(const ApplyLongBatch& b, int n_tiles, int in, hipStream_t stream) {
     if (n_tiles <= 0) return hipSuccess;
-    if (b.n_segs <= 0 || b.n_segs > kMaxApplySegs || in <= 0 || in % 8) return hipErrorInvalidValue;
+    if (b.n <= 0 || b.n > kMaxApplyLong || in <= 0 || in % 8) return hipErrorInvalidValue;
     hipLaunchKernelGGL(apply_shrink_kernel, dim3((unsigned)n_tiles), dim3(64 * kShrinkWaves), 0, stream, b, in);
     return hipGetLastError();
 }
@@ -228,14 +259,15 @@ __device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
 // pieces (1 KB per wave-wide load, fully coalesced), multiply with the segment's x rows and
 // reduce across lanes once per token at the end.  Four rank rows per workgroup, so a decode
 // batch of 64 requests at rank 16 is 256 workgroups whose loads are all independent.
-__global__ __launch_bounds__(256) void apply_shrink_short_kernel(const ApplyBatch batch, int in) {
+__global__ __launch_bounds__(256) void apply_shrink_short_kernel(const ApplyShortBatch batch, int in) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int si = blockIdx.x >> 4;                               // 16 workgroups per segment: 64 rank rows
+    const int e = blockIdx.x >> 4;                                // 16 workgroups per (segment, slot): 64 rank rows
     const int k = ((blockIdx.x & 15) << 2) + wave;
-    const ApplySeg sg = batch.seg[si];
-    if (k >= sg.rp) return;
-    const int rows = sg.t1 - sg.t0;                               // 1 .. kApplyShortRows
+    const int si = e / batch.n_slots;
+    const ApplyEntry sg = resolve(batch, si, e - si * batch.n_slots);
+    if (sg.r == 0 || k >= sg.rp) return;
+    const int rows = sg.rows;                                     // 1 .. kApplyShortRows
     float acc[kApplyShortRows];
 #pragma unroll
     for (int t = 0; t < kApplyShortRows; ++t) acc[t] = 0.0f;
@@ -268,15 +300,16 @@ __global__ __launch_bounds__(256) void apply_shrink_short_kernel(const ApplyBatc
 #pragma unroll
         for (int t = 1; t < kApplyShortRows; ++t) v = lane == t ? acc[t] : v;
         const f32x2 r2 = {v, 0.0f};
-        as_global(batch.u)[(int64_t)sg.t0 * kApplyRankStride + lane * sg.rp + k] =
+        as_global(batch.u)[((int64_t)sg.u_tok + sg.t0) * kApplyRankStride + lane * sg.rp + k] =
             (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
     }
 }
 
-hipError_t launch_apply_shrink_short(const ApplyBatch& b, int in, hipStream_t stream) {
+hipError_t launch_apply_shrink_short(const ApplyShortBatch& b, int in, hipStream_t stream) {
     if (b.n_segs <= 0) return hipSuccess;
-    if (b.n_segs > kMaxApplySegs || in <= 0 || in % 8) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(apply_shrink_short_kernel, dim3((unsigned)(b.n_segs * 16)), dim3(256), 0, stream, b, in);
+    if (b.n_segs > kMaxApplyShort || b.n_slots <= 0 || b.n_slots > kMaxApplySlots || in <= 0 || in % 8)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(apply_shrink_short_kernel, dim3((unsigned)(b.n_segs * b.n_slots * 16)), dim3(256), 0, stream, b, in);
     return hipGetLastError();
 }
 
@@ -284,8 +317,9 @@ hipError_t launch_apply_shrink_short(const ApplyBatch& b, int in, hipStream_t st
 // expand, matrix cores
 // ---------------------------------------------------------------------------------------
 template <int KS>
-__device__ __forceinline__ void expand_walk(const ApplyBatch& batch, const ApplySeg& sg, int t_begin, int chunk_rows,
-                                            int out, int j0, int lane) {
+__device__ __forceinline__ void expand_walk(const ApplyLongBatch& batch, const ApplyLongEntry& sg, int t_begin,
+                                            int chunk_rows, int j0, int lane) {
+    const int out = sg.out;
     constexpr int NT = 8;
     bf16x8 bop[NT][KS];
     load_strip<NT, KS>(sg.Bp, out, j0, lane, bop);               // rows of B for the lane's 8 outputs
@@ -295,8 +329,8 @@ __device__ __forceinline__ void expand_walk(const ApplyBatch& batch, const Apply
     const int t_end = sg.t1 < t_begin + chunk_rows ? sg.t1 : t_begin + chunk_rows;
     for (int t = t_begin; t < t_end; t += 32) {
         const int rows = t_end - t < 32 ? t_end - t : 32;
-        const uint16_t* u = batch.u + (int64_t)sg.t0 * kApplyRankStride + (int64_t)(t - sg.t0) * sg.rp;
-        uint16_t* y = batch.y + (int64_t)t * out;
+        const uint16_t* u = batch.u + ((int64_t)sg.u_tok + sg.t0) * kApplyRankStride + (int64_t)(t - sg.t0) * sg.rp;
+        uint16_t* y = sg.y + (int64_t)t * out;
         const bool full = strip_full && rows == 32;
         uint32_t w[16][NT / 2];
         load_block<NT>(y, rows, out, 0, jl, h, full, w);
@@ -307,39 +341,41 @@ __device__ __forceinline__ void expand_walk(const ApplyBatch& batch, const Apply
     }
 }
 
+// KS = padded rank / 16 of every entry of the launch (one kernel with all three bodies would need
+// the registers of the largest and run the small ranks at half their occupancy).
 template <int KS>
-__global__ __launch_bounds__(256) void apply_expand_kernel(const ApplyBatch batch, int n_chunks, int chunk_rows, int out,
+__global__ __launch_bounds__(256) void apply_expand_kernel(const ApplyLongBatch batch, int n_chunks, int chunk_rows,
                                                            int strips) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int item = blockIdx.x * 4 + wave;
-    if (item >= n_chunks * strips) return;
+    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+    if (item >= (int64_t)n_chunks * strips) return;
     // the four waves of a workgroup take neighbouring strips of one chunk: adjacent pieces of the same y rows
-    const int chunk = item / strips;
-    const int strip = item - chunk * strips;
-    const int si = find_segment(batch, chunk);
-    const ApplySeg sg = batch.seg[si];
+    const int chunk = (int)(item / strips);
+    const int strip = (int)(item - (int64_t)chunk * strips);
+    const int si = find_entry(batch, chunk);
+    const ApplyLongEntry sg = batch.e[si];
+    if (strip * 256 >= sg.out) return;                            // strips are counted for the widest slot
     const int t_begin = sg.t0 + chunk_rows * (chunk - batch.first[si]);
-    expand_walk<KS>(batch, sg, t_begin, chunk_rows, out, strip * 256, lane);
+    expand_walk<KS>(batch, sg, t_begin, chunk_rows, strip * 256, lane);
 }
 
-// All segments of the batch have the padded rank rp.
-hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int chunk_tiles, int out, int rp,
+// rp: the padded rank of every entry of the launch
+hipError_t launch_apply_expand(const ApplyLongBatch& b, int n_chunks, int chunk_tiles, int max_out, int rp,
                                hipStream_t stream) {
     if (n_chunks <= 0) return hipSuccess;
-    if (b.n_segs <= 0 || b.n_segs > kMaxApplySegs || out <= 0 || out % 8 || chunk_tiles < 1) return hipErrorInvalidValue;
-    const int chunk_rows = 32 * chunk_tiles;
-    const int strips = (out + 255) / 256;
+    if (b.n <= 0 || b.n > kMaxApplyLong || max_out <= 0 || chunk_tiles < 1) return hipErrorInvalidValue;
+    for (int k = 0; k < b.n; ++k)
+        if (b.e[k].out <= 0 || b.e[k].out % 8 || b.e[k].out > max_out || b.e[k].rp != rp) return hipErrorInvalidValue;
+    const int strips = (max_out + 255) / 256;
     const int64_t items = (int64_t)n_chunks * strips;
-    if (items > 0x7FFFFFF0) return hipErrorInvalidValue;
+    if ((items + 3) / 4 > 0x7FFFFFF0) return hipErrorInvalidValue;
     const dim3 grid((unsigned)((items + 3) / 4));
+    const int chunk_rows = 32 * chunk_tiles;
     switch (rp) {
-        case 16: hipLaunchKernelGGL(apply_expand_kernel<1>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, out,
-                                    strips); break;
-        case 32: hipLaunchKernelGGL(apply_expand_kernel<2>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, out,
-                                    strips); break;
-        case 64: hipLaunchKernelGGL(apply_expand_kernel<4>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, out,
-                                    strips); break;
+        case 16: hipLaunchKernelGGL(apply_expand_kernel<1>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, strips); break;
+        case 32: hipLaunchKernelGGL(apply_expand_kernel<2>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, strips); break;
+        case 64: hipLaunchKernelGGL(apply_expand_kernel<4>, grid, dim3(256), 0, stream, b, n_chunks, chunk_rows, strips); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -348,20 +384,22 @@ hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int chunk_tile
 // ---------------------------------------------------------------------------------------
 // expand, few tokens per segment: one lane per output
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyBatch batch, int out, int blocks_per_seg) {
-    const int si = blockIdx.x / blocks_per_seg;
-    const int i = (blockIdx.x - si * blocks_per_seg) * 256 + threadIdx.x;
-    if (i >= out) return;
-    const ApplySeg sg = batch.seg[si];
-    const int rows = sg.t1 - sg.t0;                               // 1 .. kApplyShortRows
-    const uint16_t* u = batch.u + (int64_t)sg.t0 * kApplyRankStride;
+__global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyShortBatch batch, int blocks_per_seg) {
+    const int e = blockIdx.x / blocks_per_seg;                    // (segment, slot), slots fastest
+    const int i = (blockIdx.x - e * blocks_per_seg) * 256 + threadIdx.x;
+    const int si = e / batch.n_slots;
+    const ApplyEntry sg = resolve(batch, si, e - si * batch.n_slots);
+    const int out = sg.out;
+    if (sg.r == 0 || i >= out) return;
+    const int rows = sg.rows;                                     // 1 .. kApplyShortRows
+    const uint16_t* u = batch.u + ((int64_t)sg.u_tok + sg.t0) * kApplyRankStride;
     const uint16_t* brow = sg.Bp + (int64_t)i * sg.rp;
     float acc[kApplyShortRows], yv[kApplyShortRows];
 #pragma unroll
     for (int t = 0; t < kApplyShortRows; ++t) {
         acc[t] = 0.0f;
         yv[t] = 0.0f;
-        if (t < rows) yv[t] = __uint_as_float((uint32_t)as_global(batch.y)[(int64_t)(sg.t0 + t) * out + i] << 16);
+        if (t < rows) yv[t] = __uint_as_float((uint32_t)as_global(sg.y)[(int64_t)(sg.t0 + t) * out + i] << 16);
     }
     for (int k0 = 0; k0 < sg.rp; k0 += 8) {
         float b8[8];
@@ -382,18 +420,18 @@ __global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyBatc
     for (int t = 0; t < kApplyShortRows; ++t) {
         if (t < rows) {
             const f32x2 r2 = {__builtin_fmaf(sg.s, acc[t], yv[t]), 0.0f};
-            as_global(batch.y)[(int64_t)(sg.t0 + t) * out + i] =
+            as_global(sg.y)[(int64_t)(sg.t0 + t) * out + i] =
                 (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
         }
     }
 }
 
-hipError_t launch_apply_expand_short(const ApplyBatch& b, int out, hipStream_t stream) {
+hipError_t launch_apply_expand_short(const ApplyShortBatch& b, int max_out, hipStream_t stream) {
     if (b.n_segs <= 0) return hipSuccess;
-    if (b.n_segs > kMaxApplySegs || out <= 0) return hipErrorInvalidValue;
-    const int blocks_per_seg = (out + 255) / 256;
-    hipLaunchKernelGGL(apply_expand_short_kernel, dim3((unsigned)(b.n_segs * blocks_per_seg)), dim3(256), 0, stream, b,
-                       out, blocks_per_seg);
+    if (b.n_segs > kMaxApplyShort || b.n_slots <= 0 || b.n_slots > kMaxApplySlots || max_out <= 0) return hipErrorInvalidValue;
+    const int blocks_per_seg = (max_out + 255) / 256;
+    hipLaunchKernelGGL(apply_expand_short_kernel, dim3((unsigned)(b.n_segs * b.n_slots * blocks_per_seg)), dim3(256), 0,
+                       stream, b, blocks_per_seg);
     return hipGetLastError();
 }
 

@@ -941,27 +941,42 @@ extern "C" size_t tidal_lora_apply_workspace_bytes(int32_t n_tokens) {
     return align_up((size_t)n_tokens * kApplyRankStride * 2, kSlotAlign);
 }
 
-extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_adapter* const* adapters,
-                                int32_t n_adapters, const tidal_lora_segment* segs, int32_t n_segs, const void* x,
-                                void* y, int32_t n_tokens, void* workspace, size_t workspace_bytes, void* stream_) {
+static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_slots,
+                           const tidal_adapter* const* adapters, int32_t n_adapters, const tidal_lora_segment* segs,
+                           int32_t n_segs, const void* x, void* const* ys, int32_t n_tokens, void* workspace,
+                           size_t workspace_bytes, void* stream_) {
     if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
-    if (slot < 0 || slot >= (int32_t)t->slots.size()) return fail(TIDAL_E_INVAL, "slot %d out of range", slot);
+    if (n_slots < 0 || (!slots && n_slots > 0)) return fail(TIDAL_E_INVAL, "bad slot list");
     if (n_adapters < 0 || (!adapters && n_adapters > 0)) return fail(TIDAL_E_INVAL, "bad adapter list");
     if (n_segs < 0 || (!segs && n_segs > 0)) return fail(TIDAL_E_INVAL, "bad segment list");
     if (n_tokens < 0) return fail(TIDAL_E_INVAL, "n_tokens is negative");
-    const SlotState& st = t->slots[slot];
-    if (st.rows > 0x7FFFFFFF || st.cols > 0x7FFFFFFF) return fail(TIDAL_E_INVAL, "slot %d is too large", slot);
-    const int out = (int)st.rows, in = (int)st.cols;
-    if (st.elems > 0 && (in % 8 || out % 8))
-        return fail(TIDAL_E_INVAL, "slot %d is %d x %d: both must be multiples of 8", slot, out, in);
-    // per adapter: its entry for this slot
-    std::vector<const PackedTarget*> entry((size_t)n_adapters, nullptr);
+    int64_t in = -1;
+    for (int32_t k = 0; k < n_slots; ++k) {
+        const int32_t slot = slots[k];
+        if (slot < 0 || slot >= (int32_t)t->slots.size()) return fail(TIDAL_E_INVAL, "slot %d out of range", slot);
+        for (int32_t m = 0; m < k; ++m)
+            if (slots[m] == slot) return fail(TIDAL_E_INVAL, "slot %d given twice", slot);
+        const SlotState& st = t->slots[slot];
+        if (st.rows > 0x7FFFFFFF || st.cols > 0x7FFFFFFF) return fail(TIDAL_E_INVAL, "slot %d is too large", slot);
+        if (st.elems > 0 && (st.cols % 8 || st.rows % 8))
+            return fail(TIDAL_E_INVAL, "slot %d is %lld x %lld: both must be multiples of 8", slot, (long long)st.rows,
+                        (long long)st.cols);
+        if (in >= 0 && st.cols != in)
+            return fail(TIDAL_E_INVAL, "slot %d has %lld input columns, slot %d has %lld: the targets of one call share x",
+                        slot, (long long)st.cols, slots[0], (long long)in);
+        in = st.cols;
+    }
+    // per (adapter, slot): the adapter's entry for that slot
+    std::vector<const PackedTarget*> entry((size_t)n_adapters * (size_t)std::max(n_slots, 1), nullptr);
     for (int32_t a = 0; a < n_adapters; ++a) {
         if (!adapters[a]) return fail(TIDAL_E_INVAL, "adapter %d is NULL", a);
         if (adapters[a]->owner != t) return fail(TIDAL_E_INVAL, "adapter %d belongs to another template", a);
-        for (const PackedTarget& p : adapters[a]->rec.targets)
-            if (p.slot == slot) entry[a] = &p;
-        if (!entry[a]) return fail(TIDAL_E_INVAL, "adapter %d does not target slot %d", a, slot);
+        for (int32_t k = 0; k < n_slots; ++k) {
+            for (const PackedTarget& p : adapters[a]->rec.targets)
+                if (p.slot == slots[k]) entry[(size_t)a * n_slots + k] = &p;
+            if (!entry[(size_t)a * n_slots + k])
+                return fail(TIDAL_E_INVAL, "adapter %d does not target slot %d", a, slots[k]);
+        }
     }
     // segments: in range, disjoint
     std::vector<std::pair<int32_t, int32_t>> spans;
@@ -978,88 +993,187 @@ extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_ada
         if (spans[i].first < spans[i - 1].second)
             return fail(TIDAL_E_INVAL, "segments overlap at token %d", spans[i].first);
 
-    std::vector<ApplySeg> all;
+    // what there is to do: segments with an adapter, on slots that exist
+    struct HostSeg { int32_t t0, t1, adapter; };
+    std::vector<HostSeg> longs, shorts;
     for (int32_t i = 0; i < n_segs; ++i) {
         const tidal_lora_segment& g = segs[i];
-        if (g.adapter < 0 || g.token_end == g.token_begin || st.elems == 0) continue;
-        const PackedTarget* p = entry[g.adapter];
-        if (!p->active()) continue;
-        if (p->ar_off == kNoOffset) return fail(TIDAL_E_STATE, "adapter %d holds no row-major A for slot %d", g.adapter, slot);
-        const char* base = adapters[g.adapter]->rec.dev;
-        ApplySeg sg;
-        memset(&sg, 0, sizeof sg);
-        sg.Ar = (const uint16_t*)(base + p->ar_off);
-        sg.Bp = (const uint16_t*)(base + p->bp_off);
-        sg.t0 = g.token_begin;
-        sg.t1 = g.token_end;
-        sg.s = p->alpha / (float)p->r;
-        sg.r = p->r;
-        sg.rp = p->rp;
-        all.push_back(sg);
+        if (g.adapter < 0 || g.token_end == g.token_begin) continue;
+        (g.token_end - g.token_begin <= kApplyShortRows ? shorts : longs).push_back(HostSeg{g.token_begin, g.token_end, g.adapter});
     }
-    if (all.empty()) return TIDAL_OK;
-    if (!x || !y) return fail(TIDAL_E_INVAL, "x or y is NULL");
-    if ((uintptr_t)x % 16 || (uintptr_t)y % 16) return fail(TIDAL_E_INVAL, "x and y must be 16-byte aligned");
+    if (n_slots > kMaxApplySlots) return fail(TIDAL_E_INVAL, "at most %d slots per call", kMaxApplySlots);
+    ApplySlot slot_tab[kMaxApplySlots];
+    memset(slot_tab, 0, sizeof slot_tab);
+    int max_out = 0;
+    bool any = false;
+    for (int32_t k = 0; k < n_slots; ++k) {
+        const SlotState& st = t->slots[slots[k]];
+        slot_tab[k].out = st.elems > 0 ? (int32_t)st.rows : 0;
+        slot_tab[k].u_tok = (uint32_t)((int64_t)k * n_tokens);
+        max_out = std::max(max_out, slot_tab[k].out);
+    }
+    // factors of an (adapter, slot) pair, as offsets from the lowest adapter address
+    const char* lowest = nullptr;
+    for (int32_t a = 0; a < n_adapters; ++a)
+        if (!lowest || adapters[a]->rec.dev < lowest) lowest = adapters[a]->rec.dev;
+    std::vector<char> used((size_t)std::max(n_adapters, 1), 0);
+    for (const HostSeg& g : longs) used[g.adapter] = 1;
+    for (const HostSeg& g : shorts) used[g.adapter] = 1;
+    std::vector<ApplyFactor> facs((size_t)n_adapters * (size_t)std::max(n_slots, 1));
+    for (int32_t a = 0; a < n_adapters; ++a) {
+        for (int32_t k = 0; k < n_slots; ++k) {
+            ApplyFactor& f = facs[(size_t)a * n_slots + k];
+            memset(&f, 0, sizeof f);
+            const PackedTarget* p = entry[(size_t)a * n_slots + k];
+            if (!used[a] || slot_tab[k].out == 0 || !p->active()) continue;     // r stays 0: nothing to do
+            if (p->ar_off == kNoOffset)
+                return fail(TIDAL_E_STATE, "adapter %d holds no row-major A for slot %d", a, slots[k]);
+            const uint64_t ar = (uint64_t)(adapters[a]->rec.dev - lowest) + p->ar_off;
+            const uint64_t bp = (uint64_t)(adapters[a]->rec.dev - lowest) + p->bp_off;
+            if (ar % kLoraUnit || bp % kLoraUnit || ar / kLoraUnit > 0xFFFFFFFFull || bp / kLoraUnit > 0xFFFFFFFFull)
+                return fail(TIDAL_E_INVAL, "adapter %d lies too far from the others (more than 1 TB of address space)", a);
+            f.ar = (uint32_t)(ar / kLoraUnit);
+            f.bp = (uint32_t)(bp / kLoraUnit);
+            f.s = p->alpha / (float)p->r;
+            f.r = (uint16_t)p->r;
+            f.rp = (uint16_t)p->rp;
+            if (!ys || !ys[k]) return fail(TIDAL_E_INVAL, "y of slot %d is NULL", slots[k]);
+            if ((uintptr_t)ys[k] % 16) return fail(TIDAL_E_INVAL, "y of slot %d is not 16-byte aligned", slots[k]);
+            any = true;
+        }
+    }
+    if (!any) return TIDAL_OK;
+    for (int32_t k = 0; k < n_slots; ++k) slot_tab[k].y = (uint16_t*)(ys ? ys[k] : nullptr);
+    if (!x) return fail(TIDAL_E_INVAL, "x is NULL");
+    if ((uintptr_t)x % 16) return fail(TIDAL_E_INVAL, "x must be 16-byte aligned");
     if (!workspace || (uintptr_t)workspace % kSlotAlign) return fail(TIDAL_E_INVAL, "workspace is NULL or not 256-byte aligned");
-    if (workspace_bytes < tidal_lora_apply_workspace_bytes(n_tokens))
-        return fail(TIDAL_E_NOMEM, "workspace needs %zu bytes, got %zu", tidal_lora_apply_workspace_bytes(n_tokens),
+    const int64_t ws_tokens = (int64_t)n_tokens * n_slots;
+    if (ws_tokens > 0x7FFFFFFF) return fail(TIDAL_E_INVAL, "n_tokens x n_slots is too large");
+    if (workspace_bytes < tidal_lora_apply_workspace_bytes((int32_t)ws_tokens))
+        return fail(TIDAL_E_NOMEM, "workspace needs %zu bytes, got %zu", tidal_lora_apply_workspace_bytes((int32_t)ws_tokens),
                     workspace_bytes);
     int rc = ensure_device(t);
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)stream_;
     if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));   // adapter uploads
 
-    // One launch covers up to kMaxApplySegs segments; work units are numbered within a launch.
-    auto run = [&](const std::vector<ApplySeg>& list, int kind, int rp) -> int {
-        for (size_t at = 0; at < list.size(); at += kMaxApplySegs) {
-            const int n = (int)std::min(list.size() - at, (size_t)kMaxApplySegs);
-            ApplyBatch b;
+    // ---- prompts: one self-contained entry per (segment, active slot), kMaxApplyLong per launch
+    std::vector<ApplyLongEntry> long_entries;
+    for (const HostSeg& g : longs) {
+        for (int32_t k = 0; k < n_slots; ++k) {
+            const ApplyFactor& f = facs[(size_t)g.adapter * n_slots + k];
+            if (f.r == 0) continue;
+            ApplyLongEntry e;
+            memset(&e, 0, sizeof e);
+            e.Ar = (const uint16_t*)(lowest + (size_t)f.ar * kLoraUnit);
+            e.Bp = (const uint16_t*)(lowest + (size_t)f.bp * kLoraUnit);
+            e.y = slot_tab[k].y;
+            e.t0 = g.t0;
+            e.t1 = g.t1;
+            e.s = f.s;
+            e.r = f.r;
+            e.rp = f.rp;
+            e.out = slot_tab[k].out;
+            e.u_tok = slot_tab[k].u_tok;
+            long_entries.push_back(e);
+        }
+    }
+    // shrink = true: u = bf16(A x) for all entries; else the expand of the entries with padded
+    // rank rp (the specialised kernels run at twice the occupancy of the one that takes any rank)
+    auto run_long = [&](bool shrink, int rp) -> int {
+        std::vector<const ApplyLongEntry*> list;
+        for (const ApplyLongEntry& e : long_entries)
+            if (shrink || e.rp == rp) list.push_back(&e);
+        for (size_t at = 0; at < list.size(); at += kMaxApplyLong) {
+            const int n = (int)std::min(list.size() - at, (size_t)kMaxApplyLong);
+            ApplyLongBatch b;
             memset(&b, 0, sizeof b);
             b.x = (const uint16_t*)x;
-            b.y = (uint16_t*)y;
             b.u = (uint16_t*)workspace;
-            b.n_segs = n;
-            int64_t tiles = 0, chunks = 0;
-            for (int k = 0; k < n; ++k) tiles += ((int64_t)list[at + k].t1 - list[at + k].t0 + 31) / 32;
+            b.n = n;
+            int64_t tiles = 0;
+            int launch_out = 0;
+            for (int k = 0; k < n; ++k) {
+                tiles += ((int64_t)list[at + k]->t1 - list[at + k]->t0 + 31) / 32;
+                launch_out = std::max(launch_out, list[at + k]->out);
+            }
             // tiles a wave walks per strip of B: long walks amortise the strip, short ones keep
             // small batches spread over the chip (aim: >= 4096 waves)
-            const int64_t strips = (out + 255) / 256;
+            const int64_t strips = (launch_out + 255) / 256;
             const int ct = (int)std::max<int64_t>(1, std::min<int64_t>(kApplyChunkTiles, tiles * strips / 4096));
-            tiles = 0;
-            for (int k = 0; k < kMaxApplySegs; ++k) b.first[k] = 0x7FFFFFFF;
+            int64_t units = 0;
+            for (int k = 0; k < kMaxApplyLong; ++k) b.first[k] = 0x7FFFFFFF;
             for (int k = 0; k < n; ++k) {
-                const ApplySeg& sg = list[at + k];
-                const int64_t len = (int64_t)sg.t1 - sg.t0;
-                b.first[k] = (int32_t)(kind == 1 ? chunks : tiles);
-                tiles += (len + 31) / 32;
-                chunks += (len + 32 * ct - 1) / (32 * ct);
-                b.seg[k] = sg;
+                b.e[k] = *list[at + k];
+                const int64_t len = (int64_t)b.e[k].t1 - b.e[k].t0;
+                b.first[k] = (int32_t)units;
+                units += shrink ? (len + 31) / 32 : (len + 32 * ct - 1) / (32 * ct);
             }
-            if (kind == 0) HIP_TRY(launch_apply_shrink(b, (int)tiles, in, stream));
-            else if (kind == 1) HIP_TRY(launch_apply_expand(b, (int)chunks, ct, out, rp, stream));
-            else if (kind == 2) HIP_TRY(launch_apply_shrink_short(b, in, stream));
-            else HIP_TRY(launch_apply_expand_short(b, out, stream));
+            if (units > 0x7FFFFFF0) return fail(TIDAL_E_INVAL, "batch too large");
+            if (shrink) HIP_TRY(launch_apply_shrink(b, (int)units, (int)in, stream));
+            else HIP_TRY(launch_apply_expand(b, (int)units, ct, launch_out, rp, stream));
         }
         return TIDAL_OK;
     };
-    std::vector<ApplySeg> longs, shorts, by_rank[3];
-    for (const ApplySeg& sg : all) {
-        if (sg.t1 - sg.t0 <= kApplyShortRows) {
-            shorts.push_back(sg);
-        } else {
-            longs.push_back(sg);
-            by_rank[sg.rp == 16 ? 0 : (sg.rp == 32 ? 1 : 2)].push_back(sg);
+    // ---- decode steps: compact tables, up to kMaxApplyShort segments whose adapters' factor
+    // entries (n_slots each) fit the factor table
+    auto run_short = [&](bool shrink) -> int {
+        size_t at = 0;
+        while (at < shorts.size()) {
+            ApplyShortBatch b;
+            memset(&b, 0, sizeof b);
+            b.x = (const uint16_t*)x;
+            b.u = (uint16_t*)workspace;
+            b.adapter_base = lowest;
+            b.n_slots = n_slots;
+            memcpy(b.slot, slot_tab, sizeof slot_tab);
+            std::map<int32_t, int> fac_of;
+            int n = 0, nfac = 0;
+            while (at + n < shorts.size() && n < kMaxApplyShort) {
+                const HostSeg& g = shorts[at + n];
+                if (!fac_of.count(g.adapter)) {
+                    if (nfac + n_slots > kMaxApplyFactors) break;
+                    fac_of[g.adapter] = nfac;
+                    for (int32_t k = 0; k < n_slots; ++k) b.fac[nfac + k] = facs[(size_t)g.adapter * n_slots + k];
+                    nfac += n_slots;
+                }
+                b.seg[n].t0 = g.t0;
+                b.seg[n].rows = (uint16_t)(g.t1 - g.t0);
+                b.seg[n].fac = (uint16_t)fac_of[g.adapter];
+                ++n;
+            }
+            b.n_segs = n;
+            if (shrink) HIP_TRY(launch_apply_shrink_short(b, (int)in, stream));
+            else HIP_TRY(launch_apply_expand_short(b, max_out, stream));
+            at += n;
         }
-    }
-    rc = run(longs, 0, 0);
+        return TIDAL_OK;
+    };
+    rc = run_long(true, 0);
     if (rc) return rc;
-    rc = run(shorts, 2, 0);
+    rc = run_short(true);
     if (rc) return rc;
-    for (int g = 0; g < 3; ++g) {
-        rc = run(by_rank[g], 1, 16 << g);
+    for (int rp = 16; rp <= 64; rp *= 2) {
+        rc = run_long(false, rp);
         if (rc) return rc;
     }
-    return run(shorts, 3, 0);
+    return run_short(false);
+}
+
+extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_adapter* const* adapters,
+                                int32_t n_adapters, const tidal_lora_segment* segs, int32_t n_segs, const void* x,
+                                void* y, int32_t n_tokens, void* workspace, size_t workspace_bytes, void* stream) {
+    void* ys[1] = {y};
+    return lora_apply_impl(t, &slot, 1, adapters, n_adapters, segs, n_segs, x, ys, n_tokens, workspace, workspace_bytes,
+                           stream);
+}
+
+extern "C" int tidal_lora_apply_multi(tidal_template* t, const int32_t* slots, int32_t n_slots,
+                                      const tidal_adapter* const* adapters, int32_t n_adapters,
+                                      const tidal_lora_segment* segs, int32_t n_segs, const void* x, void* const* ys,
+                                      int32_t n_tokens, void* workspace, size_t workspace_bytes, void* stream) {
+    return lora_apply_impl(t, slots, n_slots, adapters, n_adapters, segs, n_segs, x, ys, n_tokens, workspace,
+                           workspace_bytes, stream);
 }
 
 extern "C" int tidal_lora_detach(tidal_template* t, void* stream) {

@@ -86,40 +86,77 @@ struct FusedPiece {
 hipError_t launch_convert_merge(const FusedPiece& p, bool ordered, hipStream_t stream);
 
 // ---- unmerged adapter apply ---------------------------------------------------------------
-// One entry per run of consecutive tokens that share an adapter.  Adapters live in separate
-// caller-owned allocations, hence full pointers; 80 entries travel in the kernel arguments,
-// batches with more segments take several launches.  Work units (32-token tiles for the shrink,
-// chunks of one to kApplyChunkTiles tiles for the expand) are numbered through the launch; first[k]
-// is the number of segment k's first one (INT32_MAX past the last segment).  The kernels count
-// the entries <= their unit: one independent read of a compact array instead of a bisection,
-// whose dependent reads of the kernel arguments would cost more than a small batch's work.
-struct ApplySeg {
+// Everything a launch needs travels in its kernel arguments (4 KB), in two formats:
+//
+// Prompts (segments of more than kApplyShortRows tokens) are few and long.  Their waves are
+// short-lived (one tile each), so the chain of dependent reads in front of the first data load
+// counts: one self-contained entry per (segment, target slot), found with one search.  Work
+// units -- 32-token tiles for the shrink, chunks of one to kApplyChunkTiles tiles for the expand
+// -- are numbered entry by entry; first[k] is entry k's first unit (INT32_MAX past the last
+// entry) and a wave counts the entries <= its unit: independent reads of a compact array instead
+// of a bisection.
+struct ApplyLongEntry {
     const uint16_t* Ar;      // r x in bf16, A row-major
     const uint16_t* Bp;      // out x rp bf16, zero padded
+    uint16_t* y;             // this slot's output: n_tokens x out
     int32_t t0, t1;          // token rows [t0, t1)
     float s;                 // alpha / r
     int32_t r, rp;           // true and padded rank
+    int32_t out;
+    uint32_t u_tok;          // first token row of this slot's part of the workspace
     int32_t pad_;
 };
-constexpr int kMaxApplySegs = 80;
-constexpr int kApplyRankStride = 64;   // workspace elements reserved per token
-constexpr int kApplyChunkTiles = 4;    // most 32-token tiles a wave of the expand kernel walks per strip
-constexpr int kApplyShortRows = 4;     // segments up to this many tokens take the vector-ALU expand
-struct ApplyBatch {
-    const uint16_t* x;       // n_tokens x in
-    uint16_t* y;             // n_tokens x out
-    uint16_t* u;             // workspace: token t's rank-space row at u + t0 * kApplyRankStride + (t - t0) * rp
-    int32_t n_segs, pad_;
-    int32_t first[kMaxApplySegs];
-    ApplySeg seg[kMaxApplySegs];   // 3200 bytes
+constexpr int kMaxApplyLong = 64;
+struct ApplyLongBatch {
+    const uint16_t* x;       // n_tokens x in, shared by all slots
+    uint16_t* u;             // workspace: an entry's rows start at u + (u_tok + t0) * kApplyRankStride, pitch rp
+    int32_t n, pad_;
+    int32_t first[kMaxApplyLong];
+    ApplyLongEntry e[kMaxApplyLong];         // 3584 bytes
 };
-// Segments longer than kApplyShortRows tokens take the matrix-core kernels: u = bf16(A x)
-// (n_tiles = total 32-token tiles), then y += s * B u (n_chunks = total chunks; all segments of
-// that launch share the padded rank rp).  Shorter ones take the vector-ALU pair.
-hipError_t launch_apply_shrink(const ApplyBatch& b, int n_tiles, int in, hipStream_t stream);
-hipError_t launch_apply_expand(const ApplyBatch& b, int n_chunks, int chunk_tiles, int out, int rp, hipStream_t stream);
-hipError_t launch_apply_shrink_short(const ApplyBatch& b, int in, hipStream_t stream);
-hipError_t launch_apply_expand_short(const ApplyBatch& b, int out, hipStream_t stream);
+// Decode steps (segments of at most kApplyShortRows tokens) are many and tiny: three small
+// tables, so that 256 requests on up to 4 slots are one launch -- the slots (output pointer and
+// width), the factors of every (adapter, slot) pair in use (offsets in 256-byte units from the
+// lowest adapter address: adapters are separate allocations) and the segments (first token, row
+// count and the index of their adapter's first factor entry; its other slots follow).
+struct ApplySlot {
+    uint16_t* y;             // n_tokens x out
+    int32_t out;
+    uint32_t u_tok;
+};
+struct ApplyFactor {
+    uint32_t ar, bp;         // A row-major (r x in) and B (out x rp, zero padded)
+    float s;                 // alpha / r
+    uint16_t r, rp;          // true and padded rank; r = 0: nothing to do for this pair
+};
+struct ApplyShortSeg {
+    int32_t t0;
+    uint16_t rows;           // 1 .. kApplyShortRows
+    uint16_t fac;            // factor entry of (adapter, slot 0)
+};
+constexpr int kMaxApplyShort = 256;
+constexpr int kMaxApplyFactors = 96;
+constexpr int kMaxApplySlots = 4;
+struct ApplyShortBatch {
+    const uint16_t* x;
+    uint16_t* u;
+    const char* adapter_base;
+    int32_t n_segs, n_slots;
+    ApplySlot slot[kMaxApplySlots];          //   64 bytes
+    ApplyShortSeg seg[kMaxApplyShort];       // 2048
+    ApplyFactor fac[kMaxApplyFactors];       // 1536
+};
+static_assert(sizeof(ApplyLongBatch) <= 3900 && sizeof(ApplyShortBatch) <= 3900, "kernel arguments are limited to 4 KB");
+constexpr int kApplyRankStride = 64;   // workspace elements reserved per token and slot
+constexpr int kApplyChunkTiles = 4;    // most 32-token tiles a wave of the expand kernel walks per strip
+constexpr int kApplyShortRows = 4;     // segments up to this many tokens take the vector-ALU kernels
+// Matrix-core pair: u = bf16(A x) (n_tiles = 32-token tiles over all entries), then y += s * B u
+// (n_chunks = chunks over all entries; rp = the padded rank all entries of the launch have).
+hipError_t launch_apply_shrink(const ApplyLongBatch& b, int n_tiles, int in, hipStream_t stream);
+hipError_t launch_apply_expand(const ApplyLongBatch& b, int n_chunks, int chunk_tiles, int max_out, int rp, hipStream_t stream);
+// Vector-ALU pair for the short segments.
+hipError_t launch_apply_shrink_short(const ApplyShortBatch& b, int in, hipStream_t stream);
+hipError_t launch_apply_expand_short(const ApplyShortBatch& b, int max_out, hipStream_t stream);
 
 inline int padded_rank(int r) { return r <= 0 ? 0 : (r <= 16 ? 16 : (r <= 32 ? 32 : 64)); }
 

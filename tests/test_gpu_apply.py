@@ -107,7 +107,7 @@ def test_many_single_token_requests_span_several_launches(orc):
     rng = np.random.default_rng(12)
     with Template([(512, 256)]) as T:
         items, handles = make_adapters(T, rng, 0, [8, 16, 32, 64], [16.0, 32.0, 64.0, 128.0])
-        n = 150                                          # more tiles than one launch carries
+        n = 300                                          # more segments than one launch carries
         segs = [(i % 4, i, i + 1) for i in range(n)]
         X = bf16_bits(rng, (n, 256), 1.0)
         Y = bf16_bits(rng, (n, 512), 0.5)
@@ -197,3 +197,82 @@ def test_random_batches(orc, seed):
         Y = bf16_bits(rng, (t, out), 1.0)
         got = run_apply(T, 0, handles, [segs[i] for i in order], X, Y)
         check(orc, items, segs, X, Y, got)
+
+
+def test_multi_target_call_equals_one_call_per_slot(orc):
+    """Query, key and value projections read the same x: one call for the three targets must give
+    exactly what three calls give (and therefore what the oracle gives)."""
+    rng = np.random.default_rng(16)
+    shapes = [(320, 192), (136, 192), (136, 192), (64, 64)]
+    with Template(shapes) as T:
+        # the third adapter has another rank on every slot and none at all on the last one
+        ranks, alphas = [(8, 8, 8), (64, 64, 64), (20, 64, 0)], [16.0, 128.0, 40.0]
+        per_slot, handles = {0: [], 1: [], 2: []}, []
+        for rs, al in zip(ranks, alphas):
+            items = []
+            for s in (0, 1, 2):
+                r = rs[s]
+                out, inn = shapes[s]
+                A = rng.normal(0, 0.05, (r, inn)).astype(np.float32)
+                B = rng.normal(0, 0.05, (out, r)).astype(np.float32)
+                per_slot[s].append((A, B, al))
+                items.append((s, al, A, B))
+            handles.append(T.upload_adapter(items))
+        lens = [(0, 1), (1, 40), (2, 3), (-1, 2), (0, 200), (1, 4), (2, 5)]
+        segs, t = [], 0
+        for a, n in lens:
+            segs.append((a, t, t + n))
+            t += n
+        X = bf16_bits(rng, (t, 192), 1.0)
+        Ys = [bf16_bits(rng, (t, shapes[s][0]), 1.0) for s in (0, 1, 2)]
+        single = [run_apply(T, s, handles, segs, X, Ys[s]) for s in (0, 1, 2)]
+        for s in (0, 1, 2):
+            check(orc, per_slot[s], segs, X, Ys[s], single[s])
+        xd = dev(X)
+        yd = [dev(y) for y in Ys]
+        nb = tb.tidal_lora_apply_workspace_bytes(3 * t)
+        ws = torch.full((nb,), 0x7F, dtype=torch.uint8, device="cuda:0")
+        tb.tidal_lora_apply_multi(T.h, [0, 1, 2], handles, segs, xd, yd, t, ws, nb, T.compute_stream)
+        T.sync()
+        for s in (0, 1, 2):
+            assert np.array_equal(host(yd[s]).reshape(Ys[s].shape), single[s]), s
+        # slots with different input widths cannot share a call; the workspace scales with the slots
+        with pytest.raises(tb.TidalError) as e:
+            tb.tidal_lora_apply_multi(T.h, [0, 3], handles, segs, xd, yd[:2], t, ws, nb, T.compute_stream)
+        assert e.value.code == tb.TIDAL_E_INVAL
+        with pytest.raises(tb.TidalError) as e:
+            tb.tidal_lora_apply_multi(T.h, [0, 1, 2], handles, segs, xd, yd, t, ws,
+                                      tb.tidal_lora_apply_workspace_bytes(2 * t), T.compute_stream)
+        assert e.value.code == tb.TIDAL_E_NOMEM
+
+
+def test_more_adapters_than_one_launch_carries(orc):
+    """40 adapters on three slots are 120 (adapter, slot) pairs: the factor table of a decode launch
+    holds 96, so the batch is cut where the table is full."""
+    rng = np.random.default_rng(17)
+    shapes = [(64, 64), (72, 64), (64, 64)]
+    with Template(shapes) as T:
+        per_slot, handles = {0: [], 1: [], 2: []}, []
+        for a in range(40):
+            r, al = 1 + a % 5, 2.0 + a
+            items = []
+            for s in (0, 1, 2):
+                A = rng.normal(0, 0.2, (r, 64)).astype(np.float32)
+                B = rng.normal(0, 0.2, (shapes[s][0], r)).astype(np.float32)
+                per_slot[s].append((A, B, al))
+                items.append((s, al, A, B))
+            handles.append(T.upload_adapter(items))
+        segs, t = [], 0
+        for i in range(130):
+            n = 1 + i % 3
+            segs.append(((i * 7) % 40, t, t + n))
+            t += n
+        X = bf16_bits(rng, (t, 64), 1.0)
+        Ys = [bf16_bits(rng, (t, shapes[s][0]), 1.0) for s in (0, 1, 2)]
+        xd, yd = dev(X), [dev(y) for y in Ys]
+        nb = tb.tidal_lora_apply_workspace_bytes(3 * t)
+        ws = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
+        tb.tidal_lora_apply_multi(T.h, [0, 1, 2], handles, segs, xd, yd, t, ws, nb, T.compute_stream)
+        T.sync()
+        for s in (0, 1, 2):
+            check(orc, per_slot[s], segs, X, Ys[s], host(yd[s]).reshape(Ys[s].shape))
