@@ -1098,9 +1098,13 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
                 launch_out = std::max(launch_out, list[at + k]->out);
             }
             // tiles a wave walks per strip of B: long walks amortise the strip, short ones keep
-            // small batches spread over the chip (aim: >= 4096 waves)
+            // small batches spread over the chip (aim: >= 1024 waves; measured best of 1, 2, 4)
             const int64_t strips = (launch_out + 255) / 256;
-            const int ct = (int)std::max<int64_t>(1, std::min<int64_t>(kApplyChunkTiles, tiles * strips / 4096));
+            int ct = (int)std::max<int64_t>(1, std::min<int64_t>(kApplyChunkTiles, tiles * strips / 1024));
+            if (const char* e = getenv("TIDAL_APPLY_CT")) {       // tuning runs only
+                const int v = atoi(e);
+                if (v >= 1 && v <= kApplyChunkTiles) ct = v;
+            }
             int64_t units = 0;
             for (int k = 0; k < kMaxApplyLong; ++k) b.first[k] = 0x7FFFFFFF;
             for (int k = 0; k < n; ++k) {
