@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per lora_mfma_kernel launch on the default workload (32 layers, r=16, 64 targets), from
 # the two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 calibration factor + WRITE_SIZE x 1.0) whose
 # summary is kept under profiles/: mean of the attach and the fused-swap launch.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 4_320_940_000
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 4_320_966_000
 
 
 def log(*a):
@@ -175,7 +175,8 @@ def main() -> int:
     swp_ms = float(np.median([e[2].elapsed_time(e[3]) for e in evs]))
 
     w_elems = wl.lora_w_elements
-    packed = adapter_bytes                                   # bf16 A^T and B, rank padded to 16
+    # what the kernel reads of an adapter: bf16 A^T (in x rp) and B (out x rp), rank padded to 16
+    packed = sum(2 * 16 * (wl.tensors[s].rows + wl.tensors[s].cols) for s in wl.lora_slots)
     attach_bytes = 4 * w_elems + packed
     swap_bytes = 4 * w_elems + 2 * packed
     launches = st["lora_launches"]
