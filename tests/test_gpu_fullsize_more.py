@@ -201,3 +201,92 @@ def test_adapter_churn_full_size_first_steps(orc):
         for h in handles.values():
             tb.tidal_adapter_destroy(h)
         tb.tidal_template_destroy(T)
+
+
+def test_llama3_70b_shaped_materialize_attach(orc):
+    """Configuration 5 at full size: 562 bf16 tensors, 141.1 GB, streamed from a 24 GiB pinned pool
+    that the tensors are mapped into modulo its size (each at its own offset).  bf16 sources are
+    pure DMA into their slots: every slot is compared with its source on the device.  Then r = 16
+    on all seven projections of 80 layers (560 targets); bands of four layers' projections against
+    the oracle, every untargeted slot unchanged."""
+    from paper_2503_06421_amd import harness as hz
+    assert torch.cuda.is_available()
+    wl = wl_mod.llama3_70b()
+    pool = hz.HostPool(wl, limit_bytes=24 << 30)
+    assert pool.wrapped
+    print("pool drawn in %.1f s" % pool.draw_seconds, flush=True)
+    layers_checked = (0, 27, 54, 79)
+    sampled = [s for s in wl.lora_slots if int(wl.tensors[s].name.split(".")[0][1:]) in layers_checked]
+    assert len(sampled) == 28
+    shared, items = {}, []
+    for s in wl.lora_slots:
+        t = wl.tensors[s]
+        if s in sampled:
+            A, B = wl_mod.draw_adapter(wl, 0, s)
+        else:
+            if (t.rows, t.cols) not in shared:
+                shared[(t.rows, t.cols)] = wl_mod.draw_adapter(wl, 0, s)
+            A, B = shared[(t.rows, t.cols)]
+        items.append((s, wl.alpha, A, B))
+    adapter_bytes = sum(2 * 16 * (wl.tensors[s].rows + wl.tensors[s].cols) for s in wl.lora_slots)
+    cfg = tb.make_config(max_adapter_bytes=adapter_bytes)
+    need = tb.tidal_template_required_bytes(wl.shapes, cfg)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    T = tb.tidal_template_create(wl.shapes, arena, need, cfg)
+    copy_s, comp_s = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def dev_slot(i):
+        p, nb = tb.tidal_template_slot_ptr(T, i)
+        o = p - arena.data_ptr()
+        return arena[o:o + nb]
+
+    def host_rows(i, r0, r1):
+        cols = wl.tensors[i].cols
+        return dev_slot(i)[2 * r0 * cols: 2 * r1 * cols].cpu().numpy().view(np.uint16).reshape(r1 - r0, cols)
+
+    try:
+        tb.tidal_materialize(T, pool.sources(), copy_s, comp_s)
+        tb.tidal_template_sync(T)
+        torch.cuda.synchronize()
+        st = tb.tidal_get_stats(T)
+        assert st["converted_elems"] == 0 and st["h2d_bytes"] == wl.source_bytes     # pure DMA
+        print("materialised", flush=True)
+        scratch = torch.empty(max(2 * t.numel for t in wl.tensors), dtype=torch.uint8, device="cuda:0")
+        for i, v in enumerate(pool.views):
+            src = torch.from_numpy(v.reshape(-1).view(np.uint8))
+            scratch[:src.numel()].copy_(src)
+            assert torch.equal(dev_slot(i), scratch[:src.numel()]), "slot %d (%s)" % (i, wl.tensors[i].name)
+        print("placement bit-exact on all %d slots" % len(pool.views), flush=True)
+        del scratch
+
+        prev = {(s, b): host_rows(s, *b) for s in sampled for b in bands_for(wl.tensors[s].rows)}
+        untargeted = [i for i in range(len(wl.tensors)) if i not in set(wl.lora_slots)]
+        before = {i: dev_slot(i).clone() for i in untargeted}
+        tb.tidal_lora_attach(T, tb.targets_from_arrays(items), comp_s)
+        tb.tidal_template_sync(T)
+        torch.cuda.synchronize()
+        by_slot = {s: (al, A, B) for s, al, A, B in items}
+
+        def check_band(key):
+            s, b = key
+            al, A, B = by_slot[s]
+            want = prev[key].copy()
+            orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(np.ascontiguousarray(B[b[0]:b[1]])), al, +1)
+            got = host_rows(s, *b)
+            g, w = f32(got), f32(want)
+            ok = (np.max(np.abs(g - w)) <= 2.0 ** -7 * np.max(np.abs(w)) and np.mean(got != want) < 2e-3
+                  and np.mean(got != prev[key]) > 0.3)
+            return key, bool(ok), float(np.max(np.abs(g - w)) / np.max(np.abs(w)))
+
+        worst = 0.0
+        with ThreadPoolExecutor(max_workers=12) as ex:
+            for key, ok, err in ex.map(check_band, list(prev)):
+                assert ok, ("attach", key, err)
+                worst = max(worst, err)
+        print("attach r=16: %d bands checked, worst max-abs-err / max|W| = %.3g" % (len(prev), worst), flush=True)
+        for i in untargeted:
+            assert torch.equal(dev_slot(i), before[i]), "untargeted slot %d changed" % i
+        assert tb.tidal_get_stats(T)["rmw_elems"] == wl.lora_w_elements
+    finally:
+        torch.cuda.synchronize()
+        tb.tidal_template_destroy(T)
