@@ -73,9 +73,10 @@ def check(orc, items, segs, X, Y, got):
     err = np.abs(g - w)
     assert np.all(err <= ulp(np.maximum(np.abs(g), np.abs(w))) + bound[touched] + 1e-30), float(err.max())
     exact = np.mean(got[touched] == want[touched])
-    assert exact > 0.9, exact                                               # most elements agree bit for bit
+    assert exact > 0.99, exact                                              # nearly all elements agree bit for bit (measured >= 0.999)
     changed = np.mean(got[touched] != Y[touched])
     assert changed > 0.5, changed
+    print("apply parity: %d rows, %.4f of elements bit-exact, max err %.3g" % (int(touched.sum()), exact, float(err.max())), flush=True)
     return exact
 
 
