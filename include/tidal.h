@@ -247,7 +247,9 @@ int tidal_lora_swap_adapter(tidal_template* t, const tidal_adapter* a_new, void*
  * not changed.  `workspace` is caller-owned device memory of at least
  * tidal_lora_apply_workspace_bytes(n_tokens) bytes, 256-byte aligned, used only during the call's
  * kernels (the rank-space intermediate bf16(A x)); calls that share a workspace must be ordered on
- * one stream.  Kernels are enqueued on `stream` after the adapters' uploads. */
+ * one stream.  Kernels are enqueued on `stream` after the adapters' uploads.  With
+ * TIDAL_FLAG_ORDERED_ACCUM both sums run as one fused multiply-add chain in ascending index order
+ * (bit-reproducible against a sequential definition, and slow). */
 typedef struct tidal_lora_segment {
     int32_t adapter;       /* index into adapters[], or < 0 for "no adapter" */
     int32_t token_begin;   /* first token row of the segment                 */

@@ -43,6 +43,8 @@
 // serves tiles that share one), u is a few KB per tile.
 #include "lora_device.h"
 
+#include <algorithm>
+
 namespace tidal {
 
 // Entry that owns work unit `unit`: the number of later entries whose first unit is <= unit.
@@ -432,6 +434,62 @@ hipError_t launch_apply_expand_short(const ApplyShortBatch& b, int max_out, hipS
     const int blocks_per_seg = (max_out + 255) / 256;
     hipLaunchKernelGGL(apply_expand_short_kernel, dim3((unsigned)(b.n_segs * b.n_slots * blocks_per_seg)), dim3(256), 0,
                        stream, b, blocks_per_seg);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// ordered accumulation (TIDAL_FLAG_ORDERED_ACCUM): both sums as one fused multiply-add chain in
+// ascending index order, the order a sequential definition takes -- reproducible bit for bit,
+// and slow: one lane per u[t][k] walks the whole input width.  Entries as for the prompts.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void apply_ordered_shrink_kernel(const ApplyLongBatch batch, int in) {
+    const ApplyLongEntry sg = batch.e[blockIdx.y];
+    const int rows = sg.t1 - sg.t0;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)rows * sg.rp) return;
+    const int t = (int)(idx / sg.rp), k = (int)(idx - (int64_t)t * sg.rp);
+    float acc = 0.0f;
+    if (k < sg.r) {
+        const TIDAL_GLOBAL uint16_t* a = as_global(sg.Ar + (int64_t)k * in);
+        const TIDAL_GLOBAL uint16_t* x = as_global(batch.x + (int64_t)(sg.t0 + t) * in);
+        for (int j = 0; j < in; ++j)
+            acc = __builtin_fmaf(__uint_as_float((uint32_t)a[j] << 16), __uint_as_float((uint32_t)x[j] << 16), acc);
+    }
+    const f32x2 r2 = {acc, 0.0f};
+    as_global(batch.u)[((int64_t)sg.u_tok + sg.t0) * kApplyRankStride + (int64_t)t * sg.rp + k] =
+        (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
+}
+
+__global__ __launch_bounds__(256) void apply_ordered_expand_kernel(const ApplyLongBatch batch) {
+    const ApplyLongEntry sg = batch.e[blockIdx.y];
+    const int rows = sg.t1 - sg.t0;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)rows * sg.out) return;
+    const int t = (int)(idx / sg.out), i = (int)(idx - (int64_t)t * sg.out);
+    const TIDAL_GLOBAL uint16_t* b = as_global(sg.Bp + (int64_t)i * sg.rp);
+    const TIDAL_GLOBAL uint16_t* u = as_global(batch.u + ((int64_t)sg.u_tok + sg.t0) * kApplyRankStride + (int64_t)t * sg.rp);
+    float acc = 0.0f;
+    for (int k = 0; k < sg.r; ++k)
+        acc = __builtin_fmaf(__uint_as_float((uint32_t)b[k] << 16), __uint_as_float((uint32_t)u[k] << 16), acc);
+    TIDAL_GLOBAL uint16_t* y = as_global(sg.y + (int64_t)(sg.t0 + t) * sg.out + i);
+    const f32x2 r2 = {__builtin_fmaf(sg.s, acc, __uint_as_float((uint32_t)*y << 16)), 0.0f};
+    *y = (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);
+}
+
+hipError_t launch_apply_ordered(const ApplyLongBatch& b, int in, bool shrink, hipStream_t stream) {
+    if (b.n <= 0) return hipSuccess;
+    if (b.n > kMaxApplyLong || in <= 0) return hipErrorInvalidValue;
+    int64_t most = 0;
+    for (int k = 0; k < b.n; ++k) {
+        const int64_t rows = (int64_t)b.e[k].t1 - b.e[k].t0;
+        most = std::max(most, rows * (shrink ? b.e[k].rp : b.e[k].out));
+    }
+    const int64_t blocks = (most + 255) / 256;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7FFFFFF0) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks, (unsigned)b.n);
+    if (shrink) hipLaunchKernelGGL(apply_ordered_shrink_kernel, grid, dim3(256), 0, stream, b, in);
+    else hipLaunchKernelGGL(apply_ordered_expand_kernel, grid, dim3(256), 0, stream, b);
     return hipGetLastError();
 }
 

@@ -1057,6 +1057,12 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
     hipStream_t stream = (hipStream_t)stream_;
     if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));   // adapter uploads
 
+    // with ordered accumulation every segment takes the (slow, bit-reproducible) ordered kernels
+    const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
+    if (ordered) {
+        longs.insert(longs.end(), shorts.begin(), shorts.end());
+        shorts.clear();
+    }
     // ---- prompts: one self-contained entry per (segment, active slot), kMaxApplyLong per launch
     std::vector<ApplyLongEntry> long_entries;
     for (const HostSeg& g : longs) {
@@ -1114,7 +1120,8 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
                 units += shrink ? (len + 31) / 32 : (len + 32 * ct - 1) / (32 * ct);
             }
             if (units > 0x7FFFFFF0) return fail(TIDAL_E_INVAL, "batch too large");
-            if (shrink) HIP_TRY(launch_apply_shrink(b, (int)units, (int)in, stream));
+            if (ordered) HIP_TRY(launch_apply_ordered(b, (int)in, shrink, stream));
+            else if (shrink) HIP_TRY(launch_apply_shrink(b, (int)units, (int)in, stream));
             else HIP_TRY(launch_apply_expand(b, (int)units, ct, launch_out, rp, stream));
         }
         return TIDAL_OK;

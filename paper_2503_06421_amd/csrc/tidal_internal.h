@@ -154,6 +154,8 @@ constexpr int kApplyShortRows = 4;     // segments up to this many tokens take t
 // (n_chunks = chunks over all entries; rp = the padded rank all entries of the launch have).
 hipError_t launch_apply_shrink(const ApplyLongBatch& b, int n_tiles, int in, hipStream_t stream);
 hipError_t launch_apply_expand(const ApplyLongBatch& b, int n_chunks, int chunk_tiles, int max_out, int rp, hipStream_t stream);
+// Both steps with ordered accumulation (any segment length): u = bf16(A x) if shrink, else the expand.
+hipError_t launch_apply_ordered(const ApplyLongBatch& b, int in, bool shrink, hipStream_t stream);
 // Vector-ALU pair for the short segments.
 hipError_t launch_apply_shrink_short(const ApplyShortBatch& b, int in, hipStream_t stream);
 hipError_t launch_apply_expand_short(const ApplyShortBatch& b, int max_out, hipStream_t stream);

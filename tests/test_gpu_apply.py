@@ -53,7 +53,11 @@ def run_apply(T, slot, handles, segs, X, Y, ws_extra=0):
     return host(yd).reshape(Y.shape)
 
 
-def check(orc, items, segs, X, Y, got):
+ORDERED = tb.TIDAL_FLAG_ORDERED_ACCUM
+MODES = pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "fast"])
+
+
+def check(orc, items, segs, X, Y, got, exact_bits=False):
     want = Y.copy()
     touched = np.zeros(X.shape[0], bool)
     bound = np.zeros(Y.shape)
@@ -69,6 +73,10 @@ def check(orc, items, segs, X, Y, got):
             # u may land on the neighbouring bf16 (2^-8 relative) when the fp32 sums differ in order
             bound[t0:t1] = 2.0 ** -8 * (al / A.shape[0]) * (np.abs(u) @ np.abs(f32(Bb)).T)
     assert np.array_equal(got[~touched], Y[~touched])                       # other rows: bit-identical
+    if exact_bits:                                                          # ordered accumulation: the oracle's own order
+        assert np.array_equal(got, want), "%d elements differ" % int(np.sum(got != want))
+        assert np.mean(got[touched] != Y[touched]) > 0.5
+        return 1.0
     g, w = f32(got[touched]), f32(want[touched])
     err = np.abs(g - w)
     assert np.all(err <= ulp(np.maximum(np.abs(g), np.abs(w))) + bound[touched] + 1e-30), float(err.max())
@@ -80,11 +88,12 @@ def check(orc, items, segs, X, Y, got):
     return exact
 
 
+@MODES
 @pytest.mark.parametrize("dtype", [np.float32, np.float16])
-def test_mixed_batch_matches_oracle(orc, dtype):
+def test_mixed_batch_matches_oracle(orc, dtype, flags):
     rng = np.random.default_rng(11)
     shapes = [(64, 64), (384, 520)]                      # in: ragged last 64-column group; out: 1.5 strips
-    with Template(shapes) as T:
+    with Template(shapes, flags=flags) as T:
         ranks = [4, 16, 24, 64, 33, 8]
         alphas = [8.0, 32.0, 48.0, 96.0, 66.0, 0.0]       # the last adapter is switched off by alpha
         items, handles = make_adapters(T, rng, 1, ranks, alphas, dtype)
@@ -98,7 +107,7 @@ def test_mixed_batch_matches_oracle(orc, dtype):
         X = bf16_bits(rng, (t, 520), 1.0)
         Y = bf16_bits(rng, (t, 384), 1.0)
         got = run_apply(T, 1, handles, segs, X, Y)
-        check(orc, items, segs, X, Y, got)
+        check(orc, items, segs, X, Y, got, bool(flags))
         # segments given in another order, same result
         got2 = run_apply(T, 1, handles, segs[::-1], X, Y)
         assert np.array_equal(got, got2)
@@ -116,11 +125,12 @@ def test_many_single_token_requests_span_several_launches(orc):
         check(orc, items, segs, X, Y, got)
 
 
-def test_segment_lengths_around_the_kernel_boundaries(orc):
+@MODES
+def test_segment_lengths_around_the_kernel_boundaries(orc, flags):
     """4 | 5 tokens: vector and matrix-core expand; 128 | 129: one and two chunks of four tiles;
     more than 80 longer segments: several launches of the matrix-core kernels."""
     rng = np.random.default_rng(15)
-    with Template([(320, 192)]) as T:
+    with Template([(320, 192)], flags=flags) as T:
         items, handles = make_adapters(T, rng, 0, [16, 40, 1], [32.0, 80.0, 2.0])
         lens = [4, 5, 128, 129, 31, 32, 2, 8, 9] + [5] * 90
         segs, t = [], 0
@@ -130,7 +140,7 @@ def test_segment_lengths_around_the_kernel_boundaries(orc):
         X = bf16_bits(rng, (t, 192), 1.0)
         Y = bf16_bits(rng, (t, 320), 1.0)
         got = run_apply(T, 0, handles, segs, X, Y)
-        check(orc, items, segs, X, Y, got)
+        check(orc, items, segs, X, Y, got, bool(flags))
 
 
 def test_long_prompt_one_adapter_and_merged_weights_untouched(orc):
@@ -178,12 +188,13 @@ def test_apply_rejects_bad_arguments():
         assert np.array_equal(host(Y), y0)                                                     # nothing ran
 
 
+@MODES
 @pytest.mark.parametrize("seed", [101, 102, 103])
-def test_random_batches(orc, seed):
+def test_random_batches(orc, seed, flags):
     """Seeded random mixes of prompts and decode steps, ranks and gaps."""
     rng = np.random.default_rng(seed)
     out, inn = int(rng.choice([136, 264, 512])), int(rng.choice([72, 200, 448]))
-    with Template([(out, inn)]) as T:
+    with Template([(out, inn)], flags=flags) as T:
         ranks = [int(r) for r in rng.choice([1, 2, 7, 8, 16, 17, 32, 48, 64], size=5)]
         items, handles = make_adapters(T, rng, 0, ranks, [2.0 * r for r in ranks])
         segs, t = [], 0
@@ -197,15 +208,16 @@ def test_random_batches(orc, seed):
         X = bf16_bits(rng, (t, inn), 1.0)
         Y = bf16_bits(rng, (t, out), 1.0)
         got = run_apply(T, 0, handles, [segs[i] for i in order], X, Y)
-        check(orc, items, segs, X, Y, got)
+        check(orc, items, segs, X, Y, got, bool(flags))
 
 
-def test_multi_target_call_equals_one_call_per_slot(orc):
+@MODES
+def test_multi_target_call_equals_one_call_per_slot(orc, flags):
     """Query, key and value projections read the same x: one call for the three targets must give
     exactly what three calls give (and therefore what the oracle gives)."""
     rng = np.random.default_rng(16)
     shapes = [(320, 192), (136, 192), (136, 192), (64, 64)]
-    with Template(shapes) as T:
+    with Template(shapes, flags=flags) as T:
         # the third adapter has another rank on every slot and none at all on the last one
         ranks, alphas = [(8, 8, 8), (64, 64, 64), (20, 64, 0)], [16.0, 128.0, 40.0]
         per_slot, handles = {0: [], 1: [], 2: []}, []
@@ -228,7 +240,7 @@ def test_multi_target_call_equals_one_call_per_slot(orc):
         Ys = [bf16_bits(rng, (t, shapes[s][0]), 1.0) for s in (0, 1, 2)]
         single = [run_apply(T, s, handles, segs, X, Ys[s]) for s in (0, 1, 2)]
         for s in (0, 1, 2):
-            check(orc, per_slot[s], segs, X, Ys[s], single[s])
+            check(orc, per_slot[s], segs, X, Ys[s], single[s], bool(flags))
         xd = dev(X)
         yd = [dev(y) for y in Ys]
         nb = tb.tidal_lora_apply_workspace_bytes(3 * t)
