@@ -23,7 +23,7 @@ def draw(rng, shape, dtype, scale):
     return x.astype(dtype)
 
 
-def run_case(orc, flags, dtype, shapes, targets, chunk_bytes, seed):
+def run_case(orc, flags, dtype, shapes, targets, chunk_bytes, seed, one_stream=False):
     """targets: {slot: (r, alpha)}"""
     rng = np.random.default_rng(seed)
     src = {i: draw(rng, s, dtype, 0.05) for i, s in enumerate(shapes)}
@@ -40,7 +40,7 @@ def run_case(orc, flags, dtype, shapes, targets, chunk_bytes, seed):
             srcs.append((i, tb.dtype_code(v), tb.host_ptr(v)))
         items = [(s, al, A, B) for s, (al, A, B) in ad.items()]
         tg = T._targets(items)
-        tb.tidal_materialize_attach(T.h, srcs, tg, T.copy_stream, T.compute_stream)
+        tb.tidal_materialize_attach(T.h, srcs, tg, T.compute_stream if one_stream else T.copy_stream, T.compute_stream)
         T.sync()
         exact = bool(flags & ORDERED)
         for i in range(len(shapes)):
@@ -78,6 +78,8 @@ def test_fused_cold_start_one_chunk_and_ragged_widths(orc):
     shapes = [(40, 37), (17, 129), (64, 64)]
     run_case(orc, ORDERED, np.float16, shapes, {0: (5, 10.0), 1: (16, 32.0)}, 1 << 20, seed=32)
     run_case(orc, 0, np.float32, shapes, {0: (5, 10.0), 1: (16, 32.0), 2: (0, 4.0)}, 1 << 20, seed=33)
+    # copies and kernels on one stream
+    run_case(orc, ORDERED, np.float32, SHAPES, TARGETS, 160 << 10, seed=36, one_stream=True)
 
 
 def test_one_rounding_beats_two(orc):
