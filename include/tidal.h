@@ -112,6 +112,9 @@ typedef struct {
     int32_t flags;             /* TIDAL_FLAG_*                                                   */
     size_t coalesce_bytes;     /* host tensors smaller than this are gathered by the CPU into a
                                   pinned buffer and shipped as one copy; 0 = 64 KiB              */
+    int32_t gather_threads;    /* host threads that copy pageable sources into the pinned buffer
+                                  (pieces of 8 MiB or more are split among them); 0 = 4, at most
+                                  16.  One thread moves about half of what the link carries.     */
 } tidal_config;
 
 /* One planned host->device copy unit, as tidal_materialize would issue it (introspection). */

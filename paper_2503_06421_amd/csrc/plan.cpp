@@ -13,16 +13,19 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
         c.max_adapter_bytes = 0;
         c.flags = 0;
         c.coalesce_bytes = 0;
+        c.gather_threads = 0;
     }
     if (c.chunk_bytes == 0) c.chunk_bytes = (size_t)64 << 20;
     if (c.max_rank == 0) c.max_rank = 64;
     if (c.coalesce_bytes == 0) c.coalesce_bytes = (size_t)64 << 10;
+    if (c.gather_threads == 0) c.gather_threads = 4;
     c.chunk_bytes = align_up(c.chunk_bytes, 4096);
     c.max_adapter_bytes = align_up(c.max_adapter_bytes, kSlotAlign);
     if (c.chunk_bytes < ((size_t)64 << 10)) { *msg = "chunk_bytes below 64 KiB"; return false; }
     if (c.chunk_bytes > ((size_t)1 << 32)) { *msg = "chunk_bytes above 4 GiB"; return false; }
     if (c.max_rank < 0 || c.max_rank > 64) { *msg = "max_rank outside 1..64"; return false; }
     if (c.coalesce_bytes > c.chunk_bytes) { *msg = "coalesce_bytes above chunk_bytes"; return false; }
+    if (c.gather_threads < 1 || c.gather_threads > 16) { *msg = "gather_threads outside 1..16"; return false; }
     const int32_t known = TIDAL_FLAG_ORDERED_ACCUM | TIDAL_FLAG_TWO_PASS_SWAP | TIDAL_FLAG_SLOT_EVENTS |
                           TIDAL_FLAG_KERNEL_TIMING | TIDAL_FLAG_ASYNC_ENQUEUE | TIDAL_FLAG_NO_COPY_MERGE;
     if (c.flags & ~known) { *msg = "unknown flag bits"; return false; }

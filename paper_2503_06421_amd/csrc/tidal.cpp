@@ -10,6 +10,7 @@
 #include <map>
 #include <new>
 #include <string>
+#include <thread>
 #include <tuple>
 #include <vector>
 
@@ -254,6 +255,27 @@ extern "C" int tidal_template_slot_ptr(const tidal_template* t, int32_t slot, vo
 // ---------------------------------------------------------------------------------------
 // materialisation
 // ---------------------------------------------------------------------------------------
+// Copy of a pageable source into the pinned buffer.  One host thread moves about 27 GB/s here,
+// half of what the link carries, so large pieces are split among a few threads (started per
+// piece: tens of microseconds against the millisecond the piece takes).
+static void gather_copy(char* dst, const char* src, size_t bytes, int threads) {
+    constexpr size_t kSplitFrom = (size_t)8 << 20;
+    if (threads <= 1 || bytes < kSplitFrom) {
+        memcpy(dst, src, bytes);
+        return;
+    }
+    const size_t part = (bytes / threads + 4095) & ~(size_t)4095;
+    std::vector<std::thread> pool;
+    for (int k = 1; k < threads; ++k) {
+        const size_t o = (size_t)k * part;
+        if (o >= bytes) break;
+        const size_t n = std::min(part, bytes - o);
+        pool.emplace_back([=] { memcpy(dst + o, src + o, n); });
+    }
+    memcpy(dst, src, std::min(part, bytes));
+    for (std::thread& th : pool) th.join();
+}
+
 static int gather_sources(const tidal_template* t, const tidal_src* srcs, int32_t n_src, int32_t assume_pinned,
                           std::vector<SourceInfo>* out) {
     if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
@@ -352,7 +374,7 @@ struct Pipeline {
         size_t slack = 0;               // alignment gap that may be copied along
         if (gathered) {
             char* stage = t->bounce[b] + buf_off;
-            memcpy(stage, host, bytes);
+            gather_copy(stage, host, bytes, t->cfg.gather_threads);
             t->stats.gathered_bytes += bytes;
             src = stage;
             slack = kSlotAlign - 1;     // gaps inside the library's own buffers only ever land in padding

@@ -281,3 +281,11 @@ def test_lora_apply_validates_segments_without_a_device():
         _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_apply, t, 0, [], [], 0, 0, -1, 0, 0)
     finally:
         tb.tidal_template_destroy(t)
+
+
+def test_gather_threads_default_and_range():
+    cfg = tb.tidal_config_default()
+    assert cfg.gather_threads == 4
+    assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(gather_threads=16)) > 0
+    assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(gather_threads=17)) == 0
+    assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(gather_threads=-1)) == 0

@@ -85,6 +85,20 @@ def test_fp32_random_bit_patterns_multi_chunk(orc, G):
         assert np.array_equal(T.slot(0), orc.convert_to_bf16(x))
 
 
+@pytest.mark.parametrize("threads", [1, 3, 16])
+def test_large_pageable_sources_split_among_gather_threads(orc, G, threads):
+    """Pageable sources go through the pinned bounce buffer; pieces of 8 MiB or more are copied
+    there by several host threads.  Odd sizes so that the parts are ragged."""
+    rng = np.random.default_rng(6)
+    a = rng.normal(0, 1, (2999, 3001)).astype(np.float32)                    # 36 MB, pageable
+    b = rng.normal(0, 1, (1777, 4099)).astype(np.float16)                    # 14.6 MB
+    with G.Template([a.shape, b.shape, (3, 5)], chunk_bytes=24 << 20, gather_threads=threads) as T:
+        T.materialize({0: a, 1: b, 2: np.ones((3, 5), np.float32)}, pinned=False)
+        assert np.array_equal(T.slot(0), orc.convert_to_bf16(a))
+        assert np.array_equal(T.slot(1), orc.convert_to_bf16(b))
+        assert tb.tidal_get_stats(T.h)["gathered_bytes"] == a.nbytes + b.nbytes + 60
+
+
 def test_empty_and_degenerate(orc, G):
     shapes = [(0, 5), (1, 1), (3, 0), (1, 7)]
     arrays = {1: np.array([[1.5]], np.float32), 3: np.arange(7, dtype=np.float16).reshape(1, 7),
