@@ -48,6 +48,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=32, help="fewer layers for a quick functional run (not a valid score)")
     ap.add_argument("--chunk-mib", type=int, default=64)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline; 0 = skip")
+    ap.add_argument("--pipelined-upload", action="store_true",
+                    help="TIDAL_FLAG_PIPELINED_UPLOAD: adapter upload overlapped with the merge in three groups (not the default run)")
     ap.add_argument("--threads", type=int, default=0, help="host threads for drawing the synthetic tensors")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -110,7 +112,7 @@ def main() -> int:
     tb.tidal_template_destroy(t_probe)
     del arena0
     cfg = tb.make_config(chunk_bytes=args.chunk_mib << 20, max_adapter_bytes=adapter_bytes,
-                         flags=tb.TIDAL_FLAG_KERNEL_TIMING)
+                         flags=tb.TIDAL_FLAG_KERNEL_TIMING | (tb.TIDAL_FLAG_PIPELINED_UPLOAD if args.pipelined_upload else 0))
     need = tb.tidal_template_required_bytes(wl.shapes, cfg)
     arena = torch.empty(need, dtype=torch.uint8, device="cuda:0")
     T = tb.tidal_template_create(wl.shapes, arena, need, cfg)
@@ -182,7 +184,8 @@ def main() -> int:
     launches = st["lora_launches"]
     kernel_ms_total = st["lora_kernel_ms"]
     avg_kernel_ms = kernel_ms_total / max(1, launches)
-    bytes_per_launch = (attach_bytes + swap_bytes) / 2.0
+    # every timed step is one attach and one swap, however many launches the library makes of them
+    bytes_per_launch = args.steps * (attach_bytes + swap_bytes) / max(1, launches)
     lora_gbps = bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
     mat_gbps = wl.source_bytes / (mat_ms * 1e-3) / 1e9
 

@@ -99,7 +99,13 @@ enum {
     /* Issue one hipMemcpyAsync per planned piece: neighbouring pieces are not merged into one
      * copy and tiny tensors are not gathered by the CPU.  For measuring what tensor merging
      * (Sec. 6) buys; results are identical.                                                    */
-    TIDAL_FLAG_NO_COPY_MERGE = 32
+    TIDAL_FLAG_NO_COPY_MERGE = 32,
+    /* tidal_lora_attach / _swap with adapters of 4 MiB or more: upload and merge in three
+     * groups of targets (1/8, 2/8, 5/8 of the bytes), the upload of a group on a stream of the
+     * library's own while the group before it is merged on the caller's.  Shorter time per
+     * invocation, three smaller launches instead of one (each a little less efficient);
+     * results are identical.                                                                   */
+    TIDAL_FLAG_PIPELINED_UPLOAD = 64
 };
 
 typedef struct {

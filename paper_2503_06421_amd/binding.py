@@ -23,6 +23,7 @@ TIDAL_OK, TIDAL_E_INVAL, TIDAL_E_NOMEM, TIDAL_E_STATE, TIDAL_E_HIP = 0, -1, -2, 
 TIDAL_FLAG_ORDERED_ACCUM, TIDAL_FLAG_TWO_PASS_SWAP, TIDAL_FLAG_SLOT_EVENTS, TIDAL_FLAG_KERNEL_TIMING = 1, 2, 4, 8
 TIDAL_FLAG_ASYNC_ENQUEUE = 16
 TIDAL_FLAG_NO_COPY_MERGE = 32
+TIDAL_FLAG_PIPELINED_UPLOAD = 64
 
 EXPORTS = [
     "tidal_config_default", "tidal_template_required_bytes", "tidal_template_create", "tidal_materialize",

@@ -27,7 +27,8 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
     if (c.coalesce_bytes > c.chunk_bytes) { *msg = "coalesce_bytes above chunk_bytes"; return false; }
     if (c.gather_threads < 1 || c.gather_threads > 16) { *msg = "gather_threads outside 1..16"; return false; }
     const int32_t known = TIDAL_FLAG_ORDERED_ACCUM | TIDAL_FLAG_TWO_PASS_SWAP | TIDAL_FLAG_SLOT_EVENTS |
-                          TIDAL_FLAG_KERNEL_TIMING | TIDAL_FLAG_ASYNC_ENQUEUE | TIDAL_FLAG_NO_COPY_MERGE;
+                          TIDAL_FLAG_KERNEL_TIMING | TIDAL_FLAG_ASYNC_ENQUEUE | TIDAL_FLAG_NO_COPY_MERGE |
+                          TIDAL_FLAG_PIPELINED_UPLOAD;
     if (c.flags & ~known) { *msg = "unknown flag bits"; return false; }
     *out = c;
     return true;

@@ -90,6 +90,8 @@ struct tidal_template {
     hipEvent_t ev_start = nullptr, ev_copy_done = nullptr;
     hipEvent_t ev_last_compute = nullptr, ev_last_lora = nullptr;
     bool last_compute_rec = false, last_lora_rec = false;
+    hipStream_t up_stream = nullptr;                   // library-owned: adapter uploads that overlap the merge
+    hipEvent_t ev_up_begin = nullptr, ev_up_done[4] = {nullptr, nullptr, nullptr, nullptr};
     char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
     bool bounce_used[2] = {false, false};
     bool staging_rec[2] = {false, false};
@@ -135,6 +137,14 @@ static int ensure_device(tidal_template* t) {
 
 static int ensure_bounce(tidal_template* t, int b) {
     if (!t->bounce[b]) HIP_TRY(hipHostMalloc((void**)&t->bounce[b], t->cfg.chunk_bytes, hipHostMallocDefault));
+    return TIDAL_OK;
+}
+
+static int ensure_upload_stream(tidal_template* t) {
+    if (t->up_stream) return TIDAL_OK;
+    HIP_TRY(hipStreamCreateWithFlags(&t->up_stream, hipStreamNonBlocking));      // default priority
+    HIP_TRY(hipEventCreateWithFlags(&t->ev_up_begin, hipEventDisableTiming));
+    for (int g = 0; g < 4; ++g) HIP_TRY(hipEventCreateWithFlags(&t->ev_up_done[g], hipEventDisableTiming));
     return TIDAL_OK;
 }
 
@@ -648,12 +658,13 @@ extern "C" size_t tidal_adapter_required_bytes(const tidal_template* t, const ti
 
 // Stage A and B of every active target through the staging buffers and pack them into
 // rec.dev on `stream`.
-static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t stream) {
+static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t stream,
+                          size_t first = 0, size_t last = ~(size_t)0) {
     // A job is one factor staged once; A may be packed twice (transposed and, as a plain
     // conversion written as lines of 8, row-major)
     struct Job { const char* host; size_t bytes; PackSegment seg; bool pinned; bool has2; PackSegment seg2; };
     std::vector<Job> jobs;
-    for (size_t i = 0; i < rec.targets.size(); ++i) {
+    for (size_t i = first; i < std::min(last, rec.targets.size()); ++i) {
         const PackedTarget& p = rec.targets[i];
         const SlotState& s = t->slots[p.slot];
         if (!p.active() || s.elems == 0) continue;
@@ -877,11 +888,62 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
     if (rc) return rc;
     const int region = (t->cur_region == 0) ? 1 : 0;
     rec.dev = t->arena + t->lay.adapter_region[region];
-    rc = upload_adapter(t, tg, rec, (hipStream_t)stream);
-    if (rc) return rc;
     AdapterRec old = t->cur;
-    rc = do_swap_launch(t, swap ? &old : nullptr, &rec, (hipStream_t)stream);
-    if (rc) return rc;
+
+    // Upload and merge in up to three groups of targets: while group g is merged on the caller's
+    // stream, group g+1 crosses the link on a stream of the library's own.  The merge of a target
+    // takes about twice as long as its upload, so each group may be twice the size of the one
+    // before and still arrive in time: cuts at 1/8 and 3/8 of the bytes leave one eighth of the
+    // upload exposed and add two launches.  Small adapters take one upload and one pass.
+    std::vector<std::pair<size_t, size_t>> groups;
+    {
+        constexpr size_t kPipelineFrom = (size_t)4 << 20;
+        const size_t cuts[2] = {rec.bytes / 8, rec.bytes * 3 / 8};
+        size_t begin = 0, acc = 0;
+        const bool pipelined = (t->cfg.flags & TIDAL_FLAG_PIPELINED_UPLOAD) != 0;
+        for (size_t i = 0; i < rec.targets.size() && pipelined && rec.bytes >= kPipelineFrom; ++i) {
+            const PackedTarget& p = rec.targets[i];
+            const SlotState& s = t->slots[p.slot];
+            if (p.active() && s.elems > 0) acc += 2 * (size_t)p.rp * (size_t)(s.rows + s.cols);
+            if (groups.size() < 2 && acc >= cuts[groups.size()] && i + 1 < rec.targets.size()) {
+                groups.push_back({begin, i + 1});
+                begin = i + 1;
+            }
+        }
+        groups.push_back({begin, rec.targets.size()});
+    }
+    if (groups.size() <= 1) {
+        rc = upload_adapter(t, tg, rec, (hipStream_t)stream);
+        if (rc) return rc;
+        rc = do_swap_launch(t, swap ? &old : nullptr, &rec, (hipStream_t)stream);
+        if (rc) return rc;
+    } else {
+        rc = ensure_upload_stream(t);
+        if (rc) return rc;
+        // the region to be written was last read by kernels already on the caller's stream
+        HIP_TRY(hipEventRecord(t->ev_up_begin, (hipStream_t)stream));
+        HIP_TRY(hipStreamWaitEvent(t->up_stream, t->ev_up_begin, 0));
+        std::vector<char> in_new(t->slots.size(), 0);
+        for (const PackedTarget& p : rec.targets) in_new[p.slot] = 1;
+        for (size_t g = 0; g < groups.size(); ++g) {
+            rc = upload_adapter(t, tg, rec, t->up_stream, groups[g].first, groups[g].second);
+            if (rc) return rc;
+            HIP_TRY(hipEventRecord(t->ev_up_done[g], t->up_stream));
+            HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, t->ev_up_done[g], 0));
+            AdapterRec part_new, part_old;
+            part_new.dev = rec.dev;
+            part_new.targets.assign(rec.targets.begin() + groups[g].first, rec.targets.begin() + groups[g].second);
+            if (swap) {
+                std::vector<char> here(t->slots.size(), 0);
+                for (const PackedTarget& p : part_new.targets) here[p.slot] = 1;
+                part_old.dev = old.dev;
+                for (const PackedTarget& p : old.targets)       // slots only the old adapter touches go last
+                    if (here[p.slot] || (g + 1 == groups.size() && !in_new[p.slot])) part_old.targets.push_back(p);
+            }
+            rc = do_swap_launch(t, swap ? &part_old : nullptr, &part_new, (hipStream_t)stream);
+            if (rc) return rc;
+        }
+    }
     set_attached(t, rec, nullptr, region);
     return TIDAL_OK;
 }
@@ -1469,6 +1531,12 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
             (void)hipEventDestroy(t->staging_free[b]);
             (void)hipEventDestroy(t->bounce_free[b]);
             if (t->bounce[b]) (void)hipHostFree(t->bounce[b]);
+        }
+        if (t->up_stream) {
+            (void)hipStreamSynchronize(t->up_stream);
+            (void)hipEventDestroy(t->ev_up_begin);
+            for (int g = 0; g < 4; ++g) (void)hipEventDestroy(t->ev_up_done[g]);
+            (void)hipStreamDestroy(t->up_stream);
         }
         (void)hipEventDestroy(t->ev_start);
         (void)hipEventDestroy(t->ev_copy_done);

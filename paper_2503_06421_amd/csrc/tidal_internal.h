@@ -31,7 +31,8 @@ struct PackSegment {
     int64_t lines;       // in (for A) or out (for B)
     int32_t r, rp, dtype, transposed;
 };
-constexpr int kMaxPackSeg = 32;
+constexpr int kMaxPackSeg = 96;   // 40 bytes each in the kernel arguments; fewer, larger chunks: every
+                                  // copy -> pack hand-over costs tens of microseconds of bubble
 struct PackBatch { PackSegment seg[kMaxPackSeg]; };
 
 hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream);

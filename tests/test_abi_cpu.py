@@ -73,7 +73,7 @@ def test_create_rejects_bad_arguments():
     _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, shapes, FAKE_ARENA + 8, need)
     _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, shapes, 0, need)
     _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, [(-1, 4)], FAKE_ARENA, need)
-    for bad in (tb.make_config(chunk_bytes=1024), tb.make_config(max_rank=65), tb.make_config(flags=64),
+    for bad in (tb.make_config(chunk_bytes=1024), tb.make_config(max_rank=65), tb.make_config(flags=128),
                 tb.make_config(chunk_bytes=1 << 20, coalesce_bytes=1 << 21)):
         _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, shapes, FAKE_ARENA, 1 << 40, bad)
         assert tb.tidal_template_required_bytes(shapes, bad) == 0

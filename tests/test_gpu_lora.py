@@ -322,3 +322,36 @@ def test_every_rank_pair_fused_swap(orc, G, r_old, r_new):
     assert np.max(np.abs(g - w)) <= TOL * np.max(np.abs(w))
     assert np.mean(res[0] != want) < 5e-3
     assert np.mean(res[0] != before) > 0.5
+
+
+@pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
+def test_pipelined_upload_gives_the_same_bits(G, flags):
+    """TIDAL_FLAG_PIPELINED_UPLOAD splits a large adapter's upload and merge into three groups of
+    targets on two streams; attach, swap (with slots only the old adapter touches) and detach must
+    give exactly what the single pass gives."""
+    rng = np.random.default_rng(60)
+    shapes = [(512, 1024)] * 26 + [(100, 130)]
+    arrays = {i: rng.uniform(-0.05, 0.05, s).astype(np.float16) for i, s in enumerate(shapes)}
+
+    def adapter(seed, slots, r):
+        g = np.random.default_rng(seed)
+        return [(s, 2.0 * r, g.normal(0, 0.05, (r, shapes[s][1])).astype(np.float32),
+                 g.normal(0, 0.05, (shapes[s][0], r)).astype(np.float32)) for s in slots]
+
+    a0 = adapter(1, range(0, 27), 64)                      # 5.1 MB packed: enough to be pipelined
+    a1 = adapter(2, range(3, 26), 64)                      # leaves slots 0-2 and 26 to the old adapter only
+    res = []
+    for extra in (0, tb.TIDAL_FLAG_PIPELINED_UPLOAD):
+        with G.Template(shapes, max_adapter_bytes=8 << 20, flags=flags | extra) as T:
+            T.materialize(arrays)
+            T.attach(a0)
+            s_att = [T.slot(i) for i in range(len(shapes))]
+            n_att = tb.tidal_get_stats(T.h)["lora_launches"]
+            T.swap(a1)
+            s_swp = [T.slot(i) for i in range(len(shapes))]
+            T.detach()
+            res.append((s_att, s_swp, [T.slot(i) for i in range(len(shapes))], n_att))
+    assert res[1][3] > res[0][3]                           # it did take several launches
+    for k in range(3):
+        for i in range(len(shapes)):
+            assert np.array_equal(res[0][k][i], res[1][k][i]), (k, i)
