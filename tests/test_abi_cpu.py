@@ -289,3 +289,33 @@ def test_gather_threads_default_and_range():
     assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(gather_threads=16)) > 0
     assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(gather_threads=17)) == 0
     assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(gather_threads=-1)) == 0
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and C++), and a C program must
+    link against the library and call a host-only entry point."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_tidal.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "tidal.h"\n'
+        'int main(void) {\n'
+        '    tidal_config c; tidal_slot_desc s[2] = {{4, 8}, {3, 5}};\n'
+        '    if (tidal_config_default(&c) != TIDAL_OK) return 1;\n'
+        '    size_t need = tidal_template_required_bytes(s, 2, &c);\n'
+        '    tidal_template* t = 0;\n'
+        '    if (tidal_template_create(s, 2, (void*)0x700000000000ull, need, &c, &t) != TIDAL_OK) return 2;\n'
+        '    if (tidal_prefetch_bytes(1000, 0.5, 1000.0) != 500) return 3;\n'
+        '    printf("%zu %s\\n", need, tidal_last_error());\n'
+        '    return tidal_template_destroy(t);\n}\n')
+    inc = os.path.join(root, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-c", str(src), "-o",
+                    str(tmp_path / "c.o")], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-x", "c++", "-c", str(src),
+                    "-o", str(tmp_path / "cxx.o")], check=True)
+    libdir = os.path.dirname(tb.LIB_PATH)
+    exe = tmp_path / "use_tidal"
+    subprocess.run(["gcc", str(tmp_path / "c.o"), "-o", str(exe), "-L", libdir, "-ltidal", "-Wl,-rpath," + libdir],
+                   check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == tb.tidal_template_required_bytes([(4, 8), (3, 5)])
