@@ -690,24 +690,22 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
     int chunk = 0;
     while (i < jobs.size()) {
         const int b = chunk & 1;
-        // fill one staging buffer with whole factors
+        // fill one staging buffer with whole factors: all copies first (neighbouring ones merge
+        // into one DMA), then the pack launches, so that a chunk pays the copy -> kernel hand-over once
         size_t fill = 0, j = i;
         bool need_bounce = false;
         std::vector<size_t> offs;
-        int segs = 0;
-        while (j < jobs.size() && segs + (jobs[j].has2 ? 2 : 1) <= kMaxPackSeg) {
+        while (j < jobs.size()) {
             size_t off = align_up(fill, kSlotAlign);
             if (off + jobs[j].bytes > t->cfg.chunk_bytes) break;
             offs.push_back(off);
-            segs += jobs[j].has2 ? 2 : 1;
             fill = off + jobs[j].bytes;
             need_bounce |= !jobs[j].pinned || jobs[j].bytes < t->cfg.coalesce_bytes;
             ++j;
         }
         int rc = pl.acquire(b, need_bounce, true);
         if (rc) return rc;
-        PackBatch batch;
-        int nseg = 0;
+        std::vector<PackSegment> segs;
         for (size_t k = i; k < j; ++k) {
             Job& job = jobs[k];
             const bool gathered = !job.pinned || job.bytes < t->cfg.coalesce_bytes;
@@ -715,15 +713,20 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
             rc = pl.put(gathered, b, (int64_t)offs[k - i], job.host, job.bytes, dst);
             if (rc) return rc;
             job.seg.src = dst;
-            batch.seg[nseg++] = job.seg;
+            segs.push_back(job.seg);
             if (job.has2) {
                 job.seg2.src = dst;
-                batch.seg[nseg++] = job.seg2;
+                segs.push_back(job.seg2);
             }
         }
         rc = pl.copies_done(b, need_bounce, true);
         if (rc) return rc;
-        HIP_TRY(launch_pack(batch, nseg, stream));
+        for (size_t k = 0; k < segs.size(); k += kMaxPackSeg) {
+            const int n = (int)std::min(segs.size() - k, (size_t)kMaxPackSeg);
+            PackBatch batch;
+            memcpy(batch.seg, segs.data() + k, (size_t)n * sizeof(PackSegment));
+            HIP_TRY(launch_pack(batch, n, stream));
+        }
         rc = pl.consumed(b);
         if (rc) return rc;
         i = j;
