@@ -104,7 +104,9 @@ enum {
      * groups of targets (1/8, 2/8, 5/8 of the bytes), the upload of a group on a stream of the
      * library's own while the group before it is merged on the caller's.  Shorter time per
      * invocation, three smaller launches instead of one (each a little less efficient);
-     * results are identical.                                                                   */
+     * results are identical.  The extra stream shares the process's few hardware queues with
+     * the caller's streams: with four or more streams of the caller's in use, work on one of
+     * them may queue behind the uploads.                                                       */
     TIDAL_FLAG_PIPELINED_UPLOAD = 64
 };
 
