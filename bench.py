@@ -46,7 +46,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--layers", type=int, default=32, help="fewer layers for a quick functional run (not a valid score)")
-    ap.add_argument("--chunk-mib", type=int, default=64)
+    ap.add_argument("--chunk-mib", type=int, default=128)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline; 0 = skip")
     ap.add_argument("--pipelined-upload", action="store_true",
                     help="TIDAL_FLAG_PIPELINED_UPLOAD: adapter upload overlapped with the merge in three groups (not the default run)")

@@ -111,7 +111,7 @@ enum {
 };
 
 typedef struct {
-    size_t chunk_bytes;        /* source bytes per staged copy unit; 0 = 64 MiB; rounded to 4 KiB;
+    size_t chunk_bytes;        /* source bytes per staged copy unit; 0 = 128 MiB; rounded to 4 KiB;
                                   must be at least 64 KiB                                        */
     int32_t max_rank;          /* largest r accepted; 0 = 64; at most 64                         */
     size_t max_adapter_bytes;  /* size of each of the two in-arena regions that hold the packed

@@ -15,7 +15,7 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
         c.coalesce_bytes = 0;
         c.gather_threads = 0;
     }
-    if (c.chunk_bytes == 0) c.chunk_bytes = (size_t)64 << 20;
+    if (c.chunk_bytes == 0) c.chunk_bytes = (size_t)128 << 20;
     if (c.max_rank == 0) c.max_rank = 64;
     if (c.coalesce_bytes == 0) c.coalesce_bytes = (size_t)64 << 10;
     if (c.gather_threads == 0) c.gather_threads = 4;

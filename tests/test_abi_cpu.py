@@ -39,7 +39,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_config_defaults():
     c = tb.tidal_config_default()
-    assert c.chunk_bytes == 64 << 20 and c.max_rank == 64 and c.coalesce_bytes == 64 << 10
+    assert c.chunk_bytes == 128 << 20 and c.max_rank == 64 and c.coalesce_bytes == 64 << 10
     assert c.max_adapter_bytes == 0 and c.flags == 0
 
 
@@ -198,7 +198,7 @@ def test_copy_plan_llama7b_chunk_count():
         srcs = [(i, tb.TIDAL_F16, 0x1000) for i in range(len(w.shapes))]
         plan = tb.tidal_materialize_plan(t, srcs, assume_pinned=1)
         assert sum(p.src_bytes for p in plan) == w.source_bytes
-        assert plan[-1].chunk + 1 == -(-w.source_bytes // (64 << 20))     # every chunk full but the last
+        assert plan[-1].chunk + 1 == -(-w.source_bytes // (128 << 20))     # every chunk full but the last
         assert not any(p.gathered for p in plan)
     finally:
         tb.tidal_template_destroy(t)
