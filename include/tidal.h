@@ -100,10 +100,11 @@ enum {
      * copy and tiny tensors are not gathered by the CPU.  For measuring what tensor merging
      * (Sec. 6) buys; results are identical.                                                    */
     TIDAL_FLAG_NO_COPY_MERGE = 32,
-    /* tidal_lora_attach / _swap with adapters of 4 MiB or more: upload and merge in three
-     * groups of targets (1/8, 2/8, 5/8 of the bytes), the upload of a group on a stream of the
+    /* tidal_lora_attach / _swap with adapters of 4 MiB or more: upload and merge in groups of
+     * targets (three groups of 1/8, 2/8, 5/8 of the upload where the merge takes at least twice
+     * as long as the upload, else eight equal ones), the upload of a group on a stream of the
      * library's own while the group before it is merged on the caller's.  Shorter time per
-     * invocation, three smaller launches instead of one (each a little less efficient);
+     * invocation, several smaller launches instead of one (each a little less efficient);
      * results are identical.  The extra stream shares the process's few hardware queues with
      * the caller's streams: with four or more streams of the caller's in use, work on one of
      * them may queue behind the uploads.                                                       */

@@ -126,8 +126,9 @@ def bench_stack(args, wl, pool_limit=None):
     pool = hz.HostPool(wl, limit_bytes=pool_limit)
     log("host pool ready in %.1f s (%s)" % (pool.draw_seconds, "wrapped" if pool.wrapped else "full"))
     items, keep = hz.pinned_adapter(wl, 0)
-    T = hz.DeviceTemplate(wl.shapes, max_adapter_bytes=hz.packed_adapter_bytes(wl), flags=tb.TIDAL_FLAG_KERNEL_TIMING)
-    out = {"config": wl.name, "source_GB": round(wl.source_bytes / 1e9, 3), "host_pool": "wrapped into %.1f GiB" % (pool_limit / 2**30) if pool.wrapped else "full"}
+    flags = tb.TIDAL_FLAG_KERNEL_TIMING | (tb.TIDAL_FLAG_PIPELINED_UPLOAD if args.pipelined_upload else 0)
+    T = hz.DeviceTemplate(wl.shapes, max_adapter_bytes=hz.packed_adapter_bytes(wl), flags=flags)
+    out = {"config": wl.name + ("_pipelined_upload" if args.pipelined_upload else ""), "source_GB": round(wl.source_bytes / 1e9, 3), "host_pool": "wrapped into %.1f GiB" % (pool_limit / 2**30) if pool.wrapped else "full"}
     try:
         probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
         peak = tb.tidal_h2d_peak(probe, 1 << 30, 3, T.copy_stream)
@@ -489,6 +490,7 @@ def main():
     ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply", "coldstart"])
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
+    ap.add_argument("--pipelined-upload", action="store_true", help="13b / 70b: TIDAL_FLAG_PIPELINED_UPLOAD")
     ap.add_argument("--layers", type=int, default=32, help="apply: distinct layers (sets of factors and activations) per pass")
     ap.add_argument("--case", default="", help="apply: only cases whose name contains this")
     args = ap.parse_args()

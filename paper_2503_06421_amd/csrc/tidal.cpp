@@ -70,6 +70,8 @@ struct SlotState {
 
 }  // namespace
 
+constexpr int kMaxUploadGroups = 8;
+
 struct tidal_adapter {
     tidal_template* owner;
     AdapterRec rec;
@@ -91,7 +93,7 @@ struct tidal_template {
     hipEvent_t ev_last_compute = nullptr, ev_last_lora = nullptr;
     bool last_compute_rec = false, last_lora_rec = false;
     hipStream_t up_stream = nullptr;                   // library-owned: adapter uploads that overlap the merge
-    hipEvent_t ev_up_begin = nullptr, ev_up_done[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev_up_begin = nullptr, ev_up_done[kMaxUploadGroups] = {};
     char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
     bool bounce_used[2] = {false, false};
     bool staging_rec[2] = {false, false};
@@ -144,7 +146,7 @@ static int ensure_upload_stream(tidal_template* t) {
     if (t->up_stream) return TIDAL_OK;
     HIP_TRY(hipStreamCreateWithFlags(&t->up_stream, hipStreamNonBlocking));      // default priority
     HIP_TRY(hipEventCreateWithFlags(&t->ev_up_begin, hipEventDisableTiming));
-    for (int g = 0; g < 4; ++g) HIP_TRY(hipEventCreateWithFlags(&t->ev_up_done[g], hipEventDisableTiming));
+    for (int g = 0; g < kMaxUploadGroups; ++g) HIP_TRY(hipEventCreateWithFlags(&t->ev_up_done[g], hipEventDisableTiming));
     return TIDAL_OK;
 }
 
@@ -893,22 +895,37 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
     rec.dev = t->arena + t->lay.adapter_region[region];
     AdapterRec old = t->cur;
 
-    // Upload and merge in up to three groups of targets: while group g is merged on the caller's
-    // stream, group g+1 crosses the link on a stream of the library's own.  The merge of a target
-    // takes about twice as long as its upload, so each group may be twice the size of the one
-    // before and still arrive in time: cuts at 1/8 and 3/8 of the bytes leave one eighth of the
-    // upload exposed and add two launches.  Small adapters take one upload and one pass.
+    // TIDAL_FLAG_PIPELINED_UPLOAD: upload and merge in groups of targets; while group g is merged on
+    // the caller's stream, group g+1 crosses the link on a stream of the library's own.  Where a
+    // target's merge takes at least twice as long as its upload (small ranks), each group may be
+    // twice the size of the one before and still arrive in time: cuts at 1/8 and 3/8 of the upload
+    // leave one eighth of it exposed and add two launches.  Where upload and merge take about as
+    // long (large ranks), only equal groups keep both busy: eight of them.
     std::vector<std::pair<size_t, size_t>> groups;
     {
         constexpr size_t kPipelineFrom = (size_t)4 << 20;
-        const size_t cuts[2] = {rec.bytes / 8, rec.bytes * 3 / 8};
-        size_t begin = 0, acc = 0;
-        const bool pipelined = (t->cfg.flags & TIDAL_FLAG_PIPELINED_UPLOAD) != 0;
-        for (size_t i = 0; i < rec.targets.size() && pipelined && rec.bytes >= kPipelineFrom; ++i) {
+        const bool pipelined = (t->cfg.flags & TIDAL_FLAG_PIPELINED_UPLOAD) != 0 && rec.bytes >= kPipelineFrom;
+        std::vector<double> host_bytes(rec.targets.size(), 0.0);
+        double up_total = 0.0, w_bytes = 0.0;
+        for (size_t i = 0; i < rec.targets.size() && pipelined; ++i) {
             const PackedTarget& p = rec.targets[i];
             const SlotState& s = t->slots[p.slot];
-            if (p.active() && s.elems > 0) acc += 2 * (size_t)p.rp * (size_t)(s.rows + s.cols);
-            if (groups.size() < 2 && acc >= cuts[groups.size()] && i + 1 < rec.targets.size()) {
+            if (!p.active() || s.elems == 0) continue;
+            host_bytes[i] = (double)p.r * (double)(s.rows + s.cols) * (double)dtype_size(tg[i].dtype);
+            up_total += host_bytes[i];
+            w_bytes += 4.0 * (double)s.elems;
+        }
+        std::vector<double> cuts;                                  // fractions of the upload
+        if (pipelined && up_total > 0.0) {
+            const double up_ms = up_total / 55e6, merge_ms = w_bytes / 6.3e9;      // link and HBM rates of this machine
+            if (up_ms <= 0.6 * merge_ms) cuts = {0.125, 0.375};
+            else for (int g = 1; g < kMaxUploadGroups; ++g) cuts.push_back((double)g / kMaxUploadGroups);
+        }
+        size_t begin = 0;
+        double acc = 0.0;
+        for (size_t i = 0; i < rec.targets.size() && groups.size() < cuts.size(); ++i) {
+            acc += host_bytes[i];
+            if (acc >= cuts[groups.size()] * up_total && i + 1 < rec.targets.size()) {
                 groups.push_back({begin, i + 1});
                 begin = i + 1;
             }
@@ -1538,7 +1555,7 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
         if (t->up_stream) {
             (void)hipStreamSynchronize(t->up_stream);
             (void)hipEventDestroy(t->ev_up_begin);
-            for (int g = 0; g < 4; ++g) (void)hipEventDestroy(t->ev_up_done[g]);
+            for (int g = 0; g < kMaxUploadGroups; ++g) (void)hipEventDestroy(t->ev_up_done[g]);
             (void)hipStreamDestroy(t->up_stream);
         }
         (void)hipEventDestroy(t->ev_start);
