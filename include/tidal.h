@@ -348,7 +348,9 @@ int tidal_h2d_peak(void* dev /* [device] */, size_t bytes, int32_t reps, void* s
 int tidal_get_stats(tidal_template* t, tidal_stats* out /* [host] out */);
 int tidal_reset_stats(tidal_template* t);
 
-/* Block until everything this template enqueued has completed. */
+/* Block until every materialisation, adapter upload, LoRA attach / swap / detach and fork apply
+ * this template enqueued has completed.  tidal_lora_apply, tidal_slot_checksum and
+ * tidal_convert_device only enqueue kernels on the caller's stream and complete with it. */
 int tidal_template_sync(tidal_template* t);
 
 /* Waits for enqueued work, then frees the handle, pinned buffers and events.  Resident
