@@ -367,11 +367,23 @@ struct Pipeline {
     const char* run_src = nullptr;
     size_t run_len = 0;
 
+    // Small runs may be fetched by a kernel instead of the copy engine (adapter uploads, where a
+    // kernel on the same stream follows and the copy -> kernel hand-over would dominate).
+    bool kernel_copy = false;
+
     int flush() {
         if (!run) return TIDAL_OK;
         run = false;
-        HIP_TRY(hipMemcpyAsync(run_dst, run_src, run_len, hipMemcpyHostToDevice, copy));
         t->stats.h2d_copies++;
+        if (kernel_copy && run_len <= kKernelCopyMax && (uintptr_t)run_src % 16 == 0 && (uintptr_t)run_dst % 16 == 0) {
+            void* view = nullptr;            // the GPU's address for this pinned host memory
+            if (hipHostGetDevicePointer(&view, const_cast<char*>(run_src), 0) == hipSuccess && view) {
+                HIP_TRY(launch_copy_from_host(view, run_dst, run_len, copy));
+                return TIDAL_OK;
+            }
+            (void)hipGetLastError();         // not mapped: the copy engine takes it
+        }
+        HIP_TRY(hipMemcpyAsync(run_dst, run_src, run_len, hipMemcpyHostToDevice, copy));
         return TIDAL_OK;
     }
 
@@ -688,6 +700,7 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
     for (Job& j : jobs) j.pinned = host_is_pinned(j.host);
 
     Pipeline pl{t, stream, stream};
+    pl.kernel_copy = true;
     size_t i = 0;
     int chunk = 0;
     while (i < jobs.size()) {

@@ -36,6 +36,10 @@ constexpr int kMaxPackSeg = 96;   // 40 bytes each in the kernel arguments; fewe
 struct PackBatch { PackSegment seg[kMaxPackSeg]; };
 
 hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream);
+// Copy `bytes` from pinned host memory (given by its device-side address) by a kernel instead of
+// the copy engine; both addresses 16-byte aligned.  Pays below a few MiB when a kernel follows.
+hipError_t launch_copy_from_host(const void* src_device_view, void* dst, size_t bytes, hipStream_t stream);
+constexpr size_t kKernelCopyMax = (size_t)2 << 20;
 
 // ---- LoRA read-modify-write ---------------------------------------------------------------
 // One entry per targeted slot of a launch.  All slots of a launch share out, in and the padded
