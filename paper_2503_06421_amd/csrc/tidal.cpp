@@ -368,8 +368,19 @@ struct Pipeline {
     size_t run_len = 0;
 
     // Small runs may be fetched by a kernel instead of the copy engine (adapter uploads, where a
-    // kernel on the same stream follows and the copy -> kernel hand-over would dominate).
+    // kernel on the same stream follows and the copy -> kernel hand-over would dominate).  They
+    // collect here and go out in one launch per kMaxCopyRuns, at the latest in copies_done().
     bool kernel_copy = false;
+    CopyBatch kbatch;
+    int kruns = 0;
+
+    int flush_kernel_copies() {
+        if (kruns == 0) return TIDAL_OK;
+        const int n = kruns;
+        kruns = 0;
+        HIP_TRY(launch_copy_from_host(kbatch, n, copy));
+        return TIDAL_OK;
+    }
 
     int flush() {
         if (!run) return TIDAL_OK;
@@ -377,9 +388,10 @@ struct Pipeline {
         t->stats.h2d_copies++;
         if (kernel_copy && run_len <= kKernelCopyMax && (uintptr_t)run_src % 16 == 0 && (uintptr_t)run_dst % 16 == 0) {
             void* view = nullptr;            // the GPU's address for this pinned host memory
-            if (hipHostGetDevicePointer(&view, const_cast<char*>(run_src), 0) == hipSuccess && view) {
-                HIP_TRY(launch_copy_from_host(view, run_dst, run_len, copy));
-                return TIDAL_OK;
+            if (hipHostGetDevicePointer(&view, const_cast<char*>(run_src), 0) == hipSuccess && view &&
+                (uintptr_t)view % 16 == 0) {
+                kbatch.run[kruns++] = CopyRun{view, run_dst, (uint64_t)run_len};
+                return kruns == kMaxCopyRuns ? flush_kernel_copies() : TIDAL_OK;
             }
             (void)hipGetLastError();         // not mapped: the copy engine takes it
         }
@@ -440,6 +452,8 @@ struct Pipeline {
     // After the last copy of a chunk has been issued.
     int copies_done(int b, bool used_bounce, bool used_staging) {
         int rc = flush();
+        if (rc) return rc;
+        rc = flush_kernel_copies();
         if (rc) return rc;
         if (used_bounce) {
             HIP_TRY(hipEventRecord(t->bounce_free[b], copy));

@@ -36,9 +36,16 @@ constexpr int kMaxPackSeg = 96;   // 40 bytes each in the kernel arguments; fewe
 struct PackBatch { PackSegment seg[kMaxPackSeg]; };
 
 hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream);
-// Copy `bytes` from pinned host memory (given by its device-side address) by a kernel instead of
-// the copy engine; both addresses 16-byte aligned.  Pays below a few MiB when a kernel follows.
-hipError_t launch_copy_from_host(const void* src_device_view, void* dst, size_t bytes, hipStream_t stream);
+// Copies from pinned host memory (given by its device-side address) by a kernel instead of the
+// copy engine; all addresses 16-byte aligned.  Pays below a few MiB per run when a kernel follows.
+struct CopyRun {
+    const void* src;     // device-side address of pinned host memory
+    void* dst;           // device
+    uint64_t bytes;
+};
+constexpr int kMaxCopyRuns = 64;
+struct CopyBatch { CopyRun run[kMaxCopyRuns]; };                  // 1536 bytes of kernel arguments
+hipError_t launch_copy_from_host(const CopyBatch& batch, int nrun, hipStream_t stream);
 constexpr size_t kKernelCopyMax = (size_t)2 << 20;
 
 // ---- LoRA read-modify-write ---------------------------------------------------------------
