@@ -67,7 +67,9 @@ typedef struct { int32_t slot; int32_t dtype; const void* host; /* [host] borrow
 
 /* One LoRA target: slot W (out x in) gets W + (alpha/r) * B * A with A (r x in) and
  * B (out x r), row-major, dense, both of `dtype`.  r == 0 or alpha == 0 is valid and
- * leaves W untouched (A and B may then be NULL). */
+ * leaves W untouched (A and B may then be NULL).  A factor is staged whole, so each of A and
+ * B must fit in chunk_bytes (TIDAL_E_INVAL otherwise; with the default 128 MiB that is a rank-64
+ * factor of a million columns). */
 typedef struct {
     int32_t slot;
     int32_t r;

@@ -655,6 +655,11 @@ static int validate_targets(const tidal_template* t, const tidal_lora_target* tg
         if (p.active() && s.elems > 0) {
             if (!dtype_ok(g.dtype)) return fail(TIDAL_E_INVAL, "target %d: unknown dtype %d", i, g.dtype);
             if (need_host && (!g.A || !g.B)) return fail(TIDAL_E_INVAL, "target %d: A or B is NULL", i);
+            // a factor is staged whole: it has to fit one staging buffer
+            const size_t longest = (size_t)std::max(s.rows, s.cols) * (size_t)g.r * dtype_size(g.dtype);
+            if (need_host && longest > t->cfg.chunk_bytes)
+                return fail(TIDAL_E_INVAL, "target %d: a LoRA factor of %zu bytes is larger than chunk_bytes (%zu)", i, longest,
+                            t->cfg.chunk_bytes);
             p.at_off = off;
             off = align_up(off + 2 * (size_t)s.cols * p.rp, kSlotAlign);
             p.bp_off = off;

@@ -128,6 +128,26 @@ def test_adapter_too_large_for_region():
         tb.tidal_template_destroy(t)
 
 
+def test_factor_larger_than_a_chunk_is_rejected_up_front():
+    """A factor is staged whole; one that cannot fit a staging buffer is an argument error of the call,
+    found before anything is enqueued (also when another target comes first)."""
+    shapes = [(8, 16), (64, 40000)]
+    cfg = tb.make_config(chunk_bytes=64 << 10, max_adapter_bytes=1 << 24)
+    t = tb.tidal_template_create(shapes, FAKE_ARENA, 1 << 40, cfg)
+    try:
+        a0, b0 = np.zeros((2, 16), np.float32), np.zeros((8, 2), np.float32)
+        A, B = np.zeros((1, 40000), np.float32), np.zeros((64, 1), np.float32)     # A: 160,000 bytes > 65,536
+        small = (0, 2, 4.0, tb.TIDAL_F32, a0.ctypes.data, b0.ctypes.data)
+        big = (1, 1, 2.0, tb.TIDAL_F32, A.ctypes.data, B.ctypes.data)
+        with pytest.raises(tb.TidalError) as e:
+            tb.tidal_lora_attach(t, [small, big])
+        assert e.value.code == tb.TIDAL_E_INVAL and "chunk_bytes" in str(e.value)
+        half = (1, 1, 2.0, tb.TIDAL_F16, A.ctypes.data, B.ctypes.data)             # 80,000 bytes: still too large
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_attach, t, [half])
+    finally:
+        tb.tidal_template_destroy(t)
+
+
 def _check_plan(plan, shapes, dtypes, chunk_bytes, coalesce, pinned):
     isz = {tb.TIDAL_F32: 4, tb.TIDAL_F16: 2, tb.TIDAL_BF16: 2}
     # every element of every slot is covered exactly once, in order
