@@ -671,6 +671,7 @@ static int validate_targets(const tidal_template* t, const tidal_lora_target* tg
         }
         rec->targets.push_back(p);
     }
+    if (off / kLoraUnit > 0xFFFFFFFFull) return fail(TIDAL_E_INVAL, "packed adapter larger than 1 TB");
     rec->bytes = off;
     return TIDAL_OK;
 }
@@ -865,6 +866,8 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
         const Side& n = kv.second.second;
         LoraTargetDev d;
         memset(&d, 0, sizeof d);
+        if (t->lay.slot_offset[kv.first] / kLoraUnit > 0xFFFFFFFFull)      // descriptors hold 32-bit offsets in 256-byte units
+            return fail(TIDAL_E_INVAL, "slot %d lies beyond 1 TB from the start of the arena", kv.first);
         d.w = (uint32_t)(t->lay.slot_offset[kv.first] / kLoraUnit);
         int rp_old = 0, rp_new = 0, r_old = 0, r_new = 0;
         if (o.p) {
@@ -1450,6 +1453,8 @@ extern "C" int tidal_fork_apply(tidal_fork* f, const tidal_adapter* a, void* str
         const PackedTarget* p = it->second;
         LoraTargetDev d;
         memset(&d, 0, sizeof d);
+        if (t->lay.slot_offset[slot] / kLoraUnit > 0xFFFFFFFFull)
+            return fail(TIDAL_E_INVAL, "slot %d lies beyond 1 TB from the start of the arena", slot);
         d.w = (uint32_t)(t->lay.slot_offset[slot] / kLoraUnit);
         d.at_old = (uint32_t)(f->offset[i] / kLoraUnit);               // destination, relative to the fork's memory
         d.at_new = (uint32_t)(p->at_off / kLoraUnit);
