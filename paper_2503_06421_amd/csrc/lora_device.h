@@ -113,6 +113,33 @@ __device__ __forceinline__ void apply_tile(uint32_t (&w)[16][NT / 2], const f32x
         for (int p = 0; p < NT / 2; ++p) w[v][p] = rmw2(w[v][p], acc[2 * p][v], acc[2 * p + 1][v], s);
 }
 
+// delta_tile and apply_tile in one: the tiles are produced two at a time (the two adjacent columns
+// of one 32-bit word of W) and consumed at once, so only 32 accumulator registers are live instead
+// of 16 * NT.  That is what lets two waves share a SIMD for the small ranks.
+template <int NT, int KS>
+__device__ __forceinline__ void delta_apply(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
+                                            const bf16x8 (&bop)[NT][KS ? KS : 1], uint32_t (&w)[16][NT / 2], float s) {
+    if constexpr (KS > 0) {
+        int m = i0 + (lane & 31);
+        m = m < out ? m : out - 1;
+        const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
+        bf16x8 aop[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+#pragma unroll
+        for (int q = 0; q < NT / 2; ++q) {
+            f32x16 c0 = {0}, c1 = {0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], bop[2 * q][ks], c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], bop[2 * q + 1][ks], c1, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) w[v][q] = rmw2(w[v][q], c0[v], c1[v], s);
+        }
+    }
+}
+
 // W is touched exactly once per pass, so its accesses carry the non-temporal hint (measured:
 // 4-6 % more bandwidth than plain accesses, the caches keep the A/B factors instead).
 template <typename V>

@@ -34,9 +34,14 @@ namespace tidal {
 
 // FORK: the result goes to a separate destination (old_base + at_old, which are free because a
 // fork never unmerges: KS0 == 0) and W itself, the template's pristine slot, is only read.
-template <int NT, int KS0, int KS1, bool FORK = false>
-__global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraBatch batch, int out, int in, int strips, int rowblocks,
-                                                        int rc, int blocks_per_target, int total_blocks) {
+// PAIR: the delta tiles are produced and consumed two at a time (32 live accumulator registers
+// instead of 128).  Instantiations whose registers then allow two waves per SIMD without spilling
+// (found by compiling) ask for them: A strips of up to 32 ranks in all, and 32 old + 16 new.
+constexpr bool two_waves_fit(int ks0, int ks1) { return ks0 + ks1 <= 2 || (ks0 == 2 && ks1 == 1); }
+
+template <int NT, int KS0, int KS1, bool FORK = false, bool PAIR = false>
+__global__ __launch_bounds__(256, (PAIR && two_waves_fit(KS0, KS1)) ? 2 : 1) void lora_mfma_kernel(
+    const LoraBatch batch, int out, int in, int strips, int rowblocks, int rc, int blocks_per_target, int total_blocks) {
     static_assert(!FORK || KS0 == 0, "a fork starts from the pristine template: nothing to unmerge");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -79,30 +84,43 @@ __global__ __launch_bounds__(256) void lora_mfma_kernel(const LoraBatch batch, i
         const bool full = strip_full && (i0 + 32 <= out);
         uint32_t w[16][NT / 2];
         load_block<NT>(W, out, in, i0, jl, h, full, w);
-        f32x16 acc[NT];
-        if constexpr (KS0 > 0) {
-            delta_tile<NT, KS0>(Bp_old, out, i0, lane, bop0, acc);
-            apply_tile<NT>(w, acc, d.s_old);
-        }
-        if constexpr (KS1 > 0) {
-            delta_tile<NT, KS1>(Bp_new, out, i0, lane, bop1, acc);
-            apply_tile<NT>(w, acc, d.s_new);
+        if constexpr (PAIR) {
+            delta_apply<NT, KS0>(Bp_old, out, i0, lane, bop0, w, d.s_old);
+            delta_apply<NT, KS1>(Bp_new, out, i0, lane, bop1, w, d.s_new);
+        } else {
+            f32x16 acc[NT];
+            if constexpr (KS0 > 0) {
+                delta_tile<NT, KS0>(Bp_old, out, i0, lane, bop0, acc);
+                apply_tile<NT>(w, acc, d.s_old);
+            }
+            if constexpr (KS1 > 0) {
+                delta_tile<NT, KS1>(Bp_new, out, i0, lane, bop1, acc);
+                apply_tile<NT>(w, acc, d.s_new);
+            }
         }
         store_block<NT>(FORK ? (uint16_t*)(batch.old_base + (size_t)d.at_old * kLoraUnit) : W, out, in, i0, jl, h,
                         full, w);
     }
 }
 
-template <int NT, int KS0, int KS1, bool FORK = false>
+template <int NT, int KS0, int KS1, bool FORK = false, bool PAIR = false>
 static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int strips = (g.in + 32 * NT - 1) / (32 * NT);
     const int rowblocks = (g.out + 31) / 32;
     // 32-row blocks per wave.  Short walks keep waves short-lived, which this memory system
-    // rewards (about 4 blocks at r <= 16), long walks amortise the A strip, which grows with the
-    // rank (about 16 blocks at 64 ranks); small jobs get fewer so that every CU has work.
+    // rewards, long walks amortise the A strip, which grows with the rank; small jobs get fewer so
+    // that every CU has work.  Measured per instantiation on 64 x 4096^2 and 40 x 5120^2: merges of
+    // up to 32 ranks and swaps where two waves share a SIMD want 4 blocks, a 64-rank merge 8, every
+    // other swap 16; on row pitches that are no power of two the short walks gain more, so the 4 and
+    // the 8 of the swaps and the 64-rank merge are halved.
     const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
-    int rc = 4 * (KS0 + KS1);
-    rc = rc < 4 ? 4 : (rc > 16 ? 16 : rc);
+    int rc;
+    if (PAIR) {
+        rc = two_waves_fit(KS0, KS1) ? 4 : ((KS0 == 0 || KS1 == 0) ? 8 : 16);
+        if ((g.in & (g.in - 1)) != 0 && rc <= 8) rc /= 2;
+    } else {
+        rc = 4;                      // merges of up to 32 ranks
+    }
     const int64_t by_size = tiles / 4096;
     if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
     if (const char* e = getenv("TIDAL_MFMA_RC")) {        // tuning runs only
@@ -114,31 +132,32 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     const int64_t total = (int64_t)blocks_per_target * g.n_targets;
     if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1, FORK>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
+    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1, FORK, PAIR>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
                        g.in, strips, rowblocks, rc, blocks_per_target, (int)total);
     return hipGetLastError();
 }
 
-// A strips stay in registers except where one side has 64 ranks and the other 64 or at most 16:
-// there they are staged in LDS by a kernel built in its own translation unit (measured on
-// 128 x 4096^2: 64 -> 64 6.4 instead of 4.7 TB/s, 64 <-> 8/16 about 3 % more, 64 <-> 32 about 4 %
-// less, hence not used there).
+// A strips stay in registers except in swaps with a 64-rank side: there they are staged in LDS by
+// a kernel built in its own translation unit (measured on 128 x 4096^2, LDS against registers:
+// 64 -> 64 6.4 against 5.9 TB/s, 16/32 -> 64 6.5 against 6.1-6.25, 64 -> 16/32 6.5 against 6.1-6.2;
+// merges of 64 ranks run at 6.5 either way and stay here).
 hipError_t launch_lora_mfma_lds(const LoraGroup& g, hipStream_t stream);
 bool lora_mfma_lds_available(int rp_old, int rp_new);
-constexpr int kLdsFromSteps = 8;
 
 template <int NT, int KS0, int KS1>
 static hipError_t launch_mfma_pick(const LoraGroup& g, hipStream_t stream, int use_lds) {
     if constexpr (KS0 + KS1 == 0) {
         return hipSuccess;
     } else {
+        int pair = (KS0 > 0 && KS1 > 0) || KS0 + KS1 >= 4;
+        if (const char* e = getenv("TIDAL_MFMA_PAIR")) pair = atoi(e) != 0;       // tuning runs only
         if constexpr (KS0 == 0) {
-            if (g.fork) return launch_mfma_inst<NT, 0, KS1, true>(g, stream);
+            if (g.fork) return pair ? launch_mfma_inst<NT, 0, KS1, true, true>(g, stream) : launch_mfma_inst<NT, 0, KS1, true>(g, stream);
         }
         if (g.fork) return hipErrorInvalidValue;
-        if (use_lds < 0) use_lds = (KS0 + KS1 >= kLdsFromSteps || (KS0 == 4 && KS1 == 1) || (KS0 == 1 && KS1 == 4)) ? 1 : 0;
+        if (use_lds < 0) use_lds = (KS0 > 0 && KS1 > 0 && (KS0 == 4 || KS1 == 4)) ? 1 : 0;
         if (use_lds && NT == 8 && lora_mfma_lds_available(16 * KS0, 16 * KS1)) return launch_lora_mfma_lds(g, stream);
-        return launch_mfma_inst<NT, KS0, KS1>(g, stream);
+        return pair ? launch_mfma_inst<NT, KS0, KS1, false, true>(g, stream) : launch_mfma_inst<NT, KS0, KS1>(g, stream);
     }
 }
 

@@ -1,9 +1,9 @@
 // LoRA fused swap where one adapter has 64 ranks: A strips staged in LDS.  gfx950 only.
 //
 // This file is compiled with -mllvm -amdgpu-mfma-vgpr-form: the MFMA results land in ordinary
-// VGPRs, which saves one accumulator-read instruction per element and, here, lets two waves
-// share a SIMD (measured 6.4 instead of 5.3 TB/s).  The other LoRA kernels are faster with the
-// accumulators in AGPRs and stay in their own translation unit.
+// VGPRs, which saves one accumulator-read instruction per element and, here, lets two or three
+// waves share a SIMD.  The other LoRA kernels are faster with the accumulators in AGPRs and stay
+// in their own translation unit.
 #include "lora_device.h"
 
 namespace tidal {
@@ -30,6 +30,29 @@ __device__ __forceinline__ void delta_tile_lds(const uint16_t* __restrict__ Bp, 
         for (int ks = 0; ks < KS; ++ks)
             c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[(T * KS + ks) * 64 + lane], c, 0, 0, 0);
         acc[T] = c;
+    }
+}
+
+// The same with the tiles produced and consumed two at a time (32 live accumulator registers).
+template <int NT, int KS>
+__device__ __forceinline__ void delta_apply_lds(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
+                                                const bf16x8* strip, uint32_t (&w)[16][NT / 2], float s) {
+    int m = i0 + (lane & 31);
+    m = m < out ? m : out - 1;
+    const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
+    bf16x8 aop[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+#pragma unroll
+    for (int q = 0; q < NT / 2; ++q) {
+        f32x16 c0 = {0}, c1 = {0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[((2 * q) * KS + ks) * 64 + lane], c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[((2 * q + 1) * KS + ks) * 64 + lane], c1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w[v][q] = rmw2(w[v][q], c0[v], c1[v], s);
     }
 }
 
@@ -80,12 +103,15 @@ __global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraBatch batc
         const bool full = strip_full && (i0 + 32 <= out);
         uint32_t w[16][NT / 2];
         load_block<NT>(W, out, in, i0, jl, h, full, w);
-        f32x16 acc[NT];
-        if constexpr (KS0 > 0) {
+        // Tiles two at a time (three waves per SIMD at 64 -> 16/32, measured 6.5 against 5.4-5.8 TB/s
+        // with all eight live); 64 -> 64 is the exception, 2 % faster with all eight.
+        if constexpr (KS0 + KS1 < 8) {
+            delta_apply_lds<NT, KS0>(Bp_old, out, i0, lane, strip_lds, w, d.s_old);
+            delta_apply_lds<NT, KS1>(Bp_new, out, i0, lane, strip_lds + KS0 * NT * 64, w, d.s_new);
+        } else {
+            f32x16 acc[NT];
             delta_tile_lds<NT, KS0>(Bp_old, out, i0, lane, strip_lds, acc);
             apply_tile<NT>(w, acc, d.s_old);
-        }
-        if constexpr (KS1 > 0) {
             delta_tile_lds<NT, KS1>(Bp_new, out, i0, lane, strip_lds + KS0 * NT * 64, acc);
             apply_tile<NT>(w, acc, d.s_new);
         }
@@ -98,7 +124,10 @@ static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
     const int strips = (g.in + 32 * NT - 1) / (32 * NT);
     const int rowblocks = (g.out + 31) / 32;
     const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
-    int rc = 16;                                     // 32-row blocks per wave
+    // 32-row blocks per wave (measured, 64 and 128 slots of 4096^2, 40 of 5120^2 and 15 of the two
+    // 13824-wide shapes): 16 for 64 -> 64, else 8; 4 and 2 where the row pitch is no power of two
+    const bool pow2_pitch = (g.in & (g.in - 1)) == 0;
+    int rc = (KS0 + KS1 >= 8) ? (pow2_pitch ? 16 : 4) : (pow2_pitch ? 8 : 2);
     const int64_t by_size = tiles / 4096;
     if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
     if (const char* e = getenv("TIDAL_MFMA_RC")) {   // tuning runs only
