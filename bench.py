@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per lora_mfma_kernel launch on the default workload (32 layers, r=16, 64 targets), from
 # the two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 calibration factor + WRITE_SIZE x 1.0) whose
 # summary is kept under profiles/: mean of the attach and the fused-swap launch.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 4_320_965_000
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 4_320_981_000
 
 
 def log(*a):
