@@ -39,6 +39,12 @@ def _stale(target: str, deps) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+# TIDAL_TUNING_KNOBS=1 in the environment of the build: the library then reads TIDAL_MFMA_* /
+# TIDAL_APPLY_* from the environment at run time (sweeps); use --force when switching.
+if os.environ.get("TIDAL_TUNING_KNOBS", "0") not in ("", "0"):
+    FLAGS.append("-DTIDAL_TUNING_KNOBS")
+
+
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)

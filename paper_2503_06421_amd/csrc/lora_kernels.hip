@@ -123,7 +123,7 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     }
     const int64_t by_size = tiles / 4096;
     if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
-    if (const char* e = getenv("TIDAL_MFMA_RC")) {        // tuning runs only
+    if (const char* e = tuning_knob("TIDAL_MFMA_RC")) {        // tuning builds only
         const int v = atoi(e);
         if (v >= 1 && v <= 1024) rc = v;
     }
@@ -150,7 +150,7 @@ static hipError_t launch_mfma_pick(const LoraGroup& g, hipStream_t stream, int u
         return hipSuccess;
     } else {
         int pair = (KS0 > 0 && KS1 > 0) || KS0 + KS1 >= 4;
-        if (const char* e = getenv("TIDAL_MFMA_PAIR")) pair = atoi(e) != 0;       // tuning runs only
+        if (const char* e = tuning_knob("TIDAL_MFMA_PAIR")) pair = atoi(e) != 0;       // tuning builds only
         if constexpr (KS0 == 0) {
             if (g.fork) return pair ? launch_mfma_inst<NT, 0, KS1, true, true>(g, stream) : launch_mfma_inst<NT, 0, KS1, true>(g, stream);
         }
@@ -185,13 +185,13 @@ static hipError_t launch_mfma_old(const LoraGroup& g, hipStream_t stream, int us
 
 hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream) {
     if (g.n_targets <= 0 || g.out <= 0 || g.in <= 0) return hipSuccess;
-    const char* e_nt = getenv("TIDAL_MFMA_NT");             // tuning runs only
-    const char* e_lds = getenv("TIDAL_MFMA_LDS");           // tuning runs only
-    int nt = e_nt ? atoi(e_nt) : 0;
+    const char* e_lds = tuning_knob("TIDAL_MFMA_LDS");      // tuning builds only
     const int use_lds = e_lds ? atoi(e_lds) : -1;
-    if (nt != 4 && nt != 8) nt = 8;
-    if (nt == 8) return launch_mfma_old<8>(g, stream, use_lds);
-    return launch_mfma_old<4>(g, stream, use_lds);
+#ifdef TIDAL_TUNING_KNOBS
+    const char* e_nt = tuning_knob("TIDAL_MFMA_NT");        // strips of 128 columns: measured 5-10 % slower
+    if (e_nt && atoi(e_nt) == 4) return launch_mfma_old<4>(g, stream, use_lds);
+#endif
+    return launch_mfma_old<8>(g, stream, use_lds);
 }
 
 // ---------------------------------------------------------------------------------------

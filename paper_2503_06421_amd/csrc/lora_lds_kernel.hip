@@ -130,7 +130,7 @@ static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
     int rc = (KS0 + KS1 >= 8) ? (pow2_pitch ? 16 : 4) : (pow2_pitch ? 8 : 2);
     const int64_t by_size = tiles / 4096;
     if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
-    if (const char* e = getenv("TIDAL_MFMA_RC")) {   // tuning runs only
+    if (const char* e = tuning_knob("TIDAL_MFMA_RC")) {   // tuning builds only
         const int v = atoi(e);
         if (v >= 1 && v <= 1024) rc = v;
     }

@@ -1246,7 +1246,7 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
             // small batches spread over the chip (aim: >= 1024 waves; measured best of 1, 2, 4)
             const int64_t strips = (launch_out + 255) / 256;
             int ct = (int)std::max<int64_t>(1, std::min<int64_t>(kApplyChunkTiles, tiles * strips / 1024));
-            if (const char* e = getenv("TIDAL_APPLY_CT")) {       // tuning runs only
+            if (const char* e = tuning_knob("TIDAL_APPLY_CT")) {       // tuning builds only
                 const int v = atoi(e);
                 if (v >= 1 && v <= kApplyChunkTiles) ct = v;
             }

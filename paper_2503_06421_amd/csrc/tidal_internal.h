@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "tidal.h"
 
@@ -171,6 +172,18 @@ hipError_t launch_apply_ordered(const ApplyLongBatch& b, int in, bool shrink, hi
 // Vector-ALU pair for the short segments.
 hipError_t launch_apply_shrink_short(const ApplyShortBatch& b, int in, hipStream_t stream);
 hipError_t launch_apply_expand_short(const ApplyShortBatch& b, int max_out, hipStream_t stream);
+
+// Knobs for tuning runs (walk lengths, kernel variants).  They are read from the environment only
+// in builds made with -DTIDAL_TUNING_KNOBS (TIDAL_TUNING_KNOBS=1 python -m ...build --force); the
+// default build ignores the environment and has no code path that depends on it.
+inline const char* tuning_knob(const char* name) {
+#ifdef TIDAL_TUNING_KNOBS
+    return getenv(name);
+#else
+    (void)name;
+    return nullptr;
+#endif
+}
 
 inline int padded_rank(int r) { return r <= 0 ? 0 : (r <= 16 ? 16 : (r <= 32 ? 32 : 64)); }
 
