@@ -76,9 +76,10 @@ __global__ __launch_bounds__(256, (PAIR && two_waves_fit(KS0, KS1)) ? 2 : 1) voi
     const bool strip_full = (j0 + 32 * NT <= in) && (in % NT == 0);
     const int rb_end = (rowchunk + 1) * rc < rowblocks ? (rowchunk + 1) * rc : rowblocks;
 
-    // One block of loads per wave is in flight at a time; requesting the next 32-row block
-    // early (software prefetch) was measured and is slower: the extra registers cost more than
-    // the overlap gains, the memory system is already saturated.
+    // One block of loads per wave is in flight at a time.  Requesting the next 32-row block early
+    // (software prefetch, a second set of W registers) was measured: 2-3 % slower on power-of-two
+    // pitches, 1-2 % faster on the others for merges of up to 32 ranks at 2 blocks per wave, nothing
+    // at 64 ranks -- not worth a second set of instantiations.
     for (int rb = rowchunk * rc; rb < rb_end; ++rb) {
         const int i0 = rb * 32;
         const bool full = strip_full && (i0 + 32 <= out);
@@ -112,7 +113,9 @@ static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
     // that every CU has work.  Measured per instantiation on 64 x 4096^2 and 40 x 5120^2: merges of
     // up to 32 ranks and swaps where two waves share a SIMD want 4 blocks, a 64-rank merge 8, every
     // other swap 16; on row pitches that are no power of two the short walks gain more, so the 4 and
-    // the 8 of the swaps and the 64-rank merge are halved.
+    // the 8 of the swaps and the 64-rank merge are halved.  (A 16-rank merge looks 2-3 % faster at 2
+    // blocks in a sweep where all slots share one adapter; with an adapter per slot, as in the
+    // 70B-shaped stack, it is 1 % slower: the A strips then come from HBM, not from L2.)
     const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
     int rc;
     if (PAIR) {
