@@ -355,3 +355,31 @@ def test_pipelined_upload_gives_the_same_bits(G, flags):
     for k in range(3):
         for i in range(len(shapes)):
             assert np.array_equal(res[0][k][i], res[1][k][i]), (k, i)
+
+
+@pytest.mark.parametrize("out,inn,r", [(203, 331, 5), (77, 8203, 5)], ids=["gathered", "pinned-direct"])
+@pytest.mark.parametrize("offset", [0, 2, 6, 16, 30])
+def test_small_factors_at_any_host_alignment(orc, G, offset, out, inn, r):
+    """Factors of a few hundred KB are fetched from pinned host memory by a kernel when source and
+    destination are 16-byte aligned, and by the copy engine otherwise; lengths that are no multiple
+    of 16 bytes end in a byte-wise tail.  Place A and B at several byte offsets of one pinned buffer,
+    with ragged sizes, and compare the merge with the oracle bit for bit."""
+    # "gathered": both factors are below the coalescing threshold and pass through the library's pinned
+    # buffer (A 3310 B, B 2030 B); "pinned-direct": A (82,030 B) is fetched from the caller's memory
+    W, A, B = make_problem(70 + offset, out, inn, r, dtype=np.float16)
+    buf = torch.empty(1 << 18, dtype=torch.uint8, pin_memory=True)
+    raw = buf.numpy()
+    a_off = offset
+    b_off = (a_off + A.nbytes + 15) // 16 * 16 + offset      # B misaligned by the same amount
+    a_view = raw[a_off:a_off + A.nbytes].view(np.float16).reshape(A.shape)
+    b_view = raw[b_off:b_off + B.nbytes].view(np.float16).reshape(B.shape)
+    a_view[...] = A
+    b_view[...] = B
+    with G.Template([(out, inn)], flags=ORDERED, max_adapter_bytes=1 << 20) as T:
+        T.materialize({0: W})
+        want = orc.convert_to_bf16(W)
+        tb.tidal_lora_attach(T.h, tb.targets_from_arrays([(0, 10.0, a_view, b_view)]), T.compute_stream)
+        T.sync()
+        orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 10.0, +1)
+        assert np.array_equal(T.slot(0), want)
+    del buf
