@@ -286,9 +286,9 @@ int tidal_lora_apply_multi(tidal_template* t, const int32_t* slots /* [host] */,
                            const void* x /* [device] */, void* const* ys /* [host] array of [device] in/out */,
                            int32_t n_tokens, void* workspace /* [device] */, size_t workspace_bytes, void* stream);
 
-/* Copy-on-write forks (Sec. 1: a template must stay request-agnostic, "a copy-on-write
- * mechanism is critical for safe template sharing"; Sec. 5.2: a write to a forked weight goes
- * to a new tensor).  A fork owns private copies, in caller-owned device memory, of the slots an
+/* Copy-on-write forks (Sec. 1: a template must stay request-agnostic, so state that an
+ * invocation writes may not be shared; Sec. 5.2: a write to a forked weight goes to a new
+ * tensor).  A fork owns private copies, in caller-owned device memory, of the slots an
  * invocation's adapter writes; the template's slots are only read.  tidal_fork_apply rewrites
  * every private copy from the pristine template in one pass:
  *     fork[s] <- bf16( f32(template[s]) + (alpha/r) * B * A )   for slots the adapter targets,
