@@ -286,6 +286,24 @@ int tidal_lora_apply_multi(tidal_template* t, const int32_t* slots /* [host] */,
                            const void* x /* [device] */, void* const* ys /* [host] array of [device] in/out */,
                            int32_t n_tokens, void* workspace /* [device] */, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation: tidal_lora_apply for one target slot without a
+ * workspace argument.  The rank-space intermediate lives in a fixed array inside the library
+ * (128 bytes per token row, tidal_lora_apply_static_max_tokens() = 16384 rows, 2 MiB that each GPU
+ * the library runs on holds until the process ends); the call allocates nothing, on the device or
+ * through any library, and creates no HIP object.  Arguments, results and errors are those of
+ * tidal_lora_apply, and the same kernels run, so the results are bit-identical to it;
+ * in addition n_tokens above the maximum gives TIDAL_E_INVAL, and TIDAL_E_STATE is returned if no
+ * template has done device work on the current GPU yet (uploading the adapters does).  All calls
+ * on one GPU share the array, whatever template or stream they use, and it keeps the last call's
+ * contents (nothing in it needs clearing: every row a call reads it has written first): calls
+ * that may overlap on one GPU race and must be ordered by the caller (one stream, or events). */
+int32_t tidal_lora_apply_static_max_tokens(void);
+int tidal_lora_apply_static(tidal_template* t, int32_t slot, const tidal_adapter* const* adapters /* [host] */,
+                            int32_t n_adapters, const tidal_lora_segment* segments /* [host] */, int32_t n_segments,
+                            const void* x /* [device] */, void* y /* [device] in/out */, int32_t n_tokens,
+                            void* stream);
+
 /* Copy-on-write forks (Sec. 1: a template must stay request-agnostic, so state that an
  * invocation writes may not be shared; Sec. 5.2: a write to a forked weight goes to a new
  * tensor).  A fork owns private copies, in caller-owned device memory, of the slots an

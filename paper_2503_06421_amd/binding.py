@@ -30,6 +30,7 @@ EXPORTS = [
     "tidal_materialize_plan", "tidal_materialize_attach", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
     "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_lora_apply_workspace_bytes", "tidal_lora_apply", "tidal_lora_apply_multi",
+    "tidal_lora_apply_static", "tidal_lora_apply_static_max_tokens",
     "tidal_fork_required_bytes", "tidal_fork_create",
     "tidal_fork_apply", "tidal_fork_slot_ptr", "tidal_fork_destroy", "tidal_template_slot_ptr",
     "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
@@ -124,6 +125,10 @@ def lib() -> ctypes.CDLL:
                                    c_int32, vp, c_size_t, vp]
     L.tidal_lora_apply_multi.argtypes = [vp, POINTER(c_int32), c_int32, POINTER(vp), c_int32, POINTER(tidal_lora_segment),
                                          c_int32, vp, POINTER(vp), c_int32, vp, c_size_t, vp]
+    L.tidal_lora_apply_static_max_tokens.restype = c_int32
+    L.tidal_lora_apply_static_max_tokens.argtypes = []
+    L.tidal_lora_apply_static.argtypes = [vp, c_int32, POINTER(vp), c_int32, POINTER(tidal_lora_segment), c_int32, vp, vp,
+                                          c_int32, vp]
     L.tidal_fork_required_bytes.restype = c_size_t
     L.tidal_fork_required_bytes.argtypes = [vp, POINTER(c_int32), c_int32]
     L.tidal_fork_create.argtypes = [vp, POINTER(c_int32), c_int32, vp, c_size_t, POINTER(vp)]
@@ -341,6 +346,19 @@ def tidal_lora_apply(t, slot: int, adapters, segments, x, y, n_tokens: int, work
         adapters, segments = lora_apply_arrays(adapters, segments)
     _check(lib().tidal_lora_apply(t, slot, adapters[0], adapters[1], segments[0], segments[1], device_ptr(x),
                                   device_ptr(y), n_tokens, device_ptr(workspace), workspace_bytes, stream_ptr(stream)))
+
+
+def tidal_lora_apply_static_max_tokens() -> int:
+    return lib().tidal_lora_apply_static_max_tokens()
+
+
+def tidal_lora_apply_static(t, slot: int, adapters, segments, x, y, n_tokens: int, stream=None) -> None:
+    """tidal_lora_apply without a workspace: the library's fixed scratch array is used."""
+    if not (isinstance(adapters, tuple) and isinstance(segments, tuple) and len(segments) == 2
+            and isinstance(segments[0], ctypes.Array)):
+        adapters, segments = lora_apply_arrays(adapters, segments)
+    _check(lib().tidal_lora_apply_static(t, slot, adapters[0], adapters[1], segments[0], segments[1], device_ptr(x),
+                                         device_ptr(y), n_tokens, stream_ptr(stream)))
 
 
 def tidal_lora_apply_multi(t, slots, adapters, segments, x, ys, n_tokens: int, workspace, workspace_bytes: int,

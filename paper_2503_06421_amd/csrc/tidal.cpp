@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -72,6 +73,38 @@ struct SlotState {
 
 constexpr int kMaxUploadGroups = 8;
 
+// ---------------------------------------------------------------------------------------
+// scratch memory of the allocation-free apply (tidal_lora_apply_static)
+// ---------------------------------------------------------------------------------------
+// The rank-space intermediate u = bf16(A x) of the unmerged apply normally lives in a workspace the
+// caller allocates.  Callers that cannot allocate get it from this array instead: 128 bytes per
+// token row, kStaticApplyTokens rows, 2 MiB that every GPU the library runs on holds until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels
+// and copies get the per-device address that call returns.
+constexpr int32_t kStaticApplyTokens = 16384;
+constexpr size_t kStaticScratchBytes = (size_t)kStaticApplyTokens * kApplyRankStride * 2;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};          // per device: each GPU has its own copy of the array
+
+// Set-up step, run with the device current that the calling template works on: resolves this
+// device's address of the scratch array once.
+static int resolve_scratch() {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TIDAL_E_HIP, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(TIDAL_E_HIP, "hipGetSymbolAddress returned no address for the scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    return TIDAL_OK;
+}
+
 struct tidal_adapter {
     tidal_template* owner;
     AdapterRec rec;
@@ -133,6 +166,8 @@ static int ensure_device(tidal_template* t) {
     HIP_TRY(hipEventCreateWithFlags(&t->ev_copy_done, flags));
     HIP_TRY(hipEventCreateWithFlags(&t->ev_last_compute, flags));
     HIP_TRY(hipEventCreateWithFlags(&t->ev_last_lora, flags));
+    int rc = resolve_scratch();
+    if (rc) return rc;
     t->dev_ready = true;
     return TIDAL_OK;
 }
@@ -1083,7 +1118,7 @@ extern "C" size_t tidal_lora_apply_workspace_bytes(int32_t n_tokens) {
 static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_slots,
                            const tidal_adapter* const* adapters, int32_t n_adapters, const tidal_lora_segment* segs,
                            int32_t n_segs, const void* x, void* const* ys, int32_t n_tokens, void* workspace,
-                           size_t workspace_bytes, void* stream_) {
+                           size_t workspace_bytes, void* stream_, bool no_alloc = false) {
     if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
     if (n_slots < 0 || (!slots && n_slots > 0)) return fail(TIDAL_E_INVAL, "bad slot list");
     if (n_adapters < 0 || (!adapters && n_adapters > 0)) return fail(TIDAL_E_INVAL, "bad adapter list");
@@ -1191,7 +1226,10 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
     if (workspace_bytes < tidal_lora_apply_workspace_bytes((int32_t)ws_tokens))
         return fail(TIDAL_E_NOMEM, "workspace needs %zu bytes, got %zu", tidal_lora_apply_workspace_bytes((int32_t)ws_tokens),
                     workspace_bytes);
-    int rc = ensure_device(t);
+    // resident adapters exist, so their upload has set the template's device side up already; the
+    // allocation-free entry point relies on that and creates nothing
+    if (no_alloc && !t->dev_ready) return fail(TIDAL_E_STATE, "the template has not been used on a device yet");
+    int rc = no_alloc ? TIDAL_OK : ensure_device(t);
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)stream_;
     if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));   // adapter uploads
@@ -1316,6 +1354,27 @@ extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_ada
     void* ys[1] = {y};
     return lora_apply_impl(t, &slot, 1, adapters, n_adapters, segs, n_segs, x, ys, n_tokens, workspace, workspace_bytes,
                            stream);
+}
+
+extern "C" int32_t tidal_lora_apply_static_max_tokens(void) { return kStaticApplyTokens; }
+
+extern "C" int tidal_lora_apply_static(tidal_template* t, int32_t slot, const tidal_adapter* const* adapters,
+                                       int32_t n_adapters, const tidal_lora_segment* segs, int32_t n_segs,
+                                       const void* x, void* y, int32_t n_tokens, void* stream) {
+    if (n_tokens > kStaticApplyTokens)
+        return fail(TIDAL_E_INVAL, "n_tokens = %d exceeds the %d token rows the library's scratch memory holds; "
+                    "use tidal_lora_apply with a workspace", n_tokens, kStaticApplyTokens);
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    void* ws = nullptr;
+    if (dev >= 0 && dev < kMaxDevices) {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        ws = g_scratch_ptr[dev];
+    }
+    if (!ws) return fail(TIDAL_E_STATE, "no template has been set up on device %d yet (adapters are uploaded first)", dev);
+    void* ys[1] = {y};
+    return lora_apply_impl(t, &slot, 1, adapters, n_adapters, segs, n_segs, x, ys, n_tokens, ws, kStaticScratchBytes,
+                           stream, true);
 }
 
 extern "C" int tidal_lora_apply_multi(tidal_template* t, const int32_t* slots, int32_t n_slots,
