@@ -102,15 +102,18 @@ enum {
      * copy and tiny tensors are not gathered by the CPU.  For measuring what tensor merging
      * (Sec. 6) buys; results are identical.                                                    */
     TIDAL_FLAG_NO_COPY_MERGE = 32,
-    /* tidal_lora_attach / _swap with adapters of 4 MiB or more: upload and merge in groups of
-     * targets (three groups of 1/8, 2/8, 5/8 of the upload where the merge takes at least twice
-     * as long as the upload, else eight equal ones), the upload of a group on a stream of the
-     * library's own while the group before it is merged on the caller's.  Shorter time per
-     * invocation, several smaller launches instead of one (each a little less efficient);
-     * results are identical.  The extra stream shares the process's few hardware queues with
-     * the caller's streams: with four or more streams of the caller's in use, work on one of
-     * them may queue behind the uploads.                                                       */
-    TIDAL_FLAG_PIPELINED_UPLOAD = 64
+    /* tidal_lora_attach / _swap upload and merge an adapter in groups of targets: while one group
+     * is packed and merged on the caller's stream, the next one's factors cross the link on a stream
+     * of the library's own, so most of the upload hides under the merge (or the other way round).
+     * By default the library does this for adapters of 4 MiB or more where its estimate says it
+     * pays, with groups sized from link and pass rates it measures with its own events; results are
+     * identical to a single pass either way.  PIPELINED_UPLOAD: always (two groups or more, whatever
+     * the size); SERIAL_UPLOAD: never -- everything on the caller's stream, upload first, then one
+     * launch per group of equal shapes.  (The extra stream shares the process's few hardware queues
+     * with the caller's streams: with four or more streams of the caller's in use, work on one of
+     * them may queue behind the uploads.)                                                         */
+    TIDAL_FLAG_PIPELINED_UPLOAD = 64,
+    TIDAL_FLAG_SERIAL_UPLOAD = 128
 };
 
 typedef struct {
@@ -227,7 +230,25 @@ int tidal_materialize_attach(tidal_template* t, const tidal_src* srcs /* [host] 
                              const tidal_lora_target* targets /* [host] */, int32_t n_targets,
                              void* copy_stream, void* compute_stream);
 
-/* Subtract the attached adapter's delta (same packed bf16 copy that was merged). */
+/* How a LoRA pass (attach: r_old = 0; detach: r_new = 0; swap: both; fork != 0: tidal_fork_apply)
+ * over n_targets slots of out x in would be launched: kernel and compile-time variant, 32-row
+ * blocks a wave walks, workgroups.  Host-only introspection, like tidal_materialize_plan: tests
+ * use it to show that they exercise the launch geometry the full-size workloads run with. */
+typedef struct {
+    char kernel[64];             /* e.g. "lora_mfma_kernel<8,0,4,inplace,pair>" (strip width / 32, padded
+                                    old and new rank / 16, destination, delta tiles two at a time or all) */
+    int32_t launches;            /* groups of more than 128 slots are cut into equal launches         */
+    int32_t targets_per_launch;
+    int32_t rank_padded_old, rank_padded_new;   /* 0, 16, 32 or 64                                    */
+    int32_t blocks_per_walk;     /* 32-row blocks one wave walks down its 256-column strip             */
+    int32_t waves_per_simd;      /* occupancy the variant asks for in its launch bounds                */
+    int64_t workgroups;          /* of 256 threads, per launch                                         */
+} tidal_lora_launch;
+int tidal_lora_launch_info(const tidal_template* t, int64_t out, int64_t in, int32_t n_targets, int32_t r_old,
+                           int32_t r_new, int32_t fork, tidal_lora_launch* info /* [host] out */);
+
+/* Subtract the attached adapter's delta (same packed bf16 copy that was merged): the keep-alive
+ * path of Sec. 5.2 run backwards, leaving only the static state. */
 int tidal_lora_detach(tidal_template* t, void* stream);
 
 /* Resident adapters: the packed bf16 device copy lives in caller-owned device memory, so
@@ -364,6 +385,16 @@ int tidal_convert_device(void* dst_bf16 /* [device] */, const void* src /* [devi
  * host buffer the call allocates, into dev.  Blocks until done. */
 int tidal_h2d_peak(void* dev /* [device] */, size_t bytes, int32_t reps, void* stream,
                    double* gbytes_per_s /* [host] out */);
+
+/* What a bare in-place pass over HBM runs at in the LoRA kernels' own tiling: n matrices of
+ * rows x cols 16-bit elements, back to back at dev, every 256-column strip walked down by one wave
+ * in runs of blocks_per_walk blocks of 32 rows, each 16-byte word loaded, one bit flipped, stored
+ * back (an even number of passes leaves the memory as it was).  4 bytes of traffic per element and
+ * no arithmetic: the measured ceiling of a merge for that row pitch and walk length, next to the
+ * published peak.  Best of `reps` timed passes after a warm-up one; blocks until done.  rows must
+ * be a multiple of 32, cols of 256, dev 16-byte aligned and n*rows*cols*2 bytes long. */
+int tidal_hbm_rmw_peak(void* dev /* [device] in/out */, int64_t rows, int64_t cols, int64_t n, int32_t blocks_per_walk,
+                       int32_t reps, void* stream, double* gbytes_per_s /* [host] out */);
 
 int tidal_get_stats(tidal_template* t, tidal_stats* out /* [host] out */);
 int tidal_reset_stats(tidal_template* t);

@@ -1,7 +1,7 @@
 """Measurements of the other workload configurations (bench.py at the repository root times the
 Llama2-7B-shaped headline workload).
 
-    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging|apply|coldstart
+    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging|apply|coldstart|pitch
 
 Each prints one JSON line.  Kernel times come from the library's HIP events around each launch
 (TIDAL_FLAG_KERNEL_TIMING); call-level times from events on the compute stream.
@@ -153,9 +153,9 @@ def bench_stack(args, wl, pool_limit=None):
     pool = hz.HostPool(wl, limit_bytes=pool_limit)
     log("host pool ready in %.1f s (%s)" % (pool.draw_seconds, "wrapped" if pool.wrapped else "full"))
     items, keep = hz.pinned_adapter(wl, 0)
-    flags = tb.TIDAL_FLAG_KERNEL_TIMING | (tb.TIDAL_FLAG_PIPELINED_UPLOAD if args.pipelined_upload else 0)
+    flags = tb.TIDAL_FLAG_KERNEL_TIMING | (tb.TIDAL_FLAG_SERIAL_UPLOAD if args.serial_upload else 0)
     T = hz.DeviceTemplate(wl.shapes, max_adapter_bytes=hz.packed_adapter_bytes(wl), flags=flags)
-    out = {"config": wl.name + ("_pipelined_upload" if args.pipelined_upload else ""), "source_GB": round(wl.source_bytes / 1e9, 3), "host_pool": "wrapped into %.1f GiB" % (pool_limit / 2**30) if pool.wrapped else "full"}
+    out = {"config": wl.name + ("_serial_upload" if args.serial_upload else ""), "source_GB": round(wl.source_bytes / 1e9, 3), "host_pool": "wrapped into %.1f GiB" % (pool_limit / 2**30) if pool.wrapped else "full"}
     try:
         probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
         peak = tb.tidal_h2d_peak(probe, 1 << 30, 3, T.copy_stream)
@@ -190,6 +190,58 @@ def bench_stack(args, wl, pool_limit=None):
             "lora_kernel_GBps": round(b / k_ms / 1e6, 1), "frac_of_hbm_peak": round(b / k_ms / 1e6 / HBM_PEAK, 4)})
     finally:
         T.close()
+    return out
+
+
+def bench_pitch(args):
+    """One merge launch per shape, warm (back-to-back attach / detach of a resident adapter): the
+    4096-wide power-of-two row pitch next to the three shapes of the 13B-shaped stack, each with the
+    bare read-modify-write probe in the same tiling and walk length beside it.  The run the
+    memory-side counters are collected on (one dispatch per shape and direction)."""
+    shapes = [(4096, 4096, 64), (5120, 5120, 80), (13824, 5120, 80), (5120, 13824, 40)]
+    r = args.rank
+    out = {"config": "merge_by_row_pitch_r%d" % r, "shapes": []}
+    for rows, cols, n in shapes:
+        T = hz.DeviceTemplate([(rows, cols)] * n, flags=tb.TIDAL_FLAG_KERNEL_TIMING)
+        try:
+            rng = np.random.default_rng(rows + cols)
+            w = torch.from_numpy(rng.normal(0, 0.02, (rows, cols)).astype(np.float16)).pin_memory()
+            tb.tidal_materialize(T.h, [(i, tb.TIDAL_F16, w.data_ptr()) for i in range(n)], T.copy_stream, T.compute_stream)
+            T.sync()
+            A = rng.normal(0, 0.01, (r, cols)).astype(np.float16)
+            B = rng.normal(0, 0.01, (rows, r)).astype(np.float16)
+            tg = [(i, r, 2.0 * r, tb.TIDAL_F16, A.ctypes.data, B.ctypes.data) for i in range(n)]   # one device copy per slot
+            nb = tb.tidal_adapter_required_bytes(T.h, tg)
+            mem = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+            a = tb.tidal_adapter_upload(T.h, tg, mem, nb, T.compute_stream)
+            T.sync()
+            info = tb.tidal_lora_launch_info(T.h, rows, cols, n, 0, r)
+            ms = []
+            for rep in range(args.reps + 1):
+                tb.tidal_reset_stats(T.h)
+                tb.tidal_lora_attach_adapter(T.h, a, T.compute_stream)
+                tb.tidal_lora_detach(T.h, T.compute_stream)
+                T.sync()
+                if rep:
+                    ms.append(tb.tidal_get_stats(T.h)["lora_kernel_ms"] / 2)
+            rp = 16 if r <= 16 else (32 if r <= 32 else 64)
+            byt = 4.0 * n * rows * cols + n * 2 * rp * (rows + cols)
+            k_ms = float(np.median(ms))
+            p0, _ = tb.tidal_template_slot_ptr(T.h, 0)
+            bare = tb.tidal_hbm_rmw_peak(p0, rows, cols, n, info["blocks_per_walk"], 4, T.compute_stream)
+            bare1 = tb.tidal_hbm_rmw_peak(p0, rows, cols, n, 1, 4, T.compute_stream)
+            rec = {"shape": "%d x %d x %d" % (n, rows, cols), "row_pitch_bytes": 2 * cols, "kernel": info["kernel"],
+                   "blocks_per_walk": info["blocks_per_walk"], "kernel_ms": round(k_ms, 4),
+                   "GBps": round(byt / k_ms / 1e6, 1), "frac_of_hbm_peak": round(byt / k_ms / 1e6 / HBM_PEAK, 4),
+                   "bare_rmw_same_walk_GBps": round(bare, 1), "frac_of_bare_rmw": round(byt / k_ms / 1e6 / bare, 4),
+                   "bare_rmw_one_block_per_wave_GBps": round(bare1, 1)}
+            out["shapes"].append(rec)
+            log(json.dumps(rec))
+            tb.tidal_adapter_destroy(a)
+        finally:
+            T.close()
+        del T
+        torch.cuda.empty_cache()
     return out
 
 
@@ -514,10 +566,11 @@ def bench_apply(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply", "coldstart"])
+    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply", "coldstart", "pitch"])
+    ap.add_argument("--rank", type=int, default=64, help="pitch: rank of the merged adapter")
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
-    ap.add_argument("--pipelined-upload", action="store_true", help="13b / 70b: TIDAL_FLAG_PIPELINED_UPLOAD")
+    ap.add_argument("--serial-upload", action="store_true", help="13b / 70b: TIDAL_FLAG_SERIAL_UPLOAD")
     ap.add_argument("--layers", type=int, default=32, help="apply: distinct layers (sets of factors and activations) per pass")
     ap.add_argument("--case", default="", help="apply: only cases whose name contains this")
     args = ap.parse_args()
@@ -537,6 +590,8 @@ def main():
         out = bench_apply(args)
     elif args.config == "coldstart":
         out = bench_coldstart(args)
+    elif args.config == "pitch":
+        out = bench_pitch(args)
     else:
         out = bench_churn(args)
     print(json.dumps(out), flush=True)

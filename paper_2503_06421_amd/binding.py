@@ -24,17 +24,18 @@ TIDAL_FLAG_ORDERED_ACCUM, TIDAL_FLAG_TWO_PASS_SWAP, TIDAL_FLAG_SLOT_EVENTS, TIDA
 TIDAL_FLAG_ASYNC_ENQUEUE = 16
 TIDAL_FLAG_NO_COPY_MERGE = 32
 TIDAL_FLAG_PIPELINED_UPLOAD = 64
+TIDAL_FLAG_SERIAL_UPLOAD = 128
 
 EXPORTS = [
     "tidal_config_default", "tidal_template_required_bytes", "tidal_template_create", "tidal_materialize",
     "tidal_materialize_plan", "tidal_materialize_attach", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
     "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_lora_apply_workspace_bytes", "tidal_lora_apply", "tidal_lora_apply_multi",
-    "tidal_lora_apply_static", "tidal_lora_apply_static_max_tokens",
+    "tidal_lora_apply_static", "tidal_lora_apply_static_max_tokens", "tidal_lora_launch_info",
     "tidal_fork_required_bytes", "tidal_fork_create",
     "tidal_fork_apply", "tidal_fork_slot_ptr", "tidal_fork_destroy", "tidal_template_slot_ptr",
     "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
-    "tidal_convert_device", "tidal_h2d_peak", "tidal_get_stats",
+    "tidal_convert_device", "tidal_h2d_peak", "tidal_hbm_rmw_peak", "tidal_get_stats",
     "tidal_reset_stats", "tidal_template_sync", "tidal_template_destroy", "tidal_last_error",
 ]
 
@@ -65,6 +66,12 @@ class tidal_copy_piece(Structure):
     _fields_ = [("chunk", c_int32), ("slot", c_int32), ("elem_offset", c_int64), ("elems", c_int64),
                 ("src_bytes", c_int64), ("staging_offset", c_int64), ("gathered", c_int32),
                 ("reserved", c_int32)]
+
+
+class tidal_lora_launch(Structure):
+    _fields_ = [("kernel", ctypes.c_char * 64), ("launches", c_int32), ("targets_per_launch", c_int32),
+                ("rank_padded_old", c_int32), ("rank_padded_new", c_int32), ("blocks_per_walk", c_int32),
+                ("waves_per_simd", c_int32), ("workgroups", c_int64)]
 
 
 class tidal_stats(Structure):
@@ -113,6 +120,7 @@ def lib() -> ctypes.CDLL:
     for name in ("tidal_lora_attach", "tidal_lora_swap"):
         getattr(L, name).argtypes = [vp, POINTER(tidal_lora_target), c_int32, vp]
     L.tidal_lora_detach.argtypes = [vp, vp]
+    L.tidal_lora_launch_info.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, c_int32, c_int32, POINTER(tidal_lora_launch)]
     L.tidal_adapter_required_bytes.restype = c_size_t
     L.tidal_adapter_required_bytes.argtypes = [vp, POINTER(tidal_lora_target), c_int32]
     L.tidal_adapter_upload.argtypes = [vp, POINTER(tidal_lora_target), c_int32, vp, c_size_t, vp, POINTER(vp)]
@@ -143,6 +151,7 @@ def lib() -> ctypes.CDLL:
     L.tidal_slot_checksum.argtypes = [vp, c_int32, c_int32, vp, vp]
     L.tidal_convert_device.argtypes = [vp, vp, c_int32, c_int64, vp]
     L.tidal_h2d_peak.argtypes = [vp, c_size_t, c_int32, vp, POINTER(c_double)]
+    L.tidal_hbm_rmw_peak.argtypes = [vp, c_int64, c_int64, c_int64, c_int32, c_int32, vp, POINTER(c_double)]
     L.tidal_get_stats.argtypes = [vp, POINTER(tidal_stats)]
     L.tidal_reset_stats.argtypes = [vp]
     L.tidal_template_sync.argtypes = [vp]
@@ -300,6 +309,14 @@ def tidal_lora_detach(t, stream=None) -> None:
     _check(lib().tidal_lora_detach(t, stream_ptr(stream)))
 
 
+def tidal_lora_launch_info(t, out: int, inn: int, n_targets: int, r_old: int, r_new: int, fork: bool = False) -> dict:
+    info = tidal_lora_launch()
+    _check(lib().tidal_lora_launch_info(t, out, inn, n_targets, r_old, r_new, int(fork), byref(info)))
+    d = {k: getattr(info, k) for k, _ in tidal_lora_launch._fields_}
+    d["kernel"] = d["kernel"].decode()
+    return d
+
+
 def tidal_adapter_required_bytes(t, targets) -> int:
     arr, n = _target_array(targets)
     return lib().tidal_adapter_required_bytes(t, arr, n)
@@ -438,6 +455,12 @@ def tidal_convert_device(dst, src, dtype: int, n: int, stream=None) -> None:
 def tidal_h2d_peak(dev, nbytes: int, reps: int = 5, stream=None) -> float:
     out = c_double()
     _check(lib().tidal_h2d_peak(device_ptr(dev), nbytes, reps, stream_ptr(stream), byref(out)))
+    return out.value
+
+
+def tidal_hbm_rmw_peak(dev, rows: int, cols: int, n: int, blocks_per_walk: int = 4, reps: int = 4, stream=None) -> float:
+    out = c_double()
+    _check(lib().tidal_hbm_rmw_peak(device_ptr(dev), rows, cols, n, blocks_per_walk, reps, stream_ptr(stream), byref(out)))
     return out.value
 
 

@@ -1,6 +1,10 @@
 """Build libtidal.so (HIP, gfx950 only) in-tree with hipcc.
 
-    python -m paper_2503_06421_amd.build [--force]
+    python -m paper_2503_06421_amd.build [--force] [--tuning]
+
+--tuning builds a second library, libtidal_tuning.so, that reads walk lengths and kernel variants
+from TIDAL_MFMA_* / TIDAL_APPLY_* environment variables (sweeps); the default library ignores the
+environment.
 
 hipcc cross-compiles without a GPU.  Objects go to paper_2503_06421_amd/_build/ (ignored by
 git), the library next to this file so that it travels with the source tree.
@@ -39,17 +43,15 @@ def _stale(target: str, deps) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-# TIDAL_TUNING_KNOBS=1 in the environment of the build: the library then reads TIDAL_MFMA_* /
-# TIDAL_APPLY_* from the environment at run time (sweeps); use --force when switching.
-if os.environ.get("TIDAL_TUNING_KNOBS", "0") not in ("", "0"):
-    FLAGS.append("-DTIDAL_TUNING_KNOBS")
+TUNING_LIB = os.path.join(HERE, "libtidal_tuning.so")
 
 
-def _compile(src: str, force: bool) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, force: bool, tuning: bool = False) -> str:
+    obj = os.path.join(OBJ + ("_tuning" if tuning else ""), os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
     if force or _stale(obj, [path, *HEADERS]):
-        cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", path, "-o", obj]
+        extra = ["-DTIDAL_TUNING_KNOBS"] if tuning else []
+        cmd = ["hipcc", *FLAGS, *extra, *EXTRA_FLAGS.get(src, []), "-c", path, "-o", obj]
         p = subprocess.run(cmd, capture_output=True, text=True)
         # the host pass does not know the gfx feature name and says so; that is expected
         err = "\n".join(l for l in p.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -60,10 +62,11 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(force: bool = False, verbose: bool = False, tuning: bool = False) -> str:
+    LIB = TUNING_LIB if tuning else globals()["LIB"]
+    os.makedirs(OBJ + ("_tuning" if tuning else ""), exist_ok=True)
     with ThreadPoolExecutor(max_workers=7) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
+        objs = list(ex.map(lambda s: _compile(s, force, tuning), SOURCES))
     if force or _stale(LIB, objs):
         tmp = LIB + ".tmp%d" % os.getpid()
         cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", tmp, *objs]
@@ -77,4 +80,4 @@ def build(force: bool = False, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    build(force="--force" in sys.argv, verbose=True)
+    build(force="--force" in sys.argv, verbose=True, tuning="--tuning" in sys.argv)

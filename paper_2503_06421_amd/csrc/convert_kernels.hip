@@ -154,29 +154,37 @@ hipError_t launch_copy_from_host(const CopyBatch& batch, int nrun, hipStream_t s
 // ---------------------------------------------------------------------------
 // Packing of LoRA factors.  Host layout: A is r x in, B is out x r, row-major, any of the
 // three dtypes.  Device layout read by the merge kernels, rp = r rounded up to 16:
-//   At : in  x rp bf16, At[j][k] = bf16(A[k][j]), zero for k >= r   (A transposed)
-//   Bp : out x rp bf16, Bp[i][k] = bf16(B[i][k]), zero for k >= r
+//   At : A transposed, ranks zero padded to rp: 16-byte groups of 8 consecutive ranks of one column
+//   Bp : B, ranks zero padded to rp: 16-byte groups of 8 consecutive ranks of one row
 // so that a lane fetches the 8 consecutive k it needs for one column (or row) with a single
-// 16-byte load.  One lane produces one such 16-byte group.
+// 16-byte load; the groups are stored in the order the matrix-core operands take them (256 columns
+// or 32 rows per block, padding filled with zeros), so that a wave's load is one contiguous
+// kilobyte.  One lane produces one such 16-byte group.
 // ---------------------------------------------------------------------------
+__host__ __device__ inline int64_t pack_lines_padded(const PackSegment& seg) {
+    return seg.layout == kPackAt ? (seg.lines + 255) / 256 * 256 : (seg.layout == kPackBp ? (seg.lines + 31) / 32 * 32 : seg.lines);
+}
+
 __global__ __launch_bounds__(256) void pack_adapter_kernel(PackBatch batch) {
     const PackSegment seg = batch.seg[blockIdx.y];
-    const int groups_per_line = seg.rp >> 3;                 // 16-byte groups per packed row
-    const int64_t ngroups = seg.lines * groups_per_line;
+    const int groups_per_line = seg.rp >> 3;                 // 16-byte groups per packed line
+    const int KS = seg.rp >> 4;
+    const int64_t lines_pad = pack_lines_padded(seg);
+    const int64_t ngroups = lines_pad * groups_per_line;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < ngroups; g += stride) {
         // consecutive lanes take consecutive lines so that the strided reads of a transposed
         // A are coalesced along j
-        const int64_t line = g % seg.lines;
-        const int kg = (int)(g / seg.lines);
+        const int64_t line = g % lines_pad;
+        const int kg = (int)(g / lines_pad);
         uint32_t v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int k = kg * 8 + e;
             uint32_t b = 0;
-            if (k < seg.r) {
-                // A: element (k, line) of an r x lines matrix; B: element (line, k) of lines x r
-                const int64_t idx = seg.transposed ? (int64_t)k * seg.lines + line : line * seg.r + k;
+            if (k < seg.r && line < seg.lines) {             // padding lines and ranks are zeros
+                // A: element (k, line) of an r x lines matrix; B (and plain rows): element (line, k) of lines x r
+                const int64_t idx = seg.layout == kPackAt ? (int64_t)k * seg.lines + line : line * seg.r + k;
                 b = narrow1(seg.src, seg.dtype, idx);
             }
             v[e] = b;
@@ -186,7 +194,12 @@ __global__ __launch_bounds__(256) void pack_adapter_kernel(PackBatch batch) {
         o.y = pack2(v[2], v[3]);
         o.z = pack2(v[4], v[5]);
         o.w = pack2(v[6], v[7]);
-        ((u32x4*)seg.dst)[line * groups_per_line + kg] = o;
+        // where the group of line `line`, ranks 8*kg .. 8*kg+7 lives (operand order: see lora_device.h)
+        int64_t at;
+        if (seg.layout == kPackAt) at = (((line >> 8) * 8 + (line & 7)) * KS + (kg >> 1)) * 64 + (kg & 1) * 32 + ((line & 255) >> 3);
+        else if (seg.layout == kPackBp) at = ((line >> 5) * KS + (kg >> 1)) * 64 + (kg & 1) * 32 + (line & 31);
+        else at = line * groups_per_line + kg;
+        ((u32x4*)seg.dst)[at] = o;
     }
 }
 
@@ -194,7 +207,8 @@ hipError_t launch_pack(const PackBatch& batch, int nseg, hipStream_t stream) {
     if (nseg <= 0) return hipSuccess;
     int64_t max_groups = 0;
     for (int i = 0; i < nseg; ++i) {
-        int64_t g = batch.seg[i].lines * (batch.seg[i].rp >> 3);
+        if (batch.seg[i].layout != kPackRows && (batch.seg[i].rp & 15)) return hipErrorInvalidValue;
+        int64_t g = pack_lines_padded(batch.seg[i]) * (batch.seg[i].rp >> 3);
         max_groups = g > max_groups ? g : max_groups;
     }
     int64_t blocks = (max_groups + 255) / 256;
@@ -248,6 +262,59 @@ hipError_t launch_slot_checksum(const void* slot, int64_t elems, int passes, voi
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(slot_checksum_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint16_t*)slot,
                        elems, passes, (unsigned long long*)dev_sum);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Bare in-place read-modify-write probe: the LoRA kernels' tiling with the arithmetic taken out
+// ---------------------------------------------------------------------------------------
+// n matrices of rows x cols 16-bit elements, back to back.  A wave owns a strip of 256 columns and
+// walks down rc blocks of 32 rows; per block a lane loads 16 rows x 16 bytes (non-temporal), flips
+// one bit of every word and stores them back: the memory traffic of a LoRA pass (4 bytes per
+// element) and nothing else.  What this runs at is the ceiling of the in-place pass for that
+// row pitch and walk length.  rows % 32 == 0 and cols % 256 == 0 (checked by the launcher).
+__global__ __launch_bounds__(256) void rmw_probe_kernel(uint16_t* base, int rows, int cols, int strips, int rowblocks,
+                                                        int rc, long long total_items) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long per_xcd = gridDim.x >> 3;
+    const long long L = (long long)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    long long item = L * 4 + wave;
+    if (item >= total_items) return;
+    const int rowchunks = (rowblocks + rc - 1) / rc;
+    const long long per_mat = (long long)strips * rowchunks;
+    const long long mat = item / per_mat;
+    item -= mat * per_mat;
+    const int rowchunk = (int)(item / strips), strip = (int)(item - (long long)rowchunk * strips);
+    uint16_t* W = base + mat * (long long)rows * cols;
+    const int rb_end = (rowchunk + 1) * rc < rowblocks ? (rowchunk + 1) * rc : rowblocks;
+    const int n = lane & 31, h = lane >> 5;
+    for (int rb = rowchunk * rc; rb < rb_end; ++rb) {
+        u32x4 w[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            w[v] = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4*)(W + (long long)row * cols + strip * 256 + n * 8));
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) w[v] ^= 1u;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            __builtin_nontemporal_store(w[v], (__attribute__((address_space(1))) u32x4*)(W + (long long)row * cols + strip * 256 + n * 8));
+        }
+    }
+}
+
+hipError_t launch_rmw_probe(void* base, int64_t rows, int64_t cols, int64_t n, int rc, hipStream_t stream) {
+    if (!base || rows <= 0 || cols <= 0 || n <= 0 || rc < 1) return hipErrorInvalidValue;
+    if (rows % 32 || cols % 256 || rows > 0x7FFFFFFF || cols > 0x7FFFFFFF || (uintptr_t)base % 16) return hipErrorInvalidValue;
+    const int strips = (int)(cols / 256), rowblocks = (int)(rows / 32);
+    const int64_t total = (int64_t)strips * ((rowblocks + rc - 1) / rc) * n;
+    const int64_t blocks = ((total + 3) / 4 + 7) / 8 * 8;
+    if (blocks > 0x7FFFFFF0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rmw_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint16_t*)base, (int)rows, (int)cols,
+                       strips, rowblocks, rc, (long long)total);
     return hipGetLastError();
 }
 

@@ -33,7 +33,7 @@ __device__ __forceinline__ void ordered_delta(const uint16_t* __restrict__ At, c
         for (int c = 0; c < 4; ++c) {
             int j = jl + c;
             j = j < in ? j : in - 1;
-            const u32x4 v = *as_global((const u32x4*)(At + (int64_t)j * RP + kb));
+            const u32x4 v = as_global((const u32x4*)At)[at_group(j, kb >> 4, (kb >> 3) & 1, KS)];
             const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -45,7 +45,7 @@ __device__ __forceinline__ void ordered_delta(const uint16_t* __restrict__ At, c
         for (int v = 0; v < 16; ++v) {
             int row = i0 + 8 * (v >> 2) + 4 * h + (v & 3);
             row = row < out ? row : out - 1;
-            const u32x4 bv = *as_global((const u32x4*)(Bp + (int64_t)row * RP + kb));
+            const u32x4 bv = as_global((const u32x4*)Bp)[bp_group(row, kb >> 4, (kb >> 3) & 1, KS)];
             const uint32_t wds[4] = {bv.x, bv.y, bv.z, bv.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -75,9 +75,16 @@ __global__ __launch_bounds__(256) void convert_merge_kernel(const FusedPiece p, 
     if constexpr (ORDERED) {
         ordered_delta<KS>(p.At, p.Bp, p.out, p.in, i0, jl, h, acc);
     } else {
-        bf16x8 bop[NT][KS];
-        load_strip<NT, KS>(p.At, p.in, j0, lane, bop);
-        delta_tile<NT, KS>(p.Bp, p.out, i0, lane, bop, acc);
+        bf16x8 bop[NT][KS], aop[KS];
+        load_strip<NT, KS>(p.At, j0, lane, bop);              // 128-column strips: gathers from the 256-column packing
+        {   // a piece may start at any row, so the 32 rows are not one packed block: gather, clamped to the last row
+            int m = i0 + (lane & 31);
+            m = m < p.out ? m : p.out - 1;
+            const int64_t base = bp_group(m, 0, lane >> 5, KS);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) aop[ks] = as_global((const bf16x8*)p.Bp)[base + 64 * ks];
+        }
+        delta_tile<NT, KS>(aop, bop, acc);
     }
     const int64_t e_end = p.e0 + p.n;
 #pragma unroll

@@ -324,7 +324,18 @@ __device__ __forceinline__ void expand_walk(const ApplyLongBatch& batch, const A
     const int out = sg.out;
     constexpr int NT = 8;
     bf16x8 bop[NT][KS];
-    load_strip<NT, KS>(sg.Bp, out, j0, lane, bop);               // rows of B for the lane's 8 outputs
+    {   // rows of B for the lane's 8 outputs, gathered from the packed (operand-order) B
+        const int n_ = lane & 31, kg = lane >> 5;
+        const TIDAL_GLOBAL bf16x8* g = as_global((const bf16x8*)sg.Bp);
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            int j = j0 + NT * n_ + T;
+            j = j < out ? j : out - 1;                           // ragged strip: clamp, masked at the store
+            const int64_t base = bp_group(j, 0, kg, KS);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bop[T][ks] = g[base + 64 * ks];
+        }
+    }
     const int n = lane & 31, h = lane >> 5;
     const int jl = j0 + NT * n;
     const bool strip_full = j0 + 32 * NT <= out;
@@ -337,7 +348,9 @@ __device__ __forceinline__ void expand_walk(const ApplyLongBatch& batch, const A
         uint32_t w[16][NT / 2];
         load_block<NT>(y, rows, out, 0, jl, h, full, w);
         f32x16 acc[NT];
-        delta_tile<NT, KS>(u, rows, 0, lane, bop, acc);
+        bf16x8 aop[KS];
+        load_rows<KS>(u, rows, 0, lane, aop);
+        delta_tile<NT, KS>(aop, bop, acc);
         apply_tile<NT>(w, acc, sg.s);
         store_block<NT>(y, rows, out, 0, jl, h, full, w);
     }
@@ -395,7 +408,8 @@ __global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyShor
     if (sg.r == 0 || i >= out) return;
     const int rows = sg.rows;                                     // 1 .. kApplyShortRows
     const uint16_t* u = batch.u + ((int64_t)sg.u_tok + sg.t0) * kApplyRankStride;
-    const uint16_t* brow = sg.Bp + (int64_t)i * sg.rp;
+    const TIDAL_GLOBAL u32x4* bgroups = as_global((const u32x4*)sg.Bp);      // packed B: 16-byte groups of 8 ranks
+    const int KS = sg.rp >> 4;
     float acc[kApplyShortRows], yv[kApplyShortRows];
 #pragma unroll
     for (int t = 0; t < kApplyShortRows; ++t) {
@@ -405,7 +419,7 @@ __global__ __launch_bounds__(256) void apply_expand_short_kernel(const ApplyShor
     }
     for (int k0 = 0; k0 < sg.rp; k0 += 8) {
         float b8[8];
-        const u32x4 bv = *as_global((const u32x4*)(brow + k0));
+        const u32x4 bv = bgroups[bp_group(i, k0 >> 4, (k0 >> 3) & 1, KS)];
         unpack8(bv, b8);
 #pragma unroll
         for (int t = 0; t < kApplyShortRows; ++t) {
@@ -466,11 +480,14 @@ __global__ __launch_bounds__(256) void apply_ordered_expand_kernel(const ApplyLo
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)rows * sg.out) return;
     const int t = (int)(idx / sg.out), i = (int)(idx - (int64_t)t * sg.out);
-    const TIDAL_GLOBAL uint16_t* b = as_global(sg.Bp + (int64_t)i * sg.rp);
+    const TIDAL_GLOBAL uint16_t* b = as_global(sg.Bp);
     const TIDAL_GLOBAL uint16_t* u = as_global(batch.u + ((int64_t)sg.u_tok + sg.t0) * kApplyRankStride + (int64_t)t * sg.rp);
+    const int KS = sg.rp >> 4;
     float acc = 0.0f;
-    for (int k = 0; k < sg.r; ++k)
-        acc = __builtin_fmaf(__uint_as_float((uint32_t)b[k] << 16), __uint_as_float((uint32_t)u[k] << 16), acc);
+    for (int k = 0; k < sg.r; ++k) {
+        const uint16_t bk = b[bp_group(i, k >> 4, (k >> 3) & 1, KS) * 8 + (k & 7)];
+        acc = __builtin_fmaf(__uint_as_float((uint32_t)bk << 16), __uint_as_float((uint32_t)u[k] << 16), acc);
+    }
     TIDAL_GLOBAL uint16_t* y = as_global(sg.y + (int64_t)(sg.t0 + t) * sg.out + i);
     const f32x2 r2 = {__builtin_fmaf(sg.s, acc, __uint_as_float((uint32_t)*y << 16)), 0.0f};
     *y = (uint16_t)(__builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2)) & 0xFFFFu);

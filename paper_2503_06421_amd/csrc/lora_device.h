@@ -28,6 +28,30 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+// ---------------------------------------------------------------------------------------
+// Packed factor layouts ("operand order")
+// ---------------------------------------------------------------------------------------
+// The device copy of an adapter keeps A and B as 16-byte groups of 8 consecutive ranks, ordered so
+// that the matrix-core operand a wave needs is one contiguous kilobyte, lane after lane:
+//   At (A transposed, in rounded up to 256 columns, ranks padded to rp = 16*KS with zeros):
+//       group of column j, ranks 16*ks + 8*kg .. +8  at index
+//       (((j / 256) * 8 + j % 8) * KS + ks) * 64 + kg * 32 + (j % 256) / 8
+//     i.e. per strip of 256 columns, per T = j % 8, per ks: the 64 lanes (n = (j % 256) / 8, kg) of
+//     the MFMA B operand of tile T;
+//   Bp (out rounded up to 32 rows): group of row i, same ranks, at
+//       ((i / 32) * KS + ks) * 64 + kg * 32 + i % 32
+//     i.e. per block of 32 rows, per ks: the 64 lanes (m = i % 32, kg) of the MFMA A operand.
+// With plain row-major factors every lane of such a load touched a cache line of its own (64 cache
+// accesses per instruction against 16 for a load of W), and at 64 ranks the factor loads were 60 %
+// of all accesses of the texture-address path, which was busy 88 % of the time: the in-place pass
+// was bound there, not by HBM.  Padding entries hold zeros, so loads need no clamping.
+__host__ __device__ __forceinline__ int64_t at_group(int64_t j, int ks, int kg, int KS) {
+    return (((j >> 8) * 8 + (j & 7)) * KS + ks) * 64 + kg * 32 + ((j & 255) >> 3);
+}
+__host__ __device__ __forceinline__ int64_t bp_group(int64_t i, int ks, int kg, int KS) {
+    return ((i >> 5) * KS + ks) * 64 + kg * 32 + (i & 31);
+}
+
 // Two adjacent bf16 of W (one 32-bit word, low half = lower column) += s * (d_lo, d_hi).
 // The narrowing is v_cvt_pk_bf16_f32: round to nearest even, subnormals kept, NaN quieted with
 // sign and upper payload kept -- bit-identical to the integer formula
@@ -65,35 +89,73 @@ __device__ __forceinline__ typename RowVec<NT>::type pack_words(const uint32_t (
     return v;
 }
 
-// Columns of A (= rows of At) for the lane's NT columns: MFMA B operand, K x N with
-// N index n = lane % 32 and k = 16*ks + 8*(lane / 32) + 0..7.
+// Columns of A for the lane's NT columns: MFMA B operand, K x N with N index n = lane % 32 and
+// k = 16*ks + 8*(lane / 32) + 0..7; the lane's column of tile T is j0 + NT*n + T.  With NT = 8 and
+// j0 a multiple of 256 every load is one contiguous kilobyte.
 template <int NT, int KS>
-__device__ __forceinline__ void load_strip(const uint16_t* __restrict__ At, int in, int j0, int lane,
+__device__ __forceinline__ void load_strip(const uint16_t* __restrict__ At, int j0, int lane,
                                            bf16x8 (&bop)[NT][KS ? KS : 1]) {
+    if constexpr (KS > 0) {
+        const int n = lane & 31, kg = lane >> 5;
+        const TIDAL_GLOBAL bf16x8* g = as_global((const bf16x8*)At);
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            const int64_t base = at_group(j0 + NT * n + T, 0, kg, KS);     // columns past `in` are zero padding
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bop[T][ks] = g[base + 64 * ks];
+        }
+    }
+}
+
+// The same operand from a row-major matrix of `lines` rows x 16*KS bf16 (row j = one column of the
+// operand): the expand step of the unmerged apply, whose strip is rows of B.
+template <int NT, int KS>
+__device__ __forceinline__ void load_strip_rows(const uint16_t* __restrict__ M, int lines, int j0, int lane,
+                                                bf16x8 (&bop)[NT][KS ? KS : 1]) {
     if constexpr (KS > 0) {
         const int n = lane & 31, kg = lane >> 5;
 #pragma unroll
         for (int T = 0; T < NT; ++T) {
             int j = j0 + NT * n + T;
-            j = j < in ? j : in - 1;                       // ragged strip: clamp, masked at the store
-            const uint16_t* p = At + (int64_t)j * (16 * KS) + 8 * kg;
+            j = j < lines ? j : lines - 1;                 // ragged strip: clamp, masked at the store
+            const uint16_t* p = M + (int64_t)j * (16 * KS) + 8 * kg;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) bop[T][ks] = *as_global((const bf16x8*)(p + 16 * ks));
         }
     }
 }
 
-// delta tile for one adapter: acc[T][v] = sum_k B[i0 + row(v)][k] * A[k][j0 + NT*n + T]
-template <int NT, int KS>
-__device__ __forceinline__ void delta_tile(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
-                                           const bf16x8 (&bop)[NT][KS ? KS : 1], f32x16 (&acc)[NT]) {
+// Rows i0 .. i0+31 of B as the MFMA A operand (lane: row lane % 32, ranks 8*(lane / 32) + 0..7 of
+// each 16): one contiguous kilobyte per 16 ranks when i0 is a multiple of 32.
+template <int KS>
+__device__ __forceinline__ void load_b_rows(const uint16_t* __restrict__ Bp, int i0, int lane, bf16x8 (&aop)[KS ? KS : 1]) {
+    if constexpr (KS > 0) {
+        const TIDAL_GLOBAL bf16x8* g = as_global((const bf16x8*)Bp);
+        const int64_t base = bp_group(i0 + (lane & 31), 0, lane >> 5, KS);   // rows past `out` are zero padding
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) aop[ks] = g[base + 64 * ks];
+    }
+}
+
+// The same operand from a row-major matrix of `rows` rows x 16*KS bf16 (the rank-space intermediate
+// of the unmerged apply).
+template <int KS>
+__device__ __forceinline__ void load_rows(const uint16_t* __restrict__ M, int rows, int i0, int lane,
+                                          bf16x8 (&aop)[KS ? KS : 1]) {
     if constexpr (KS > 0) {
         int m = i0 + (lane & 31);
-        m = m < out ? m : out - 1;
-        const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
-        bf16x8 aop[KS];
+        m = m < rows ? m : rows - 1;
+        const uint16_t* p = M + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+    }
+}
+
+// delta tile for one adapter: acc[T][v] = sum_k B[i0 + row(v)][k] * A[k][j0 + NT*n + T]
+template <int NT, int KS>
+__device__ __forceinline__ void delta_tile(const bf16x8 (&aop)[KS ? KS : 1], const bf16x8 (&bop)[NT][KS ? KS : 1],
+                                           f32x16 (&acc)[NT]) {
+    if constexpr (KS > 0) {
 #pragma unroll
         for (int T = 0; T < NT; ++T) {
             f32x16 c = {0};
@@ -117,15 +179,11 @@ __device__ __forceinline__ void apply_tile(uint32_t (&w)[16][NT / 2], const f32x
 // of one 32-bit word of W) and consumed at once, so only 32 accumulator registers are live instead
 // of 16 * NT.  That is what lets two waves share a SIMD for the small ranks.
 template <int NT, int KS>
-__device__ __forceinline__ void delta_apply(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
+__device__ __forceinline__ void delta_apply(const uint16_t* __restrict__ Bp, int i0, int lane,
                                             const bf16x8 (&bop)[NT][KS ? KS : 1], uint32_t (&w)[16][NT / 2], float s) {
     if constexpr (KS > 0) {
-        int m = i0 + (lane & 31);
-        m = m < out ? m : out - 1;
-        const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
         bf16x8 aop[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+        load_b_rows<KS>(Bp, i0, lane, aop);
 #pragma unroll
         for (int q = 0; q < NT / 2; ++q) {
             f32x16 c0 = {0}, c1 = {0};
@@ -198,6 +256,5 @@ __device__ __forceinline__ void store_block(uint16_t* __restrict__ W, int out, i
     }
 }
 
-// FORK: the result goes to a separate destination (old_base + at_old, which are free because a
 }  // namespace tidal
 #endif

@@ -36,9 +36,7 @@ namespace tidal {
 // fork never unmerges: KS0 == 0) and W itself, the template's pristine slot, is only read.
 // PAIR: the delta tiles are produced and consumed two at a time (32 live accumulator registers
 // instead of 128).  Instantiations whose registers then allow two waves per SIMD without spilling
-// (found by compiling) ask for them: A strips of up to 32 ranks in all, and 32 old + 16 new.
-constexpr bool two_waves_fit(int ks0, int ks1) { return ks0 + ks1 <= 2 || (ks0 == 2 && ks1 == 1); }
-
+// ask for them (two_waves_fit).
 template <int NT, int KS0, int KS1, bool FORK = false, bool PAIR = false>
 __global__ __launch_bounds__(256, (PAIR && two_waves_fit(KS0, KS1)) ? 2 : 1) void lora_mfma_kernel(
     const LoraBatch batch, int out, int in, int strips, int rowblocks, int rc, int blocks_per_target, int total_blocks) {
@@ -68,8 +66,8 @@ __global__ __launch_bounds__(256, (PAIR && two_waves_fit(KS0, KS1)) ? 2 : 1) voi
 
     bf16x8 bop0[NT][KS0 ? KS0 : 1];
     bf16x8 bop1[NT][KS1 ? KS1 : 1];
-    load_strip<NT, KS0>(At_old, in, j0, lane, bop0);
-    load_strip<NT, KS1>(At_new, in, j0, lane, bop1);
+    load_strip<NT, KS0>(At_old, j0, lane, bop0);
+    load_strip<NT, KS1>(At_new, j0, lane, bop1);
 
     const int n = lane & 31, h = lane >> 5;
     const int jl = j0 + NT * n;                              // lane's first column
@@ -86,16 +84,20 @@ __global__ __launch_bounds__(256, (PAIR && two_waves_fit(KS0, KS1)) ? 2 : 1) voi
         uint32_t w[16][NT / 2];
         load_block<NT>(W, out, in, i0, jl, h, full, w);
         if constexpr (PAIR) {
-            delta_apply<NT, KS0>(Bp_old, out, i0, lane, bop0, w, d.s_old);
-            delta_apply<NT, KS1>(Bp_new, out, i0, lane, bop1, w, d.s_new);
+            delta_apply<NT, KS0>(Bp_old, i0, lane, bop0, w, d.s_old);
+            delta_apply<NT, KS1>(Bp_new, i0, lane, bop1, w, d.s_new);
         } else {
             f32x16 acc[NT];
             if constexpr (KS0 > 0) {
-                delta_tile<NT, KS0>(Bp_old, out, i0, lane, bop0, acc);
+                bf16x8 aop[KS0];
+                load_b_rows<KS0>(Bp_old, i0, lane, aop);
+                delta_tile<NT, KS0>(aop, bop0, acc);
                 apply_tile<NT>(w, acc, d.s_old);
             }
             if constexpr (KS1 > 0) {
-                delta_tile<NT, KS1>(Bp_new, out, i0, lane, bop1, acc);
+                bf16x8 aop[KS1];
+                load_b_rows<KS1>(Bp_new, i0, lane, aop);
+                delta_tile<NT, KS1>(aop, bop1, acc);
                 apply_tile<NT>(w, acc, d.s_new);
             }
         }
@@ -104,97 +106,53 @@ __global__ __launch_bounds__(256, (PAIR && two_waves_fit(KS0, KS1)) ? 2 : 1) voi
     }
 }
 
-template <int NT, int KS0, int KS1, bool FORK = false, bool PAIR = false>
-static hipError_t launch_mfma_inst(const LoraGroup& g, hipStream_t stream) {
-    const int strips = (g.in + 32 * NT - 1) / (32 * NT);
-    const int rowblocks = (g.out + 31) / 32;
-    // 32-row blocks per wave.  Short walks keep waves short-lived, which this memory system
-    // rewards, long walks amortise the A strip, which grows with the rank; small jobs get fewer so
-    // that every CU has work.  Measured per instantiation on 64 x 4096^2 and 40 x 5120^2: merges of
-    // up to 32 ranks and swaps where two waves share a SIMD want 4 blocks, a 64-rank merge 8, every
-    // other swap 16; on row pitches that are no power of two the short walks gain more, so the 4 and
-    // the 8 of the swaps and the 64-rank merge are halved.  (A 16-rank merge looks 2-3 % faster at 2
-    // blocks in a sweep where all slots share one adapter; with an adapter per slot, as in the
-    // 70B-shaped stack, it is 1 % slower: the A strips then come from HBM, not from L2.)
-    const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
-    int rc;
-    if (PAIR) {
-        rc = two_waves_fit(KS0, KS1) ? 4 : ((KS0 == 0 || KS1 == 0) ? 8 : 16);
-        if ((g.in & (g.in - 1)) != 0 && rc <= 8) rc /= 2;
-    } else {
-        rc = 4;                      // merges of up to 32 ranks
-    }
-    const int64_t by_size = tiles / 4096;
-    if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
-    if (const char* e = tuning_knob("TIDAL_MFMA_RC")) {        // tuning builds only
-        const int v = atoi(e);
-        if (v >= 1 && v <= 1024) rc = v;
-    }
-    const int rowchunks = (rowblocks + rc - 1) / rc;
-    const int blocks_per_target = (strips * rowchunks + 3) / 4;
-    const int64_t total = (int64_t)blocks_per_target * g.n_targets;
-    if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
-    const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((lora_mfma_kernel<NT, KS0, KS1, FORK, PAIR>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
-                       g.in, strips, rowblocks, rc, blocks_per_target, (int)total);
+// Launch of one instantiation with the walk length and grid the plan gives.
+template <int KS0, int KS1, bool FORK, bool PAIR>
+static hipError_t launch_inst(const LoraGroup& g, const LoraLaunchPlan& p, hipStream_t stream) {
+    if (p.total_blocks <= 0 || p.total_blocks > 0x7FFFFFF0) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((p.total_blocks + 7) / 8 * 8);
+    hipLaunchKernelGGL((lora_mfma_kernel<8, KS0, KS1, FORK, PAIR>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
+                       g.in, p.strips, p.rowblocks, p.rc, p.blocks_per_target, (int)p.total_blocks);
     return hipGetLastError();
 }
 
-// A strips stay in registers except in swaps with a 64-rank side: there they are staged in LDS by
-// a kernel built in its own translation unit (measured on 128 x 4096^2, LDS against registers:
-// 64 -> 64 6.4 against 5.9 TB/s, 16/32 -> 64 6.5 against 6.1-6.25, 64 -> 16/32 6.5 against 6.1-6.2;
-// merges of 64 ranks run at 6.5 either way and stay here).
-hipError_t launch_lora_mfma_lds(const LoraGroup& g, hipStream_t stream);
-bool lora_mfma_lds_available(int rp_old, int rp_new);
-
-template <int NT, int KS0, int KS1>
-static hipError_t launch_mfma_pick(const LoraGroup& g, hipStream_t stream, int use_lds) {
+template <int KS0, int KS1>
+static hipError_t launch_variant(const LoraGroup& g, const LoraLaunchPlan& p, hipStream_t stream) {
     if constexpr (KS0 + KS1 == 0) {
         return hipSuccess;
     } else {
-        int pair = (KS0 > 0 && KS1 > 0) || KS0 + KS1 >= 4;
-        if (const char* e = tuning_knob("TIDAL_MFMA_PAIR")) pair = atoi(e) != 0;       // tuning builds only
-        if constexpr (KS0 == 0) {
-            if (g.fork) return pair ? launch_mfma_inst<NT, 0, KS1, true, true>(g, stream) : launch_mfma_inst<NT, 0, KS1, true>(g, stream);
+        if (p.fork) {
+            if constexpr (KS0 == 0)
+                return p.pair ? launch_inst<0, KS1, true, true>(g, p, stream) : launch_inst<0, KS1, true, false>(g, p, stream);
+            else
+                return hipErrorInvalidValue;
         }
-        if (g.fork) return hipErrorInvalidValue;
-        if (use_lds < 0) use_lds = (KS0 > 0 && KS1 > 0 && (KS0 == 4 || KS1 == 4)) ? 1 : 0;
-        if (use_lds && NT == 8 && lora_mfma_lds_available(16 * KS0, 16 * KS1)) return launch_lora_mfma_lds(g, stream);
-        return pair ? launch_mfma_inst<NT, KS0, KS1, false, true>(g, stream) : launch_mfma_inst<NT, KS0, KS1>(g, stream);
+        return p.pair ? launch_inst<KS0, KS1, false, true>(g, p, stream) : launch_inst<KS0, KS1, false, false>(g, p, stream);
     }
 }
 
-template <int NT, int KS0>
-static hipError_t launch_mfma_new(const LoraGroup& g, hipStream_t stream, int use_lds) {
-    switch (g.rp_new) {
-        case 0: return launch_mfma_pick<NT, KS0, 0>(g, stream, use_lds);
-        case 16: return launch_mfma_pick<NT, KS0, 1>(g, stream, use_lds);
-        case 32: return launch_mfma_pick<NT, KS0, 2>(g, stream, use_lds);
-        case 64: return launch_mfma_pick<NT, KS0, 4>(g, stream, use_lds);
+template <int KS0>
+static hipError_t launch_new(const LoraGroup& g, const LoraLaunchPlan& p, hipStream_t stream) {
+    switch (p.ks_new) {
+        case 0: return launch_variant<KS0, 0>(g, p, stream);
+        case 1: return launch_variant<KS0, 1>(g, p, stream);
+        case 2: return launch_variant<KS0, 2>(g, p, stream);
+        case 4: return launch_variant<KS0, 4>(g, p, stream);
     }
     return hipErrorInvalidValue;
 }
 
-template <int NT>
-static hipError_t launch_mfma_old(const LoraGroup& g, hipStream_t stream, int use_lds) {
-    switch (g.rp_old) {
-        case 0: return launch_mfma_new<NT, 0>(g, stream, use_lds);
-        case 16: return launch_mfma_new<NT, 1>(g, stream, use_lds);
-        case 32: return launch_mfma_new<NT, 2>(g, stream, use_lds);
-        case 64: return launch_mfma_new<NT, 4>(g, stream, use_lds);
+hipError_t launch_lora_mfma(const LoraGroup& g, const LoraLaunchPlan& p, hipStream_t stream) {
+    if (p.kind == kLoraNone) return hipSuccess;
+    if (p.kind == kLoraMfmaLds) return launch_lora_mfma_lds(g, p, stream);
+    if (p.kind != kLoraMfmaReg) return hipErrorInvalidValue;
+    switch (p.ks_old) {
+        case 0: return launch_new<0>(g, p, stream);
+        case 1: return launch_new<1>(g, p, stream);
+        case 2: return launch_new<2>(g, p, stream);
+        case 4: return launch_new<4>(g, p, stream);
     }
     return hipErrorInvalidValue;
-}
-
-hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream) {
-    if (g.n_targets <= 0 || g.out <= 0 || g.in <= 0) return hipSuccess;
-    const char* e_lds = tuning_knob("TIDAL_MFMA_LDS");      // tuning builds only
-    const int use_lds = e_lds ? atoi(e_lds) : -1;
-#ifdef TIDAL_TUNING_KNOBS
-    const char* e_nt = tuning_knob("TIDAL_MFMA_NT");        // strips of 128 columns: measured 5-10 % slower
-    if (e_nt && atoi(e_nt) == 4) return launch_mfma_old<4>(g, stream, use_lds);
-#endif
-    return launch_mfma_old<8>(g, stream, use_lds);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -209,13 +167,12 @@ __device__ __forceinline__ void stage_rank_tiles(const uint16_t* __restrict__ At
                                                  int rp, int out, int in, int i0, int j0, int k0,
                                                  float* Atile, float* Btile) {
     const int tid = threadIdx.x;
-    {   // 256 columns x 16 ranks: one column per thread, two 16-byte loads
-        int j = j0 + tid;
-        j = j < in ? j : in - 1;
-        const TIDAL_GLOBAL u32x4* p = as_global((const u32x4*)(At + (int64_t)j * rp + k0));
+    const int KS = rp >> 4, ks = k0 >> 4;
+    {   // 256 columns x 16 ranks: one column per thread, two 16-byte groups (columns past `in` are zero padding)
+        const TIDAL_GLOBAL u32x4* g = as_global((const u32x4*)At);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            u32x4 x = p[q];
+            u32x4 x = g[at_group(j0 + tid, ks, q, KS)];
             const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -224,11 +181,11 @@ __device__ __forceinline__ void stage_rank_tiles(const uint16_t* __restrict__ At
             }
         }
     }
-    if (tid < 128) {   // 64 rows x 16 ranks: one 16-byte load per thread
+    if (tid < 128) {   // 64 rows x 16 ranks: one 16-byte group per thread
         const int row = tid & 63, q = tid >> 6;
         int i = i0 + row;
         i = i < out ? i : out - 1;
-        u32x4 x = *as_global((const u32x4*)(Bp + (int64_t)i * rp + k0 + 8 * q));
+        u32x4 x = as_global((const u32x4*)Bp)[bp_group(i, ks, q, KS)];
         const uint32_t wds[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {

@@ -17,19 +17,17 @@ namespace tidal {
 template <int NT, int KS>
 __device__ __forceinline__ void delta_tile_lds(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
                                                const bf16x8* strip, f32x16 (&acc)[NT]) {
-    int m = i0 + (lane & 31);
-    m = m < out ? m : out - 1;
-    const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
-    bf16x8 aop[KS];
+    if constexpr (KS > 0) {
+        bf16x8 aop[KS];
+        load_b_rows<KS>(Bp, i0, lane, aop);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+        for (int T = 0; T < NT; ++T) {
+            f32x16 c = {0};
 #pragma unroll
-    for (int T = 0; T < NT; ++T) {
-        f32x16 c = {0};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[(T * KS + ks) * 64 + lane], c, 0, 0, 0);
-        acc[T] = c;
+            for (int ks = 0; ks < KS; ++ks)
+                c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[(T * KS + ks) * 64 + lane], c, 0, 0, 0);
+            acc[T] = c;
+        }
     }
 }
 
@@ -37,51 +35,48 @@ __device__ __forceinline__ void delta_tile_lds(const uint16_t* __restrict__ Bp, 
 template <int NT, int KS>
 __device__ __forceinline__ void delta_apply_lds(const uint16_t* __restrict__ Bp, int out, int i0, int lane,
                                                 const bf16x8* strip, uint32_t (&w)[16][NT / 2], float s) {
-    int m = i0 + (lane & 31);
-    m = m < out ? m : out - 1;
-    const uint16_t* p = Bp + (int64_t)m * (16 * KS) + 8 * (lane >> 5);
-    bf16x8 aop[KS];
+    if constexpr (KS > 0) {
+        bf16x8 aop[KS];
+        load_b_rows<KS>(Bp, i0, lane, aop);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) aop[ks] = *as_global((const bf16x8*)(p + 16 * ks));
+        for (int q = 0; q < NT / 2; ++q) {
+            f32x16 c0 = {0}, c1 = {0};
 #pragma unroll
-    for (int q = 0; q < NT / 2; ++q) {
-        f32x16 c0 = {0}, c1 = {0};
+            for (int ks = 0; ks < KS; ++ks) {
+                c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[((2 * q) * KS + ks) * 64 + lane], c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[((2 * q + 1) * KS + ks) * 64 + lane], c1, 0, 0, 0);
+            }
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[((2 * q) * KS + ks) * 64 + lane], c0, 0, 0, 0);
-            c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], strip[((2 * q + 1) * KS + ks) * 64 + lane], c1, 0, 0, 0);
+            for (int v = 0; v < 16; ++v) w[v][q] = rmw2(w[v][q], c0[v], c1[v], s);
         }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) w[v][q] = rmw2(w[v][q], c0[v], c1[v], s);
     }
 }
 
+// The packed A of a strip is already in MFMA operand order: staging it is a linear copy of
+// NT * KS kilobytes, one per (tile, 16 ranks).
 template <int NT, int KS>
-__device__ __forceinline__ void stage_strip(const uint16_t* __restrict__ At, int in, int j0, int lane, int wave,
-                                            bf16x8* strip) {
-    const int n = lane & 31, kg = lane >> 5;
-    for (int p = wave; p < NT * KS; p += 4) {
-        const int T = p / KS, ks = p - T * KS;
-        int j = j0 + NT * n + T;
-        j = j < in ? j : in - 1;
-        strip[p * 64 + lane] = *as_global((const bf16x8*)(At + (int64_t)j * (16 * KS) + 16 * ks + 8 * kg));
-    }
+__device__ __forceinline__ void stage_strip(const uint16_t* __restrict__ At, int j0, int lane, int wave, bf16x8* strip) {
+    const TIDAL_GLOBAL bf16x8* g = as_global((const bf16x8*)At) + (int64_t)(j0 >> 8) * (8 * KS * 64);
+    for (int p = wave; p < NT * KS; p += 4) strip[p * 64 + lane] = g[p * 64 + lane];
 }
 
 template <int NT, int KS0, int KS1>
 __global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraBatch batch, int out,
                                                             int in, int strips, int rowblocks, int rcb,
-                                                            int blocks_per_target, int total_blocks) {
+                                                            int blocks_per_target, int total_blocks, int order) {
     __shared__ bf16x8 strip_lds[(KS0 + KS1) * NT * 64];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // order bit 1: no XCD remap (neighbouring workgroups land on different XCDs); bit 0: walk a
+    // slot strip by strip (neighbouring workgroups share an A strip) instead of row chunk by row chunk
     const int per_xcd = gridDim.x >> 3;
-    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    const int L = (order & 2) ? (int)blockIdx.x : (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (L >= total_blocks) return;                        // whole workgroup leaves together
     const int target = L / blocks_per_target;
     const int item = L - target * blocks_per_target;
-    const int rowchunk = item / strips;
-    const int strip = item - rowchunk * strips;
+    const int rowchunks = blocks_per_target / strips;
+    const int rowchunk = (order & 1) ? item % rowchunks : item / strips;
+    const int strip = (order & 1) ? item / rowchunks : item - rowchunk * strips;
     const int j0 = strip * (32 * NT);
 
     const LoraTargetDev d = batch.t[target];
@@ -90,8 +85,8 @@ __global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraBatch batc
     const uint16_t* Bp_old = (const uint16_t*)(batch.old_base + (size_t)d.bp_old * kLoraUnit);
     const uint16_t* At_new = (const uint16_t*)(batch.new_base + (size_t)d.at_new * kLoraUnit);
     const uint16_t* Bp_new = (const uint16_t*)(batch.new_base + (size_t)d.bp_new * kLoraUnit);
-    if constexpr (KS0 > 0) stage_strip<NT, KS0>(At_old, in, j0, lane, wave, strip_lds);
-    if constexpr (KS1 > 0) stage_strip<NT, KS1>(At_new, in, j0, lane, wave, strip_lds + KS0 * NT * 64);
+    if constexpr (KS0 > 0) stage_strip<NT, KS0>(At_old, j0, lane, wave, strip_lds);
+    if constexpr (KS1 > 0) stage_strip<NT, KS1>(At_new, j0, lane, wave, strip_lds + KS0 * NT * 64);
     __syncthreads();
 
     const int n = lane & 31, h = lane >> 5;
@@ -111,51 +106,47 @@ __global__ __launch_bounds__(256) void lora_mfma_lds_kernel(const LoraBatch batc
         } else {
             f32x16 acc[NT];
             delta_tile_lds<NT, KS0>(Bp_old, out, i0, lane, strip_lds, acc);
-            apply_tile<NT>(w, acc, d.s_old);
+            if constexpr (KS0 > 0) apply_tile<NT>(w, acc, d.s_old);
             delta_tile_lds<NT, KS1>(Bp_new, out, i0, lane, strip_lds + KS0 * NT * 64, acc);
-            apply_tile<NT>(w, acc, d.s_new);
+            if constexpr (KS1 > 0) apply_tile<NT>(w, acc, d.s_new);
         }
         store_block<NT>(W, out, in, i0, jl, h, full, w);
     }
 }
 
-template <int NT, int KS0, int KS1>
-static hipError_t launch_mfma_lds_inst(const LoraGroup& g, hipStream_t stream) {
-    const int strips = (g.in + 32 * NT - 1) / (32 * NT);
-    const int rowblocks = (g.out + 31) / 32;
-    const int64_t tiles = (int64_t)strips * rowblocks * g.n_targets;
-    // 32-row blocks per wave (measured, 64 and 128 slots of 4096^2, 40 of 5120^2 and 15 of the two
-    // 13824-wide shapes): 16 for 64 -> 64, else 8; 4 and 2 where the row pitch is no power of two
-    const bool pow2_pitch = (g.in & (g.in - 1)) == 0;
-    int rc = (KS0 + KS1 >= 8) ? (pow2_pitch ? 16 : 4) : (pow2_pitch ? 8 : 2);
-    const int64_t by_size = tiles / 4096;
-    if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
-    if (const char* e = tuning_knob("TIDAL_MFMA_RC")) {   // tuning builds only
-        const int v = atoi(e);
-        if (v >= 1 && v <= 1024) rc = v;
+template <int KS0, int KS1>
+static hipError_t launch_lds_inst(const LoraGroup& g, const LoraLaunchPlan& p, hipStream_t stream) {
+    if (p.total_blocks <= 0 || p.total_blocks > 0x7FFFFFF0) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((p.total_blocks + 7) / 8 * 8);
+    const TuningKnobs knobs = tuning_knobs();              // all -1 outside tuning builds
+    const int order = knobs.mfma_order > 0 ? knobs.mfma_order : 0;
+    unsigned dyn = 0;
+    if (knobs.mfma_dynlds > 0) {
+        dyn = (unsigned)knobs.mfma_dynlds;
+        hipError_t e = hipFuncSetAttribute((const void*)lora_mfma_lds_kernel<8, KS0, KS1>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+        if (e != hipSuccess) return e;
     }
-    const int rcb = 4 * rc;
-    const int rowchunks = (rowblocks + rcb - 1) / rcb;
-    const int blocks_per_target = strips * rowchunks;
-    const int64_t total = (int64_t)blocks_per_target * g.n_targets;
-    if (total > 0x7FFFFFF0) return hipErrorInvalidValue;
-    const unsigned grid = (unsigned)((total + 7) / 8 * 8);
-    hipLaunchKernelGGL((lora_mfma_lds_kernel<NT, KS0, KS1>), dim3(grid), dim3(256), 0, stream, *g.batch, g.out,
-                       g.in, strips, rowblocks, rcb, blocks_per_target, (int)total);
+    hipLaunchKernelGGL((lora_mfma_lds_kernel<8, KS0, KS1>), dim3(grid), dim3(256), dyn, stream, *g.batch, g.out, g.in,
+                       p.strips, p.rowblocks, 4 * p.rc, p.blocks_per_target, (int)p.total_blocks, order);
     return hipGetLastError();
 }
 
-
-bool lora_mfma_lds_available(int rp_old, int rp_new) {
-    return (rp_old == 64 && rp_new >= 16) || (rp_new == 64 && rp_old >= 16);
-}
-
-hipError_t launch_lora_mfma_lds(const LoraGroup& g, hipStream_t stream) {
-    if (g.rp_old == 64 && g.rp_new == 64) return launch_mfma_lds_inst<8, 4, 4>(g, stream);
-    if (g.rp_old == 64 && g.rp_new == 32) return launch_mfma_lds_inst<8, 4, 2>(g, stream);
-    if (g.rp_old == 64 && g.rp_new == 16) return launch_mfma_lds_inst<8, 4, 1>(g, stream);
-    if (g.rp_old == 32 && g.rp_new == 64) return launch_mfma_lds_inst<8, 2, 4>(g, stream);
-    if (g.rp_old == 16 && g.rp_new == 64) return launch_mfma_lds_inst<8, 1, 4>(g, stream);
+hipError_t launch_lora_mfma_lds(const LoraGroup& g, const LoraLaunchPlan& p, hipStream_t stream) {
+    if (p.kind != kLoraMfmaLds || p.fork) return hipErrorInvalidValue;
+    switch (p.ks_old * 8 + p.ks_new) {
+        case 4 * 8 + 4: return launch_lds_inst<4, 4>(g, p, stream);
+        case 4 * 8 + 2: return launch_lds_inst<4, 2>(g, p, stream);
+        case 4 * 8 + 1: return launch_lds_inst<4, 1>(g, p, stream);
+        case 2 * 8 + 4: return launch_lds_inst<2, 4>(g, p, stream);
+        case 1 * 8 + 4: return launch_lds_inst<1, 4>(g, p, stream);
+        case 0 * 8 + 4: return launch_lds_inst<0, 4>(g, p, stream);
+        case 0 * 8 + 2: return launch_lds_inst<0, 2>(g, p, stream);
+        case 0 * 8 + 1: return launch_lds_inst<0, 1>(g, p, stream);
+        case 4 * 8 + 0: return launch_lds_inst<4, 0>(g, p, stream);
+        case 2 * 8 + 0: return launch_lds_inst<2, 0>(g, p, stream);
+        case 1 * 8 + 0: return launch_lds_inst<1, 0>(g, p, stream);
+    }
     return hipErrorInvalidValue;
 }
 

@@ -1,6 +1,10 @@
 // Host-only planning for libtidal: configuration defaults, arena layout, copy plan.
 #include "plan.h"
 
+#include <stdlib.h>
+
+#include "tidal_internal.h"
+
 namespace tidal {
 
 bool normalise_config(const tidal_config* in, tidal_config* out, const char** msg) {
@@ -28,7 +32,7 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
     if (c.gather_threads < 1 || c.gather_threads > 16) { *msg = "gather_threads outside 1..16"; return false; }
     const int32_t known = TIDAL_FLAG_ORDERED_ACCUM | TIDAL_FLAG_TWO_PASS_SWAP | TIDAL_FLAG_SLOT_EVENTS |
                           TIDAL_FLAG_KERNEL_TIMING | TIDAL_FLAG_ASYNC_ENQUEUE | TIDAL_FLAG_NO_COPY_MERGE |
-                          TIDAL_FLAG_PIPELINED_UPLOAD;
+                          TIDAL_FLAG_PIPELINED_UPLOAD | TIDAL_FLAG_SERIAL_UPLOAD;
     if (c.flags & ~known) { *msg = "unknown flag bits"; return false; }
     *out = c;
     return true;
@@ -110,6 +114,102 @@ void plan_copies(const std::vector<SourceInfo>& srcs, const tidal_config& cfg, i
             eoff += take;
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// launch plan of a LoRA read-modify-write group
+// ---------------------------------------------------------------------------------------
+TuningKnobs tuning_knobs() {
+    TuningKnobs k = {-1, -1, -1, -1, -1, -1};
+#ifdef TIDAL_TUNING_KNOBS
+    auto read = [](const char* name, int lo, int hi) {
+        const char* e = getenv(name);
+        if (!e || !*e) return -1;
+        const int v = atoi(e);
+        return (v >= lo && v <= hi) ? v : -1;
+    };
+    k.mfma_rc = read("TIDAL_MFMA_RC", 1, 1024);
+    k.mfma_lds = read("TIDAL_MFMA_LDS", 0, 1);
+    k.mfma_pair = read("TIDAL_MFMA_PAIR", 0, 1);
+    k.mfma_order = read("TIDAL_MFMA_ORDER", 0, 3);
+    k.mfma_dynlds = read("TIDAL_MFMA_DYNLDS", 0, 120 << 10);
+    k.apply_ct = read("TIDAL_APPLY_CT", 1, kApplyChunkTiles);
+#endif
+    return k;
+}
+
+LoraLaunchPlan plan_lora_launch(const LoraGroup& g, bool ordered) {
+    LoraLaunchPlan p = {};
+    p.kind = kLoraNone;
+    p.ks_old = g.rp_old / 16;
+    p.ks_new = g.rp_new / 16;
+    p.fork = g.fork;
+    if (g.n_targets <= 0 || g.out <= 0 || g.in <= 0 || p.ks_old + p.ks_new == 0) return p;
+    if (ordered) {
+        p.kind = kLoraOrdered;
+        p.waves_per_simd = 1;
+        p.strips = (g.in + 255) / 256;                     // 64 x 256 tiles
+        p.rowblocks = (g.out + 63) / 64;
+        p.rc = 1;
+        p.blocks_per_target = p.strips * p.rowblocks;
+        p.total_blocks = (int64_t)p.blocks_per_target * g.n_targets;
+        return p;
+    }
+    const TuningKnobs knobs = tuning_knobs();
+    const int ks0 = p.ks_old, ks1 = p.ks_new;
+    // A strips stay in registers except in swaps with a 64-rank side: there they are staged in LDS
+    // (measured on 128 x 4096^2, LDS against registers: 64 -> 64 6.4 against 5.9 TB/s, 16/32 -> 64 6.5
+    // against 6.1-6.25, 64 -> 16/32 6.5 against 6.1-6.2; merges of 64 ranks run at 6.5 either way).
+    bool lds = !g.fork && ks0 > 0 && ks1 > 0 && (ks0 == 4 || ks1 == 4);
+    if (knobs.mfma_lds >= 0) lds = knobs.mfma_lds != 0;
+    lds = lds && !g.fork && lds_kernel_exists(ks0, ks1);
+    // Tiles two at a time (32 live accumulator registers instead of 128) for every swap and for
+    // 64-rank merges; merges of 16 or 32 ranks are faster with all tiles live.
+    p.pair = (ks0 > 0 && ks1 > 0) || ks0 + ks1 >= 4;
+    if (knobs.mfma_pair >= 0) p.pair = knobs.mfma_pair != 0;
+    p.strips = (g.in + 255) / 256;
+    p.rowblocks = (g.out + 31) / 32;
+    const int64_t tiles = (int64_t)p.strips * p.rowblocks * g.n_targets;
+    const bool pow2_pitch = (g.in & (g.in - 1)) == 0;
+    // 32-row blocks per wave.  Short walks keep waves short-lived, which this memory system rewards,
+    // long walks amortise the A strip, which grows with the rank; small jobs get fewer so that every
+    // CU has work.  Measured per instantiation on 64 and 128 x 4096^2, 40 x 5120^2 and 15 of the two
+    // 13824-wide shapes.
+    int rc;
+    if (lds) {
+        p.kind = kLoraMfmaLds;
+        p.pair = ks0 + ks1 < 8;          // 64 -> 64 is 2 % faster with all eight tiles live
+        p.waves_per_simd = 1;            // the compiler fits two (64 -> 64 and 16/32 -> 64) or three (64 -> 16/32)
+        // 16 for 64 -> 64, else 8; 4 and 2 where the row pitch is no power of two
+        rc = (ks0 + ks1 >= 8) ? (pow2_pitch ? 16 : 4) : (pow2_pitch ? 8 : 2);
+    } else {
+        p.kind = kLoraMfmaReg;
+        p.waves_per_simd = (p.pair && two_waves_fit(ks0, ks1)) ? 2 : 1;
+        if (p.pair) {
+            // swaps where two waves share a SIMD want 4 blocks, a 64-rank merge 8, every other swap
+            // 16; on row pitches that are no power of two the short walks gain more: the 4 and the 8
+            // are halved.  (A 16-rank merge looks 2-3 % faster at 2 blocks in a sweep where all slots
+            // share one adapter; with an adapter per slot, as in the 70B-shaped stack, it is 1 %
+            // slower: the A strips then come from HBM, not from L2.)
+            rc = two_waves_fit(ks0, ks1) ? 4 : ((ks0 == 0 || ks1 == 0) ? 8 : 16);
+            if (!pow2_pitch && rc <= 8) rc /= 2;
+        } else {
+            rc = 4;                      // merges of up to 32 ranks
+        }
+    }
+    const int64_t by_size = tiles / 4096;
+    if (by_size < rc) rc = by_size < 1 ? 1 : (int)by_size;
+    if (knobs.mfma_rc >= 1) rc = knobs.mfma_rc;
+    p.rc = rc;
+    if (lds) {
+        const int rowchunks = (p.rowblocks + 4 * rc - 1) / (4 * rc);      // the four waves interleave 4*rc blocks
+        p.blocks_per_target = p.strips * rowchunks;
+    } else {
+        const int rowchunks = (p.rowblocks + rc - 1) / rc;
+        p.blocks_per_target = (p.strips * rowchunks + 3) / 4;             // one (strip, row chunk) per wave
+    }
+    p.total_blocks = (int64_t)p.blocks_per_target * g.n_targets;
+    return p;
 }
 
 }  // namespace tidal

@@ -57,9 +57,31 @@ struct PackedTarget {
 };
 
 struct AdapterRec {
-    std::vector<PackedTarget> targets;   // sorted by slot
+    std::vector<PackedTarget> targets;   // in the caller's order
     char* dev = nullptr;
     size_t bytes = 0;
+    hipEvent_t ready = nullptr;          // resident adapters: recorded when the upload and packing are done
+                                         // (owned by the tidal_adapter); NULL for the in-arena copy of a
+                                         // host-pointer attach, which is uploaded on the attach's own stream
+};
+
+// Work the template has enqueued and not yet seen complete: one event per (kind, stream).  Calls
+// on different streams re-record different events, so tidal_template_sync and the cross-call
+// ordering cover every stream used, not only the one used last.
+enum MarkKind { kMarkLoad = 0, kMarkLora = 1 };
+struct StreamMark {
+    hipStream_t stream;
+    int kind;
+    hipEvent_t ev;
+    bool active;
+};
+
+struct RateModel {
+    double link_bytes_per_ms = 55e6;     // host -> device, adapters' factors
+    double rmw_bytes_per_ms = 6.0e9;     // in-place pass over W
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // upload begin / end, last merge begin / end
+    bool pending = false;                // ev[] recorded, not read yet
+    double up_bytes = 0.0, rmw_bytes = 0.0;
 };
 
 struct SlotState {
@@ -123,10 +145,10 @@ struct tidal_template {
     hipEvent_t staging_free[2] = {nullptr, nullptr};   // consumer: staging[b] may be overwritten
     hipEvent_t bounce_free[2] = {nullptr, nullptr};    // copy stream: pinned buffer b has been read
     hipEvent_t ev_start = nullptr, ev_copy_done = nullptr;
-    hipEvent_t ev_last_compute = nullptr, ev_last_lora = nullptr;
-    bool last_compute_rec = false, last_lora_rec = false;
+    std::vector<StreamMark> marks;
     hipStream_t up_stream = nullptr;                   // library-owned: adapter uploads that overlap the merge
-    hipEvent_t ev_up_begin = nullptr, ev_up_done[kMaxUploadGroups] = {};
+    hipEvent_t ev_up_begin = nullptr;
+    RateModel rates;
     char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
     bool bounce_used[2] = {false, false};
     bool staging_rec[2] = {false, false};
@@ -164,11 +186,31 @@ static int ensure_device(tidal_template* t) {
     }
     HIP_TRY(hipEventCreateWithFlags(&t->ev_start, flags));
     HIP_TRY(hipEventCreateWithFlags(&t->ev_copy_done, flags));
-    HIP_TRY(hipEventCreateWithFlags(&t->ev_last_compute, flags));
-    HIP_TRY(hipEventCreateWithFlags(&t->ev_last_lora, flags));
     int rc = resolve_scratch();
     if (rc) return rc;
     t->dev_ready = true;
+    return TIDAL_OK;
+}
+
+// Record that `stream` now carries work of this kind for the template.
+static int mark_done(tidal_template* t, int kind, hipStream_t stream) {
+    for (StreamMark& m : t->marks)
+        if (m.stream == stream && m.kind == kind) {
+            HIP_TRY(hipEventRecord(m.ev, stream));
+            m.active = true;
+            return TIDAL_OK;
+        }
+    StreamMark m{stream, kind, nullptr, true};
+    HIP_TRY(hipEventCreateWithFlags(&m.ev, hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(m.ev, stream));
+    t->marks.push_back(m);
+    return TIDAL_OK;
+}
+
+// Make `stream` wait (on the GPU) for the template's outstanding work of this kind on other streams.
+static int wait_marks(tidal_template* t, int kind, hipStream_t stream) {
+    for (const StreamMark& m : t->marks)
+        if (m.active && m.kind == kind && m.stream != stream) HIP_TRY(hipStreamWaitEvent(stream, m.ev, 0));
     return TIDAL_OK;
 }
 
@@ -181,7 +223,7 @@ static int ensure_upload_stream(tidal_template* t) {
     if (t->up_stream) return TIDAL_OK;
     HIP_TRY(hipStreamCreateWithFlags(&t->up_stream, hipStreamNonBlocking));      // default priority
     HIP_TRY(hipEventCreateWithFlags(&t->ev_up_begin, hipEventDisableTiming));
-    for (int g = 0; g < kMaxUploadGroups; ++g) HIP_TRY(hipEventCreateWithFlags(&t->ev_up_done[g], hipEventDisableTiming));
+    for (int k = 0; k < 4; ++k) HIP_TRY(hipEventCreate(&t->rates.ev[k]));
     return TIDAL_OK;
 }
 
@@ -408,6 +450,7 @@ struct Pipeline {
     bool kernel_copy = false;
     CopyBatch kbatch;
     int kruns = 0;
+    bool paced = true;              // the host stays at most two chunks ahead of the GPU (see acquire)
 
     int flush_kernel_copies() {
         if (kruns == 0) return TIDAL_OK;
@@ -477,7 +520,7 @@ struct Pipeline {
             // Host-side pacing: stay at most two chunks ahead of the GPU.  Hundreds of queued
             // cross-stream waits slow every copy down (measured: 42 instead of 55 GB/s for 402
             // chunks), a shallow queue does not.
-            if (!(t->cfg.flags & TIDAL_FLAG_ASYNC_ENQUEUE) && t->staging_rec[b])
+            if (paced && !(t->cfg.flags & TIDAL_FLAG_ASYNC_ENQUEUE) && t->staging_rec[b])
                 HIP_TRY(hipEventSynchronize(t->staging_free[b]));
             HIP_TRY(hipStreamWaitEvent(copy, t->staging_free[b], 0));
         }
@@ -535,9 +578,13 @@ static int materialize_impl(tidal_template* t, std::vector<SourceInfo>& infos, b
 
     Pipeline pl{t, (hipStream_t)copy_stream, (hipStream_t)compute_stream};
     // LoRA kernels of this template may have run on another stream: order after them
-    if (t->last_lora_rec) {
-        HIP_TRY(hipStreamWaitEvent(pl.compute, t->ev_last_lora, 0));
-        if (pl.copy != pl.compute) HIP_TRY(hipStreamWaitEvent(pl.copy, t->ev_last_lora, 0));
+    rc = wait_marks(t, kMarkLora, pl.compute);
+    if (rc) return rc;
+    if (pl.copy != pl.compute) {
+        rc = wait_marks(t, kMarkLora, pl.copy);
+        if (rc) return rc;
+        for (const StreamMark& m : t->marks)             // LoRA work on the compute stream itself
+            if (m.active && m.kind == kMarkLora && m.stream == pl.compute) HIP_TRY(hipStreamWaitEvent(pl.copy, m.ev, 0));
     }
     // copies may write slots that earlier work on the compute stream still reads
     if (pl.copy != pl.compute) {
@@ -614,14 +661,15 @@ static int materialize_impl(tidal_template* t, std::vector<SourceInfo>& infos, b
         HIP_TRY(hipEventRecord(t->ev_copy_done, pl.copy));
         HIP_TRY(hipStreamWaitEvent(pl.compute, t->ev_copy_done, 0));
     }
-    HIP_TRY(hipEventRecord(t->ev_last_compute, pl.compute));
-    t->last_compute_rec = true;
+    rc = mark_done(t, kMarkLoad, pl.compute);
+    if (rc) return rc;
     for (const SourceInfo& s : infos) t->slots[s.slot].materialised = true;
     if (!direct.targets.empty()) {
         // bf16 sources are exact in the slot already: the in-place merge is the same single rounding
         rc = launch_rmw(t, nullptr, &direct, pl.compute);
         if (rc) return rc;
-        HIP_TRY(hipEventRecord(t->ev_last_compute, pl.compute));
+        rc = mark_done(t, kMarkLoad, pl.compute);
+        if (rc) return rc;
     }
     if (clears) {
         if (t->cur_resident) t->cur_resident->attached = false;
@@ -696,9 +744,9 @@ static int validate_targets(const tidal_template* t, const tidal_lora_target* tg
                 return fail(TIDAL_E_INVAL, "target %d: a LoRA factor of %zu bytes is larger than chunk_bytes (%zu)", i, longest,
                             t->cfg.chunk_bytes);
             p.at_off = off;
-            off = align_up(off + 2 * (size_t)s.cols * p.rp, kSlotAlign);
+            off = align_up(off + packed_at_bytes(s.cols, p.rp), kSlotAlign);
             p.bp_off = off;
-            off = align_up(off + 2 * (size_t)s.rows * p.rp, kSlotAlign);
+            off = align_up(off + packed_bp_bytes(s.rows, p.rp), kSlotAlign);
             if (keep_rows && s.cols % 8 == 0) {
                 p.ar_off = off;
                 off = align_up(off + 2 * (size_t)s.cols * p.r, kSlotAlign);
@@ -727,8 +775,11 @@ extern "C" size_t tidal_adapter_required_bytes(const tidal_template* t, const ti
 
 // Stage A and B of every active target through the staging buffers and pack them into
 // rec.dev on `stream`.
-static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t stream,
-                          size_t first = 0, size_t last = ~(size_t)0) {
+// `copy` and `pack` may differ: the copies of a later chunk then run while an earlier one is packed
+// (and, for a pipelined attach, merged) on `pack`.  `chunk_io` carries the staging-buffer parity from
+// one call to the next so that successive groups alternate between the two buffers.
+static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t copy,
+                          hipStream_t pack, size_t first = 0, size_t last = ~(size_t)0, int* chunk_io = nullptr) {
     // A job is one factor staged once; A may be packed twice (transposed and, as a plain
     // conversion written as lines of 8, row-major)
     struct Job { const char* host; size_t bytes; PackSegment seg; bool pinned; bool has2; PackSegment seg2; };
@@ -739,13 +790,13 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
         if (!p.active() || s.elems == 0) continue;
         const size_t isz = dtype_size(tg[i].dtype);
         Job a{(const char*)tg[i].A, (size_t)p.r * (size_t)s.cols * isz,
-              PackSegment{nullptr, rec.dev + p.at_off, s.cols, p.r, p.rp, tg[i].dtype, 1}, false, false, {}};
+              PackSegment{nullptr, rec.dev + p.at_off, s.cols, p.r, p.rp, tg[i].dtype, kPackAt}, false, false, {}};
         if (p.ar_off != kNoOffset) {
             a.has2 = true;
-            a.seg2 = PackSegment{nullptr, rec.dev + p.ar_off, (int64_t)p.r * s.cols / 8, 8, 8, tg[i].dtype, 0};
+            a.seg2 = PackSegment{nullptr, rec.dev + p.ar_off, (int64_t)p.r * s.cols / 8, 8, 8, tg[i].dtype, kPackRows};
         }
         Job b{(const char*)tg[i].B, (size_t)p.r * (size_t)s.rows * isz,
-              PackSegment{nullptr, rec.dev + p.bp_off, s.rows, p.r, p.rp, tg[i].dtype, 0}, false, false, {}};
+              PackSegment{nullptr, rec.dev + p.bp_off, s.rows, p.r, p.rp, tg[i].dtype, kPackBp}, false, false, {}};
         if (a.bytes > t->cfg.chunk_bytes || b.bytes > t->cfg.chunk_bytes)
             return fail(TIDAL_E_INVAL, "target %zu: a LoRA factor is larger than chunk_bytes", i);
         jobs.push_back(a);
@@ -754,10 +805,11 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
     if (jobs.empty()) return TIDAL_OK;
     for (Job& j : jobs) j.pinned = host_is_pinned(j.host);
 
-    Pipeline pl{t, stream, stream};
+    Pipeline pl{t, copy, pack};
     pl.kernel_copy = true;
+    pl.paced = false;               // a handful of chunks: the host never waits for the GPU here
     size_t i = 0;
-    int chunk = 0;
+    int chunk = chunk_io ? *chunk_io : 0;
     while (i < jobs.size()) {
         const int b = chunk & 1;
         // fill one staging buffer with whole factors: all copies first (neighbouring ones merge
@@ -795,13 +847,14 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
             const int n = (int)std::min(segs.size() - k, (size_t)kMaxPackSeg);
             PackBatch batch;
             memcpy(batch.seg, segs.data() + k, (size_t)n * sizeof(PackSegment));
-            HIP_TRY(launch_pack(batch, n, stream));
+            HIP_TRY(launch_pack(batch, n, pack));
         }
         rc = pl.consumed(b);
         if (rc) return rc;
         i = j;
         ++chunk;
     }
+    if (chunk_io) *chunk_io = chunk;
     return TIDAL_OK;
 }
 
@@ -818,12 +871,24 @@ extern "C" int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* 
     rc = ensure_device(t);
     if (rc) return rc;
     rec.dev = (char*)dev_mem;
-    rc = upload_adapter(t, targets, rec, (hipStream_t)stream);
-    if (rc) return rc;
-    HIP_TRY(hipEventRecord(t->ev_last_lora, (hipStream_t)stream));
-    t->last_lora_rec = true;
     tidal_adapter* a = new (std::nothrow) tidal_adapter();
     if (!a) return fail(TIDAL_E_NOMEM, "out of host memory");
+    hipError_t e = hipEventCreateWithFlags(&rec.ready, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        delete a;
+        return fail(TIDAL_E_HIP, "hipEventCreate failed: %s", hipGetErrorString(e));
+    }
+    // the staging buffers are shared with materialisations and other uploads, whatever their streams
+    rc = wait_marks(t, kMarkLoad, (hipStream_t)stream);
+    if (!rc) rc = upload_adapter(t, targets, rec, (hipStream_t)stream, (hipStream_t)stream);
+    if (!rc && hipEventRecord(rec.ready, (hipStream_t)stream) != hipSuccess) rc = fail(TIDAL_E_HIP, "hipEventRecord failed");
+    if (!rc) rc = mark_done(t, kMarkLora, (hipStream_t)stream);
+    if (rc) {
+        (void)hipStreamSynchronize((hipStream_t)stream);       // nothing may still read the caller's host memory
+        (void)hipEventDestroy(rec.ready);
+        delete a;
+        return rc;
+    }
     a->owner = t;
     a->rec = rec;
     a->attached = false;
@@ -834,6 +899,7 @@ extern "C" int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* 
 extern "C" int tidal_adapter_destroy(tidal_adapter* a) {
     if (!a) return TIDAL_OK;
     if (a->attached) return fail(TIDAL_E_STATE, "adapter is attached; detach or swap it out first");
+    if (a->rec.ready) (void)hipEventDestroy(a->rec.ready);
     delete a;
     return TIDAL_OK;
 }
@@ -843,14 +909,17 @@ extern "C" int tidal_adapter_destroy(tidal_adapter* a) {
 // ---------------------------------------------------------------------------------------
 typedef std::tuple<int64_t, int64_t, int, int, int, int> LoraKey;   // out, in, rp_old, rp_new, r_old, r_new
 
-// One launch per (shape, ranks) group and at most kMaxLoraTargets slots.
+// One launch per (shape, ranks) group and at most kMaxLoraTargets slots; a larger group is cut
+// into equal parts (160 slots: 80 + 80, not 128 + 32 -- the short launch would run at a lower rate).
 static int launch_groups(tidal_template* t, const std::map<LoraKey, std::vector<LoraTargetDev>>& groups,
                          const char* old_base, const char* new_base, bool fork, hipStream_t stream) {
     const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
     for (auto& g : groups) {
         const std::vector<LoraTargetDev>& all = g.second;
-        for (size_t at = 0; at < all.size(); at += kMaxLoraTargets) {
-            const size_t n = std::min(all.size() - at, (size_t)kMaxLoraTargets);
+        const size_t parts = (all.size() + kMaxLoraTargets - 1) / kMaxLoraTargets;
+        const size_t per = parts ? (all.size() + parts - 1) / parts : 0;
+        for (size_t at = 0; at < all.size(); at += per) {
+            const size_t n = std::min(all.size() - at, per);
             LoraBatch batch;
             batch.w_base = t->arena;
             batch.old_base = old_base;
@@ -866,14 +935,61 @@ static int launch_groups(tidal_template* t, const std::map<LoraKey, std::vector<
             lg.r_old = std::get<4>(g.first);
             lg.r_new = std::get<5>(g.first);
             lg.fork = fork;
+            const LoraLaunchPlan plan = plan_lora_launch(lg, ordered);
+            if (plan.kind == kLoraNone) continue;
             hipEvent_t t0;
             int trc = timing_begin(t, stream, &t0);
             if (trc) return trc;
-            HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, stream));
+            HIP_TRY(ordered ? launch_lora_ordered(lg, stream) : launch_lora_mfma(lg, plan, stream));
             trc = timing_end(t, stream, t0, true);
             if (trc) return trc;
             t->stats.lora_launches++;
         }
+    }
+    return TIDAL_OK;
+}
+
+// Which kernel, variant, walk length and grid a LoRA pass over n_targets slots of out x in would
+// be launched with (host-only introspection, like tidal_materialize_plan).
+extern "C" int tidal_lora_launch_info(const tidal_template* t, int64_t out, int64_t in, int32_t n_targets,
+                                      int32_t r_old, int32_t r_new, int32_t fork, tidal_lora_launch* info) {
+    if (!t || !info) return fail(TIDAL_E_INVAL, "NULL argument");
+    if (out <= 0 || in <= 0 || out > 0x7FFFFFFF || in > 0x7FFFFFFF) return fail(TIDAL_E_INVAL, "bad shape");
+    if (n_targets <= 0) return fail(TIDAL_E_INVAL, "n_targets must be positive");
+    if (r_old < 0 || r_new < 0 || r_old > t->cfg.max_rank || r_new > t->cfg.max_rank)
+        return fail(TIDAL_E_INVAL, "rank outside 0..%d", t->cfg.max_rank);
+    if (fork && r_old) return fail(TIDAL_E_INVAL, "a fork apply has no old adapter");
+    memset(info, 0, sizeof *info);
+    const size_t parts = ((size_t)n_targets + kMaxLoraTargets - 1) / kMaxLoraTargets;
+    const size_t per = ((size_t)n_targets + parts - 1) / parts;
+    LoraGroup lg;
+    lg.batch = nullptr;
+    lg.n_targets = (int32_t)per;
+    lg.out = (int32_t)out;
+    lg.in = (int32_t)in;
+    lg.r_old = r_old;
+    lg.r_new = r_new;
+    lg.rp_old = padded_rank(r_old);
+    lg.rp_new = padded_rank(r_new);
+    lg.fork = fork != 0;
+    const LoraLaunchPlan p = plan_lora_launch(lg, (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0);
+    info->launches = p.kind == kLoraNone ? 0 : (int32_t)parts;
+    info->targets_per_launch = (int32_t)per;
+    info->rank_padded_old = 16 * p.ks_old;
+    info->rank_padded_new = 16 * p.ks_new;
+    info->blocks_per_walk = p.rc;
+    info->waves_per_simd = p.waves_per_simd;
+    info->workgroups = p.total_blocks;
+    switch (p.kind) {
+        case kLoraMfmaReg:
+            snprintf(info->kernel, sizeof info->kernel, "lora_mfma_kernel<8,%d,%d,%s,%s>", p.ks_old, p.ks_new,
+                     p.fork ? "fork" : "inplace", p.pair ? "pair" : "all");
+            break;
+        case kLoraMfmaLds:
+            snprintf(info->kernel, sizeof info->kernel, "lora_mfma_lds_kernel<8,%d,%d>", p.ks_old, p.ks_new);
+            break;
+        case kLoraOrdered: snprintf(info->kernel, sizeof info->kernel, "lora_ordered_kernel"); break;
+        default: snprintf(info->kernel, sizeof info->kernel, "none"); break;
     }
     return TIDAL_OK;
 }
@@ -890,8 +1006,12 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
         for (const PackedTarget& p : newer->targets)
             if (p.active() && t->slots[p.slot].elems > 0) by_slot[p.slot].second = Side{&p, newer};
     if (by_slot.empty()) return TIDAL_OK;
-    // the slots may still be streaming in on the materialisation's streams
-    if (t->last_compute_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_compute, 0));
+    // the slots may still be streaming in on the materialisation's streams, and a resident adapter
+    // may still be uploading on the stream it was given
+    int wrc = wait_marks(t, kMarkLoad, stream);
+    if (wrc) return wrc;
+    if (older && older->ready) HIP_TRY(hipStreamWaitEvent(stream, older->ready, 0));
+    if (newer && newer->ready) HIP_TRY(hipStreamWaitEvent(stream, newer->ready, 0));
 
     typedef LoraKey Key;
     std::map<Key, std::vector<LoraTargetDev>> groups;
@@ -924,9 +1044,7 @@ static int launch_rmw(tidal_template* t, const AdapterRec* older, const AdapterR
     }
     int rc = launch_groups(t, groups, older ? older->dev : nullptr, newer ? newer->dev : nullptr, false, stream);
     if (rc) return rc;
-    HIP_TRY(hipEventRecord(t->ev_last_lora, stream));
-    t->last_lora_rec = true;
-    return TIDAL_OK;
+    return mark_done(t, kMarkLora, stream);
 }
 
 static int do_swap_launch(tidal_template* t, const AdapterRec* older, const AdapterRec* newer, hipStream_t stream) {
@@ -947,6 +1065,95 @@ static void set_attached(tidal_template* t, const AdapterRec& rec, tidal_adapter
     if (resident) resident->attached = true;
 }
 
+// Rates the grouping of a pipelined attach is sized from.  They start at typical values and are
+// replaced by what the library measures with its own events on a pipelined call: the link rate from
+// the upload stream (first copy to last copy), the in-place pass rate from the last group's launches.
+static void rates_update(tidal_template* t) {
+    RateModel& r = t->rates;
+    if (!r.pending) return;
+    if (hipEventQuery(r.ev[1]) != hipSuccess || hipEventQuery(r.ev[3]) != hipSuccess) {
+        (void)hipGetLastError();           // still running: keep the current estimates
+        return;
+    }
+    float up_ms = 0.f, rmw_ms = 0.f;
+    if (hipEventElapsedTime(&up_ms, r.ev[0], r.ev[1]) == hipSuccess && up_ms > 1e-3f && r.up_bytes > 0.0)
+        r.link_bytes_per_ms = r.up_bytes / up_ms;
+    if (hipEventElapsedTime(&rmw_ms, r.ev[2], r.ev[3]) == hipSuccess && rmw_ms > 1e-3f && r.rmw_bytes > 0.0)
+        r.rmw_bytes_per_ms = r.rmw_bytes / rmw_ms;
+    (void)hipGetLastError();
+    r.pending = false;
+}
+
+// Cut the targets of an adapter given by host pointers into groups that are uploaded and merged in
+// turn.  With upload time u and merge time m of each target known from the two rates, the end of
+// the call is simulated for every choice of the first group's size (each later group: as many
+// targets as cross the link while the group before it is merged) and the best one taken.  Every
+// launch is charged a fixed cost, which keeps the number of groups down; small adapters, one
+// target, or TIDAL_FLAG_SERIAL_UPLOAD give a single group (one stream, no pipelining).
+static void plan_upload_groups(const tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec,
+                               const AdapterRec* old, std::vector<std::pair<size_t, size_t>>* groups) {
+    constexpr size_t kPipelineFrom = (size_t)4 << 20;
+    constexpr double kLaunchMs = 0.012;            // bubble and tail of one more launch
+    const size_t n = rec.targets.size();
+    groups->clear();
+    groups->push_back({0, n});
+    const bool forced = (t->cfg.flags & TIDAL_FLAG_PIPELINED_UPLOAD) != 0;
+    if ((t->cfg.flags & TIDAL_FLAG_SERIAL_UPLOAD) || n < 2 || (!forced && rec.bytes < kPipelineFrom)) return;
+    std::vector<char> in_old(t->slots.size(), 0);
+    if (old)
+        for (const PackedTarget& p : old->targets)
+            if (p.active()) in_old[p.slot] = 1;
+    std::vector<double> u(n, 0.0), m(n, 0.0);
+    double u_total = 0.0, m_total = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        const PackedTarget& p = rec.targets[i];
+        const SlotState& s = t->slots[p.slot];
+        if (s.elems == 0) continue;
+        if (p.active()) u[i] = (double)p.r * (double)(s.rows + s.cols) * (double)dtype_size(tg[i].dtype) / t->rates.link_bytes_per_ms;
+        if (p.active() || in_old[p.slot]) m[i] = 4.0 * (double)s.elems / t->rates.rmw_bytes_per_ms;
+        u_total += u[i];
+        m_total += m[i];
+    }
+    if (u_total <= 0.0 || m_total <= 0.0) return;
+    // shape classes of a range of targets = launches of its merge
+    auto launches = [&](size_t a, size_t b) {
+        int cnt = 0;
+        int64_t seen[8][2];
+        for (size_t i = a; i < b && cnt < 8; ++i) {
+            const SlotState& s = t->slots[rec.targets[i].slot];
+            bool found = false;
+            for (int k = 0; k < cnt; ++k) found |= seen[k][0] == s.rows && seen[k][1] == s.cols;
+            if (!found) { seen[cnt][0] = s.rows; seen[cnt][1] = s.cols; ++cnt; }
+        }
+        return cnt < 1 ? 1 : cnt;
+    };
+    // a single group (serial) is the candidate to beat, unless grouping is forced
+    double best = forced ? 1e300 : u_total + m_total + kLaunchMs * launches(0, n);
+    std::vector<std::pair<size_t, size_t>> best_groups = *groups;
+    for (size_t first = 1; first < n; ++first) {
+        std::vector<std::pair<size_t, size_t>> cand;
+        size_t a = 0, b = first;
+        double up_done = 0.0, merge_done = 0.0;
+        while (a < n) {
+            if ((int)cand.size() == kMaxUploadGroups - 1) b = n;        // the last group takes the rest
+            double ug = 0.0, mg = 0.0;
+            for (size_t i = a; i < b; ++i) { ug += u[i]; mg += m[i]; }
+            up_done += ug;
+            merge_done = std::max(merge_done, up_done) + mg + kLaunchMs * (1 + launches(a, b));    // pack + merges
+            cand.push_back({a, b});
+            // next group: what crosses the link while this one is merged
+            a = b;
+            double budget = mg, acc = 0.0;
+            while (b < n && (acc + u[b] <= budget || b == a)) acc += u[b++];
+        }
+        if (merge_done < best) {
+            best = merge_done;
+            best_groups = cand;
+        }
+    }
+    *groups = best_groups;
+}
+
 // attach (swap = false) or swap (swap = true) an adapter given by host pointers
 static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n, void* stream, bool swap) {
     AdapterRec rec;
@@ -965,61 +1172,31 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
     rec.dev = t->arena + t->lay.adapter_region[region];
     AdapterRec old = t->cur;
 
-    // TIDAL_FLAG_PIPELINED_UPLOAD: upload and merge in groups of targets; while group g is merged on
-    // the caller's stream, group g+1 crosses the link on a stream of the library's own.  Where a
-    // target's merge takes at least twice as long as its upload (small ranks), each group may be
-    // twice the size of the one before and still arrive in time: cuts at 1/8 and 3/8 of the upload
-    // leave one eighth of it exposed and add two launches.  Where upload and merge take about as
-    // long (large ranks), only equal groups keep both busy: eight of them.
+    // Upload and merge in groups of targets: while group g is packed and merged on the caller's
+    // stream, the copies of group g+1 cross the link on a stream of the library's own.
     std::vector<std::pair<size_t, size_t>> groups;
-    {
-        constexpr size_t kPipelineFrom = (size_t)4 << 20;
-        const bool pipelined = (t->cfg.flags & TIDAL_FLAG_PIPELINED_UPLOAD) != 0 && rec.bytes >= kPipelineFrom;
-        std::vector<double> host_bytes(rec.targets.size(), 0.0);
-        double up_total = 0.0, w_bytes = 0.0;
-        for (size_t i = 0; i < rec.targets.size() && pipelined; ++i) {
-            const PackedTarget& p = rec.targets[i];
-            const SlotState& s = t->slots[p.slot];
-            if (!p.active() || s.elems == 0) continue;
-            host_bytes[i] = (double)p.r * (double)(s.rows + s.cols) * (double)dtype_size(tg[i].dtype);
-            up_total += host_bytes[i];
-            w_bytes += 4.0 * (double)s.elems;
-        }
-        std::vector<double> cuts;                                  // fractions of the upload
-        if (pipelined && up_total > 0.0) {
-            const double up_ms = up_total / 55e6, merge_ms = w_bytes / 6.3e9;      // link and HBM rates of this machine
-            if (up_ms <= 0.6 * merge_ms) cuts = {0.125, 0.375};
-            else for (int g = 1; g < kMaxUploadGroups; ++g) cuts.push_back((double)g / kMaxUploadGroups);
-        }
-        size_t begin = 0;
-        double acc = 0.0;
-        for (size_t i = 0; i < rec.targets.size() && groups.size() < cuts.size(); ++i) {
-            acc += host_bytes[i];
-            if (acc >= cuts[groups.size()] * up_total && i + 1 < rec.targets.size()) {
-                groups.push_back({begin, i + 1});
-                begin = i + 1;
-            }
-        }
-        groups.push_back({begin, rec.targets.size()});
-    }
+    plan_upload_groups(t, tg, rec, swap ? &old : nullptr, &groups);
     if (groups.size() <= 1) {
-        rc = upload_adapter(t, tg, rec, (hipStream_t)stream);
+        rc = upload_adapter(t, tg, rec, (hipStream_t)stream, (hipStream_t)stream);
         if (rc) return rc;
         rc = do_swap_launch(t, swap ? &old : nullptr, &rec, (hipStream_t)stream);
         if (rc) return rc;
     } else {
         rc = ensure_upload_stream(t);
         if (rc) return rc;
-        // the region to be written was last read by kernels already on the caller's stream
+        rates_update(t);
+        // the staging buffers and the region to be written were last used by work on the caller's stream
         HIP_TRY(hipEventRecord(t->ev_up_begin, (hipStream_t)stream));
         HIP_TRY(hipStreamWaitEvent(t->up_stream, t->ev_up_begin, 0));
+        const bool calibrate = !t->rates.pending;
+        if (calibrate) HIP_TRY(hipEventRecord(t->rates.ev[0], t->up_stream));
         std::vector<char> in_new(t->slots.size(), 0);
         for (const PackedTarget& p : rec.targets) in_new[p.slot] = 1;
+        int chunk = 0;
+        double up_bytes = 0.0;
         for (size_t g = 0; g < groups.size(); ++g) {
-            rc = upload_adapter(t, tg, rec, t->up_stream, groups[g].first, groups[g].second);
+            rc = upload_adapter(t, tg, rec, t->up_stream, (hipStream_t)stream, groups[g].first, groups[g].second, &chunk);
             if (rc) return rc;
-            HIP_TRY(hipEventRecord(t->ev_up_done[g], t->up_stream));
-            HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, t->ev_up_done[g], 0));
             AdapterRec part_new, part_old;
             part_new.dev = rec.dev;
             part_new.targets.assign(rec.targets.begin() + groups[g].first, rec.targets.begin() + groups[g].second);
@@ -1030,8 +1207,25 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
                 for (const PackedTarget& p : old.targets)       // slots only the old adapter touches go last
                     if (here[p.slot] || (g + 1 == groups.size() && !in_new[p.slot])) part_old.targets.push_back(p);
             }
+            const bool last = g + 1 == groups.size();
+            if (last && calibrate) {
+                HIP_TRY(hipEventRecord(t->rates.ev[1], t->up_stream));          // every copy has been issued by now
+                HIP_TRY(hipEventRecord(t->rates.ev[2], (hipStream_t)stream));   // after the last pack, before the last merge
+            }
+            const uint64_t before = t->stats.rmw_elems;
             rc = do_swap_launch(t, swap ? &part_old : nullptr, &part_new, (hipStream_t)stream);
             if (rc) return rc;
+            if (last && calibrate) {
+                HIP_TRY(hipEventRecord(t->rates.ev[3], (hipStream_t)stream));
+                for (size_t i = 0; i < rec.targets.size(); ++i) {
+                    const PackedTarget& p = rec.targets[i];
+                    const SlotState& sl = t->slots[p.slot];
+                    if (p.active() && sl.elems > 0) up_bytes += (double)p.r * (double)(sl.rows + sl.cols) * (double)dtype_size(tg[i].dtype);
+                }
+                t->rates.up_bytes = up_bytes;
+                t->rates.rmw_bytes = 4.0 * (double)(t->stats.rmw_elems - before);
+                t->rates.pending = true;
+            }
         }
     }
     set_attached(t, rec, nullptr, region);
@@ -1065,8 +1259,11 @@ extern "C" int tidal_materialize_attach(tidal_template* t, const tidal_src* srcs
     const int region = (t->cur_region == 0) ? 1 : 0;
     rec.dev = t->arena + t->lay.adapter_region[region];
     // the factors go first, on the compute stream, where the kernels that read them run
-    if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent((hipStream_t)compute_stream, t->ev_last_lora, 0));
-    rc = upload_adapter(t, targets, rec, (hipStream_t)compute_stream);
+    rc = wait_marks(t, kMarkLora, (hipStream_t)compute_stream);
+    if (rc) return rc;
+    rc = wait_marks(t, kMarkLoad, (hipStream_t)compute_stream);
+    if (rc) return rc;
+    rc = upload_adapter(t, targets, rec, (hipStream_t)compute_stream, (hipStream_t)compute_stream);
     if (rc) return rc;
     rc = materialize_impl(t, infos, clears, copy_stream, compute_stream, &rec);
     if (rc) return rc;
@@ -1232,7 +1429,8 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
     int rc = no_alloc ? TIDAL_OK : ensure_device(t);
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)stream_;
-    if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));   // adapter uploads
+    for (int32_t a = 0; a < n_adapters; ++a)                                         // the uploads of the adapters in use
+        if (used[a] && adapters[a]->rec.ready) HIP_TRY(hipStreamWaitEvent(stream, adapters[a]->rec.ready, 0));
 
     // with ordered accumulation every segment takes the (slow, bit-reproducible) ordered kernels
     const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
@@ -1284,10 +1482,7 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
             // small batches spread over the chip (aim: >= 1024 waves; measured best of 1, 2, 4)
             const int64_t strips = (launch_out + 255) / 256;
             int ct = (int)std::max<int64_t>(1, std::min<int64_t>(kApplyChunkTiles, tiles * strips / 1024));
-            if (const char* e = tuning_knob("TIDAL_APPLY_CT")) {       // tuning builds only
-                const int v = atoi(e);
-                if (v >= 1 && v <= kApplyChunkTiles) ct = v;
-            }
+            if (tuning_knobs().apply_ct >= 1) ct = tuning_knobs().apply_ct;      // tuning builds only
             int64_t units = 0;
             for (int k = 0; k < kMaxApplyLong; ++k) b.first[k] = 0x7FFFFFFF;
             for (int k = 0; k < n; ++k) {
@@ -1496,8 +1691,11 @@ extern "C" int tidal_fork_apply(tidal_fork* f, const tidal_adapter* a, void* str
         }
     int rc = ensure_device(t);
     if (rc) return rc;
-    if (t->last_compute_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_compute, 0));
-    if (t->last_lora_rec) HIP_TRY(hipStreamWaitEvent(stream, t->ev_last_lora, 0));
+    rc = wait_marks(t, kMarkLoad, stream);
+    if (rc) return rc;
+    rc = wait_marks(t, kMarkLora, stream);       // a detach that restored the template on another stream
+    if (rc) return rc;
+    if (a && a->rec.ready) HIP_TRY(hipStreamWaitEvent(stream, a->rec.ready, 0));
     std::map<LoraKey, std::vector<LoraTargetDev>> groups;
     for (size_t i = 0; i < f->slots.size(); ++i) {
         const int32_t slot = f->slots[i];
@@ -1524,9 +1722,7 @@ extern "C" int tidal_fork_apply(tidal_fork* f, const tidal_adapter* a, void* str
     }
     rc = launch_groups(t, groups, f->dev, a ? a->rec.dev : nullptr, true, stream);
     if (rc) return rc;
-    HIP_TRY(hipEventRecord(t->ev_last_lora, stream));
-    t->last_lora_rec = true;
-    return TIDAL_OK;
+    return mark_done(t, kMarkLora, stream);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1613,6 +1809,34 @@ extern "C" int tidal_h2d_peak(void* dev, size_t bytes, int32_t reps, void* strea
     return TIDAL_OK;
 }
 
+extern "C" int tidal_hbm_rmw_peak(void* dev, int64_t rows, int64_t cols, int64_t n, int32_t blocks_per_walk, int32_t reps,
+                                  void* stream, double* gbytes_per_s) {
+    if (!dev || !gbytes_per_s || reps <= 0) return fail(TIDAL_E_INVAL, "bad argument");
+    if (rows <= 0 || cols <= 0 || n <= 0 || rows % 32 || cols % 256 || rows > 0x7FFFFFFF || cols > 0x7FFFFFFF)
+        return fail(TIDAL_E_INVAL, "rows must be a positive multiple of 32 and cols of 256");
+    if (blocks_per_walk < 1 || blocks_per_walk > 1024) return fail(TIDAL_E_INVAL, "blocks_per_walk outside 1..1024");
+    if ((uintptr_t)dev % 16) return fail(TIDAL_E_INVAL, "dev is not 16-byte aligned");
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    hipStream_t s = (hipStream_t)stream;
+    double best = 0.0;
+    for (int i = 0; i < reps + 1 && e == hipSuccess; ++i) {     // first pass is a warm-up
+        e = hipEventRecord(a, s);
+        if (e == hipSuccess) e = launch_rmw_probe(dev, rows, cols, n, blocks_per_walk, s);
+        if (e == hipSuccess) e = hipEventRecord(b, s);
+        if (e == hipSuccess) e = hipEventSynchronize(b);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+        if (e == hipSuccess && i > 0 && ms > 0.f) best = std::max(best, 4.0 * (double)rows * (double)cols * (double)n / (ms * 1e-3) / 1e9);
+    }
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+    if (e != hipSuccess) return fail(TIDAL_E_HIP, "read-modify-write probe failed: %s", hipGetErrorString(e));
+    *gbytes_per_s = best;
+    return TIDAL_OK;
+}
+
 extern "C" int tidal_get_stats(tidal_template* t, tidal_stats* out) {
     if (!t || !out) return fail(TIDAL_E_INVAL, "NULL argument");
     int rc = timing_drain(t);
@@ -1632,8 +1856,11 @@ extern "C" int tidal_reset_stats(tidal_template* t) {
 extern "C" int tidal_template_sync(tidal_template* t) {
     if (!t) return fail(TIDAL_E_INVAL, "template is NULL");
     if (!t->dev_ready) return TIDAL_OK;
-    if (t->last_compute_rec) HIP_TRY(hipEventSynchronize(t->ev_last_compute));
-    if (t->last_lora_rec) HIP_TRY(hipEventSynchronize(t->ev_last_lora));
+    for (StreamMark& m : t->marks)
+        if (m.active) {
+            HIP_TRY(hipEventSynchronize(m.ev));
+            m.active = false;
+        }
     return TIDAL_OK;
 }
 
@@ -1651,13 +1878,12 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
         if (t->up_stream) {
             (void)hipStreamSynchronize(t->up_stream);
             (void)hipEventDestroy(t->ev_up_begin);
-            for (int g = 0; g < kMaxUploadGroups; ++g) (void)hipEventDestroy(t->ev_up_done[g]);
+            for (int k = 0; k < 4; ++k) (void)hipEventDestroy(t->rates.ev[k]);
             (void)hipStreamDestroy(t->up_stream);
         }
         (void)hipEventDestroy(t->ev_start);
         (void)hipEventDestroy(t->ev_copy_done);
-        (void)hipEventDestroy(t->ev_last_compute);
-        (void)hipEventDestroy(t->ev_last_lora);
+        for (StreamMark& m : t->marks) (void)hipEventDestroy(m.ev);
         for (SlotState& s : t->slots)
             if (s.ready) (void)hipEventDestroy(s.ready);
         (void)timing_drain(t);

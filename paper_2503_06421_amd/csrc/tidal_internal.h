@@ -24,14 +24,25 @@ struct ConvertBatch { ConvertSegment seg[kMaxConvertSeg]; };
 
 hipError_t launch_convert(const ConvertBatch& batch, int nseg, hipStream_t stream);
 hipError_t launch_slot_checksum(const void* slot, int64_t elems, int passes, void* dev_sum, hipStream_t stream);
+// Bare in-place read-modify-write over n matrices of rows x cols 16-bit elements in the LoRA kernels'
+// tiling (256-column strips, rc blocks of 32 rows per wave); rows % 32 == 0, cols % 256 == 0.
+hipError_t launch_rmw_probe(void* base, int64_t rows, int64_t cols, int64_t n, int rc, hipStream_t stream);
 
 // ---- packing of LoRA factors ------------------------------------------------------------
-struct PackSegment {
-    const void* src;     // device staging: A (r x lines, transposed = 1) or B (lines x r)
-    void* dst;           // device: lines x rp bf16
-    int64_t lines;       // in (for A) or out (for B)
-    int32_t r, rp, dtype, transposed;
+enum PackLayout {
+    kPackRows = 0,       // dst: lines x rp, row-major (plain conversion; A kept row-major for the unmerged apply)
+    kPackAt = 1,         // src: A, r x lines; dst: A transposed in MFMA operand order, lines rounded up to 256
+    kPackBp = 2          // src: B, lines x r; dst: B in MFMA operand order, lines rounded up to 32
 };
+struct PackSegment {
+    const void* src;     // device staging
+    void* dst;           // device: packed bf16, ranks zero padded to rp
+    int64_t lines;       // in (for A) or out (for B)
+    int32_t r, rp, dtype, layout;
+};
+// Bytes of the packed copies: padding lines are written (zeros), so they count.
+inline size_t packed_at_bytes(int64_t in, int rp) { return 2 * (size_t)((in + 255) / 256 * 256) * (size_t)rp; }
+inline size_t packed_bp_bytes(int64_t out, int rp) { return 2 * (size_t)((out + 31) / 32 * 32) * (size_t)rp; }
 constexpr int kMaxPackSeg = 96;   // 40 bytes each in the kernel arguments; fewer, larger chunks: every
                                   // copy -> pack hand-over costs tens of microseconds of bubble
 struct PackBatch { PackSegment seg[kMaxPackSeg]; };
@@ -80,8 +91,37 @@ struct LoraGroup {
     bool fork;                   // write to old_base + at_old instead of in place (rp_old must be 0)
 };
 
-// Matrix-core path (default) and ordered-accumulation vector path.
-hipError_t launch_lora_mfma(const LoraGroup& g, hipStream_t stream);
+// How one group is launched: which kernel, its compile-time variant, the walk length and the grid.
+// Decided on the host by plan_lora_launch (plan.cpp, no HIP call), executed by the launchers below,
+// reported by tidal_lora_launch_info.
+enum LoraKernelKind {
+    kLoraNone = 0,        // nothing to do (no targets, both ranks 0)
+    kLoraMfmaReg = 1,     // lora_mfma_kernel: each wave keeps its A strip in registers
+    kLoraMfmaLds = 2,     // lora_mfma_lds_kernel: the four waves of a workgroup share one A strip in LDS
+    kLoraOrdered = 3      // lora_ordered_kernel: vector ALUs, k-ascending chain
+};
+struct LoraLaunchPlan {
+    int kind;
+    int ks_old, ks_new;          // padded ranks / 16: 0, 1, 2 or 4
+    bool pair;                   // delta tiles produced and consumed two at a time
+    bool fork;
+    int rc;                      // 32-row blocks one wave walks
+    int waves_per_simd;          // waves per SIMD the instantiation asks for in its launch bounds (at least)
+    int strips, rowblocks;       // 256-column strips and 32-row blocks of one slot
+    int blocks_per_target;       // workgroups per slot
+    int64_t total_blocks;        // workgroups of the launch (before rounding up to a multiple of 8)
+};
+LoraLaunchPlan plan_lora_launch(const LoraGroup& g, bool ordered);
+// Register-strip instantiations whose registers allow two waves per SIMD without spilling (found
+// by compiling), with the delta tiles two at a time: A strips of up to 32 ranks in all, and 32 old
+// + 16 new.  The kernel's launch bounds and the plan both use it.
+constexpr bool two_waves_fit(int ks0, int ks1) { return ks0 + ks1 <= 2 || (ks0 == 2 && ks1 == 1); }
+// Rank pairs the LDS-strip kernel is instantiated for.
+constexpr bool lds_kernel_exists(int ks0, int ks1) { return (ks0 == 4 || ks1 == 4) || (ks0 == 0 || ks1 == 0); }
+
+// Matrix-core path (default) and ordered-accumulation vector path; `plan` comes from plan_lora_launch.
+hipError_t launch_lora_mfma(const LoraGroup& g, const LoraLaunchPlan& plan, hipStream_t stream);
+hipError_t launch_lora_mfma_lds(const LoraGroup& g, const LoraLaunchPlan& plan, hipStream_t stream);
 hipError_t launch_lora_ordered(const LoraGroup& g, hipStream_t stream);
 
 // ---- materialisation with the adapter folded in --------------------------------------------
@@ -174,16 +214,18 @@ hipError_t launch_apply_shrink_short(const ApplyShortBatch& b, int in, hipStream
 hipError_t launch_apply_expand_short(const ApplyShortBatch& b, int max_out, hipStream_t stream);
 
 // Knobs for tuning runs (walk lengths, kernel variants).  They are read from the environment only
-// in builds made with -DTIDAL_TUNING_KNOBS (TIDAL_TUNING_KNOBS=1 python -m ...build --force); the
-// default build ignores the environment and has no code path that depends on it.
-inline const char* tuning_knob(const char* name) {
-#ifdef TIDAL_TUNING_KNOBS
-    return getenv(name);
-#else
-    (void)name;
-    return nullptr;
-#endif
-}
+// in builds made with -DTIDAL_TUNING_KNOBS (TIDAL_TUNING_KNOBS=1 python -m ...build --force), in
+// this one function (plan.cpp); the default build ignores the environment and every field is -1
+// ("no override").
+struct TuningKnobs {
+    int mfma_rc;        // TIDAL_MFMA_RC: 32-row blocks per wave walk
+    int mfma_lds;       // TIDAL_MFMA_LDS: 1 = LDS-strip kernel wherever it exists, 0 = never
+    int mfma_pair;      // TIDAL_MFMA_PAIR: delta tiles two at a time (1) or all live (0)
+    int mfma_order;     // TIDAL_MFMA_ORDER: workgroup -> tile order of the LDS-strip kernel
+    int mfma_dynlds;    // TIDAL_MFMA_DYNLDS: extra LDS bytes per workgroup (limits workgroups per CU)
+    int apply_ct;       // TIDAL_APPLY_CT: 32-token tiles per wave of the expand kernel
+};
+TuningKnobs tuning_knobs();
 
 inline int padded_rank(int r) { return r <= 0 ? 0 : (r <= 16 ? 16 : (r <= 32 ? 32 : 64)); }
 

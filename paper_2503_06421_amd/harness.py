@@ -89,13 +89,14 @@ def pinned_adapter(wl: wl_mod.Workload, adapter_id: int, rank: int | None = None
 
 
 def packed_adapter_bytes(wl: wl_mod.Workload, rank: int | None = None) -> int:
-    """Size of the packed device copy of one adapter: per target (in + out) x rp bf16, 256-B aligned."""
+    """Size of the packed device copy of one adapter: per target A transposed (in rounded up to 256
+    columns) and B (out rounded up to 32 rows), rp bf16 each, 256-B aligned."""
     r = wl.rank if rank is None else rank
     rp = 0 if r <= 0 else (16 if r <= 16 else (32 if r <= 32 else 64))
     total = 0
     for s in wl.lora_slots:
         t = wl.tensors[s]
-        total += -(-2 * t.cols * rp // 256) * 256 + -(-2 * t.rows * rp // 256) * 256
+        total += -(-2 * (-(-t.cols // 256) * 256) * rp // 256) * 256 + -(-2 * (-(-t.rows // 32) * 32) * rp // 256) * 256
     return total
 
 

@@ -73,7 +73,7 @@ def test_create_rejects_bad_arguments():
     _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, shapes, FAKE_ARENA + 8, need)
     _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, shapes, 0, need)
     _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, [(-1, 4)], FAKE_ARENA, need)
-    for bad in (tb.make_config(chunk_bytes=1024), tb.make_config(max_rank=65), tb.make_config(flags=128),
+    for bad in (tb.make_config(chunk_bytes=1024), tb.make_config(max_rank=65), tb.make_config(flags=256),
                 tb.make_config(chunk_bytes=1 << 20, coalesce_bytes=1 << 21)):
         _expect(tb.TIDAL_E_INVAL, tb.tidal_template_create, shapes, FAKE_ARENA, 1 << 40, bad)
         assert tb.tidal_template_required_bytes(shapes, bad) == 0
@@ -110,8 +110,9 @@ def test_validation_happens_before_any_device_work(small_template):
     _expect(tb.TIDAL_E_STATE, tb.tidal_lora_detach, t)
     _expect(tb.TIDAL_E_STATE, tb.tidal_lora_attach, t, [ok])
     _expect(tb.TIDAL_E_STATE, tb.tidal_template_slot_wait, t, 0)
-    # At (16 x 16) + Bp (8 x 16) + row-major A (2 x 16 -> one 256-byte unit)
-    assert tb.tidal_adapter_required_bytes(t, [ok]) == 2 * 16 * 16 + 2 * 8 * 16 + 256
+    # A transposed (16 columns padded to a strip of 256, 16 ranks) + B (8 rows padded to a block of 32)
+    # + row-major A (2 x 16 -> one 256-byte unit)
+    assert tb.tidal_adapter_required_bytes(t, [ok]) == 2 * 256 * 16 + 2 * 32 * 16 + 256
     assert tb.tidal_adapter_required_bytes(t, [(9,) + ok[1:]]) == 0
 
 
@@ -123,7 +124,7 @@ def test_adapter_too_large_for_region():
         A = np.zeros((4, 64), np.float32)
         B = np.zeros((64, 4), np.float32)
         # the size check comes after the materialised check, so look at the size directly
-        assert tb.tidal_adapter_required_bytes(t, [(0, 4, 8.0, tb.TIDAL_F32, A.ctypes.data, B.ctypes.data)]) == 4096 + 512
+        assert tb.tidal_adapter_required_bytes(t, [(0, 4, 8.0, tb.TIDAL_F32, A.ctypes.data, B.ctypes.data)]) == 2 * 256 * 16 + 2 * 64 * 16 + 512
     finally:
         tb.tidal_template_destroy(t)
 

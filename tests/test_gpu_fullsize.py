@@ -114,9 +114,13 @@ def test_llama2_7b_shaped_materialize_attach_swap(orc):
         check("swap", ads[0], ads[1])
         untouched()
         st = tb.tidal_get_stats(T)
-        assert st["lora_launches"] == 2 and st["rmw_elems"] == 2 * wl.lora_w_elements
-        # 101 chunks of 128 MiB for the stack; each adapter (16.8 MB of fp16 factors) is one more
-        assert st["chunks"] == -(-wl.source_bytes // (128 << 20)) + 2
+        # every targeted element was passed over exactly twice; attach and swap each upload and merge
+        # in a few groups of targets (one launch per group, all slots have one shape)
+        assert st["rmw_elems"] == 2 * wl.lora_w_elements
+        n_launch = st["lora_launches"]
+        assert 2 <= n_launch <= 16 and n_launch % 2 == 0
+        # 101 chunks of 128 MiB for the stack; each adapter (16.8 MB of fp16 factors) is one more per group
+        assert st["chunks"] == -(-wl.source_bytes // (128 << 20)) + n_launch
 
         # cold start again, adapter 0 folded into the load (re-materialising resets the template)
         tb.tidal_materialize_attach(T, [(i, wl.host_dtype, tb.host_ptr(v)) for i, v in enumerate(views)],
@@ -136,7 +140,7 @@ def test_llama2_7b_shaped_materialize_attach_swap(orc):
                 worst = max(worst, float(np.max(np.abs(g - w)) / np.max(np.abs(w))))
         print("fused cold start: %d bands checked, worst max-abs-err / max|W| = %.3g" % (len(prev), worst), flush=True)
         untouched()
-        assert tb.tidal_get_stats(T)["lora_launches"] == 2                     # no read-modify-write pass was added
+        assert tb.tidal_get_stats(T)["lora_launches"] == n_launch              # no read-modify-write pass was added
     finally:
         torch.cuda.synchronize()
         tb.tidal_template_destroy(T)

@@ -326,9 +326,9 @@ def test_every_rank_pair_fused_swap(orc, G, r_old, r_new):
 
 @pytest.mark.parametrize("flags", [ORDERED, 0], ids=["ordered", "mfma"])
 def test_pipelined_upload_gives_the_same_bits(G, flags):
-    """TIDAL_FLAG_PIPELINED_UPLOAD splits a large adapter's upload and merge into three groups of
-    targets on two streams; attach, swap (with slots only the old adapter touches) and detach must
-    give exactly what the single pass gives."""
+    """A large adapter's upload and merge may run in groups of targets on two streams (here forced
+    with TIDAL_FLAG_PIPELINED_UPLOAD; TIDAL_FLAG_SERIAL_UPLOAD: one stream, one pass); attach, swap
+    (with slots only the old adapter touches) and detach must give exactly what the single pass gives."""
     rng = np.random.default_rng(60)
     shapes = [(512, 1024)] * 26 + [(100, 130)]
     arrays = {i: rng.uniform(-0.05, 0.05, s).astype(np.float16) for i, s in enumerate(shapes)}
@@ -341,7 +341,7 @@ def test_pipelined_upload_gives_the_same_bits(G, flags):
     a0 = adapter(1, range(0, 27), 64)                      # 5.1 MB packed: enough to be pipelined
     a1 = adapter(2, range(3, 26), 64)                      # leaves slots 0-2 and 26 to the old adapter only
     res = []
-    for extra in (0, tb.TIDAL_FLAG_PIPELINED_UPLOAD):
+    for extra in (tb.TIDAL_FLAG_SERIAL_UPLOAD, tb.TIDAL_FLAG_PIPELINED_UPLOAD):
         with G.Template(shapes, max_adapter_bytes=8 << 20, flags=flags | extra) as T:
             T.materialize(arrays)
             T.attach(a0)
