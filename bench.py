@@ -147,41 +147,75 @@ def run_stack(tag, wl, args, pcie_peak, pool_limit, steps, warmup, with_swap, cp
                                                           "tensors mapped into it modulo its size" if pool.wrapped else "every tensor drawn"))
     ads = [hz.pinned_adapter(wl, a) for a in ((0, 1) if with_swap else (0,))]
     targets = [tb.targets_from_arrays(items) for items, _ in ads]
+    # Two templates over one arena: the plain one gives the call-level times (ms per invocation, materialise
+    # rate, wall time per step); the one with TIDAL_FLAG_KERNEL_TIMING gives the kernel durations -- its two
+    # event records around every launch would otherwise count as part of an invocation.
     T = hz.DeviceTemplate(wl.shapes, chunk_bytes=args.chunk_mib << 20, max_adapter_bytes=hz.packed_adapter_bytes(wl),
                           flags=tb.TIDAL_FLAG_KERNEL_TIMING)
+    Tp = hz.DeviceTemplate(wl.shapes, arena=T.arena, chunk_bytes=args.chunk_mib << 20, max_adapter_bytes=hz.packed_adapter_bytes(wl))
     srcs = pool.sources()
-    comp = T.compute_stream
     ev = lambda: torch.cuda.Event(enable_timing=True)
     rec = {"config": tag}
     try:
-        def step(e=None):
+        def step(tpl, e=None):
+            comp = tpl.compute_stream
             if e:
                 e[0].record(comp)
-            tb.tidal_materialize(T.h, srcs, T.copy_stream, comp)
+            tb.tidal_materialize(tpl.h, srcs, tpl.copy_stream, comp)
             if e:
                 e[1].record(comp)
-            tb.tidal_lora_attach(T.h, targets[0], comp)
+            tb.tidal_lora_attach(tpl.h, targets[0], comp)
             if e:
                 e[2].record(comp)
             if with_swap:
-                tb.tidal_lora_swap(T.h, targets[1], comp)
+                tb.tidal_lora_swap(tpl.h, targets[1], comp)
             if e:
                 e[3].record(comp)
 
-        for _ in range(warmup):
-            step()
+        # ---- call level (--kernel-level-only: skipped, so that a profile holds nothing but the kernel-level pass)
+        call_steps, call_warm = (0, 0) if args.kernel_level_only else (steps, warmup)
+        for _ in range(call_warm):
+            step(Tp)
+        Tp.sync()
+        evs = [[ev() for _ in range(4)] for _ in range(call_steps)]
+        t0 = time.perf_counter()
+        for k in range(call_steps):
+            step(Tp, evs[k])
+        Tp.sync()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / max(1, call_steps)
+        stp = tb.tidal_get_stats(Tp.h)
+        med = lambda x: float(np.median(x)) if x else float("nan")
+        mat_ms = med([e[0].elapsed_time(e[1]) for e in evs])
+        att_ms = med([e[1].elapsed_time(e[2]) for e in evs])
+        swp_ms = med([e[2].elapsed_time(e[3]) for e in evs]) if with_swap else None
+        n_calls = (call_steps + call_warm) * (2 if with_swap else 1)
+        launches_per_call = stp["lora_launches"] / max(1, n_calls)
+        # ---- kernel level: the same rows of the path with the adapter uploaded first and merged afterwards by one
+        # launch per shape (tidal_adapter_upload + tidal_lora_attach_adapter), so that the read-modify-write kernel
+        # runs with nothing else on the GPU and its duration, bracketed by the library's events, is its own.  (In the
+        # pipelined call above its launches are cut into groups and share HBM with the copy engine and the pack kernel.)
+        comp = T.compute_stream
+        amem = [torch.empty(tb.tidal_adapter_required_bytes(T.h, t_), dtype=torch.uint8, device="cuda:0") for t_ in targets]
+        live = []
+
+        def kstep():
+            tb.tidal_materialize(T.h, srcs, T.copy_stream, comp)          # resets the template: nothing attached afterwards
+            for h in live:
+                tb.tidal_adapter_destroy(h)
+            live.clear()
+            live.append(tb.tidal_adapter_upload(T.h, targets[0], amem[0], amem[0].numel(), comp))
+            tb.tidal_lora_attach_adapter(T.h, live[0], comp)
+            if with_swap:
+                live.append(tb.tidal_adapter_upload(T.h, targets[1], amem[1], amem[1].numel(), comp))
+                tb.tidal_lora_swap_adapter(T.h, live[1], comp)
+
+        kstep()
         T.sync()
         tb.tidal_reset_stats(T.h)
-        evs = [[ev() for _ in range(4)] for _ in range(steps)]
-        t0 = time.perf_counter()
         for k in range(steps):
-            step(evs[k])
+            kstep()
         T.sync()
-        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
         st = tb.tidal_get_stats(T.h)
-        mat_ms = float(np.median([e[0].elapsed_time(e[1]) for e in evs]))
-        att_ms = float(np.median([e[1].elapsed_time(e[2]) for e in evs]))
-        swp_ms = float(np.median([e[2].elapsed_time(e[3]) for e in evs])) if with_swap else None
 
         fb = factor_bytes(wl, wl.lora_slots, wl.rank)
         attach_bytes = 4 * wl.lora_w_elements + fb
@@ -192,12 +226,11 @@ def run_stack(tag, wl, args, pcie_peak, pool_limit, steps, warmup, with_swap, cp
         gbps = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         mat_gbps = wl.source_bytes / (mat_ms * 1e-3) / 1e9
 
-        # ---- keep-alive regime: the same passes back to back (detach, attach, ...), kernels only
-        state_before_warm = None
+        # ---- keep-alive regime: the adapter stays resident, detach / attach back to back, kernels only
         tb.tidal_reset_stats(T.h)
         for _ in range(2):
             tb.tidal_lora_detach(T.h, comp)
-            tb.tidal_lora_attach(T.h, targets[-1], comp)
+            tb.tidal_lora_attach_adapter(T.h, live[-1], comp)
         T.sync()
         stw = tb.tidal_get_stats(T.h)
         warm_ms = stw["lora_kernel_ms"] / max(1, stw["lora_launches"])
@@ -213,16 +246,18 @@ def run_stack(tag, wl, args, pcie_peak, pool_limit, steps, warmup, with_swap, cp
             "steps": steps, "ms_per_step": round(wall_ms, 3),
             "materialize": {"value": round(mat_gbps, 2), "unit": "GB/s (source bytes over PCIe, H2D+convert)", "ms": round(mat_ms, 2),
                             "h2d_peak_measured": round(pcie_peak, 2), "frac_of_measured_peak": round(mat_gbps / pcie_peak, 4),
-                            "chunks_per_step": st["chunks"] // max(1, steps), "h2d_copies_per_step": st["h2d_copies"] // max(1, steps),
+                            "chunks_per_step": stp["chunks"] // max(1, call_steps + call_warm), "h2d_copies_per_step": stp["h2d_copies"] // max(1, call_steps + call_warm),
                             "convert_kernel_ms_per_step": round(st["convert_kernel_ms"] / max(1, steps), 3)},
             "lora": {"attach_ms_per_invocation": round(att_ms, 4),
                      "swap_ms_per_invocation": round(swp_ms, 4) if swp_ms is not None else None,
-                     "note": "per-invocation times include the adapter's upload over PCIe and its packing (overlapped with the merge in groups of targets)",
-                     "kernel_ms_per_invocation": round(st["lora_kernel_ms"] / (steps * (2 if with_swap else 1)), 4),
-                     "launches_per_invocation": launches / (steps * (2 if with_swap else 1)),
+                     "note": "tidal_lora_attach / _swap with host pointers: per-invocation times include the adapter's upload over PCIe "
+                             "and its packing, overlapped with the merge in groups of targets (launches_per_invocation)",
+                     "launches_per_invocation": launches_per_call,
+                     "kernel_ms_per_invocation_alone": round(st["lora_kernel_ms"] / (steps * (2 if with_swap else 1)), 4),
                      "keep_alive_kernel_GBps": round(warm_gbps, 1), "keep_alive_frac_of_hbm_peak": round(warm_gbps / HBM_PEAK_GBPS, 4),
-                     "keep_alive_note": "detach / attach issued back to back after the steps (the kept-alive function of Sec. 5.2): the "
-                                        "first pass after a load or an idle gap runs a few percent slower than the ones that follow"},
+                     "keep_alive_note": "the same adapter resident in HBM, detach / attach issued back to back after the steps (the kept-alive "
+                                        "function of Sec. 5.2): one launch per shape, nothing crossing the link; the first pass after a load or "
+                                        "an idle gap also runs a few percent slower than the ones that follow"},
             "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(traffic_key),
                          "kernel": info["kernel"], "avg_launch_ms": round(avg_ms, 4), "launches": launches,
@@ -282,8 +317,11 @@ def run_stack(tag, wl, args, pcie_peak, pool_limit, steps, warmup, with_swap, cp
         else:
             rec["cpu_baseline"], rec["parity"] = None, None
     finally:
-        T.close()
-    del pool, T
+        torch.cuda.synchronize()
+        tb.tidal_template_destroy(T.h)           # the resident adapter is still attached: the template goes first
+        T.h = None
+        Tp.close()
+    del pool, T, Tp
     torch.cuda.empty_cache()
     return rec
 
@@ -493,6 +531,9 @@ def main() -> int:
     ap.add_argument("--chunk-mib", type=int, default=128)
     ap.add_argument("--pool-gib", type=float, default=8.0, help="pinned host pool the 70B- and 13B-shaped stacks are mapped into")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle baseline of the headline workload (a third of it for each other one); 0 = skip")
+    ap.add_argument("--kernel-level-only", action="store_true",
+                    help="skip the call-level pass of the stack workloads (their per-invocation figures are then NaN): for "
+                         "profiling runs whose counters should cover the kernel-level pass and nothing else")
     ap.add_argument("--only", default="", help="comma-separated subset of 70b,single,7b,13b,churn (the headline needs 70b)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

@@ -92,11 +92,8 @@ enum {
     /* Bracket every convert and LoRA kernel launch with timing events on its stream and add
      * the elapsed times to tidal_stats (tidal_get_stats then waits for those kernels).          */
     TIDAL_FLAG_KERNEL_TIMING = 8,
-    /* tidal_materialize enqueues every chunk without waiting.  By default the calling thread
-     * stays at most two chunks ahead of the GPU (it blocks inside the call for most of the
-     * transfer, like a template-server thread would), because a deep queue of cross-stream
-     * waits makes every copy slower; with this flag the call returns as soon as everything is
-     * enqueued, at a lower transfer rate for large jobs.                                      */
+    /* tidal_materialize enqueues every chunk without waiting, however many there are (by default
+     * only a load of up to tidal_config.chunks_ahead chunks is enqueued that way).             */
     TIDAL_FLAG_ASYNC_ENQUEUE = 16,
     /* Issue one hipMemcpyAsync per planned piece: neighbouring pieces are not merged into one
      * copy and tiny tensors are not gathered by the CPU.  For measuring what tensor merging
@@ -129,6 +126,12 @@ typedef struct {
     int32_t gather_threads;    /* host threads that copy pageable sources into the pinned buffer
                                   (pieces of 8 MiB or more are split among them); 0 = 4, at most
                                   16.  One thread moves about half of what the link carries.     */
+    int32_t chunks_ahead;      /* tidal_materialize enqueues a load of up to this many staged chunks
+                                  in one burst and returns; in a longer load the calling thread
+                                  stays two chunks ahead of the GPU until only this many remain
+                                  (many hundreds of queued cross-stream waits slow every copy
+                                  down, small chunks sooner than large ones).  0 = chunk_bytes /
+                                  512 KiB, within 16..256 (256 for 128 MiB chunks); at most 4096. */
 } tidal_config;
 
 /* One planned host->device copy unit, as tidal_materialize would issue it (introspection). */
@@ -180,8 +183,8 @@ int tidal_template_create(const tidal_slot_desc* slots /* [host] copied */, int3
  * hipMemcpyAsync on copy_stream into one of two device staging buffers -> conversion to
  * bf16 (round to nearest even, subnormals kept, NaN quieted) into the slot on
  * compute_stream; bf16 sources are copied straight into the slot.  Small tensors are
- * gathered into one copy (Sec. 6, tensor merging).  On return all work is enqueued (the
- * call itself paces the enqueue, see TIDAL_FLAG_ASYNC_ENQUEUE); completion of
+ * gathered into one copy (Sec. 6, tensor merging).  On return all work is enqueued (a
+ * load of more than tidal_config.chunks_ahead chunks paces the first part of it inside the call); completion of
  * compute_stream implies completion of the whole call.  If an adapter is
  * attached, the sources must cover every slot it touches (then the template is pristine
  * again and nothing is attached), else TIDAL_E_STATE.  A slot may appear at most once. */

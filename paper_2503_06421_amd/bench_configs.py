@@ -381,7 +381,7 @@ def bench_overlap(args):
     C ~ max(load, compute) + first slot, D ~ load + compute, E ~ compute."""
     wl = wl_mod.llama2_7b()
     pool = hz.HostPool(wl, limit_bytes=2 << 30)
-    T = hz.DeviceTemplate(wl.shapes, flags=tb.TIDAL_FLAG_SLOT_EVENTS | tb.TIDAL_FLAG_ASYNC_ENQUEUE)
+    T = hz.DeviceTemplate(wl.shapes, flags=tb.TIDAL_FLAG_SLOT_EVENTS)
     consumer = torch.cuda.Stream()
     n = len(wl.shapes)
     sums = torch.zeros(n, dtype=torch.int64, device="cuda:0")

@@ -59,7 +59,8 @@ class tidal_lora_segment(Structure):
 
 class tidal_config(Structure):
     _fields_ = [("chunk_bytes", c_size_t), ("max_rank", c_int32), ("max_adapter_bytes", c_size_t),
-                ("flags", c_int32), ("coalesce_bytes", c_size_t), ("gather_threads", c_int32)]
+                ("flags", c_int32), ("coalesce_bytes", c_size_t), ("gather_threads", c_int32),
+                ("chunks_ahead", c_int32)]
 
 
 class tidal_copy_piece(Structure):
@@ -234,8 +235,9 @@ def _target_array(targets):
     return arr, len(targets)
 
 
-def make_config(chunk_bytes=0, max_rank=0, max_adapter_bytes=0, flags=0, coalesce_bytes=0, gather_threads=0) -> tidal_config:
-    return tidal_config(chunk_bytes, max_rank, max_adapter_bytes, flags, coalesce_bytes, gather_threads)
+def make_config(chunk_bytes=0, max_rank=0, max_adapter_bytes=0, flags=0, coalesce_bytes=0, gather_threads=0,
+                chunks_ahead=0) -> tidal_config:
+    return tidal_config(chunk_bytes, max_rank, max_adapter_bytes, flags, coalesce_bytes, gather_threads, chunks_ahead)
 
 
 def sources_from_arrays(arrays: dict):

@@ -147,7 +147,8 @@ struct tidal_template {
     hipEvent_t ev_start = nullptr, ev_copy_done = nullptr;
     std::vector<StreamMark> marks;
     hipStream_t up_stream = nullptr;                   // library-owned: adapter uploads that overlap the merge
-    hipEvent_t ev_up_begin = nullptr;
+    hipStream_t pack_stream = nullptr;                 // library-owned: packs each uploaded group beside the merges
+    hipEvent_t ev_up_begin = nullptr, ev_group_packed[kMaxUploadGroups] = {};
     RateModel rates;
     char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
     bool bounce_used[2] = {false, false};
@@ -222,7 +223,9 @@ static int ensure_bounce(tidal_template* t, int b) {
 static int ensure_upload_stream(tidal_template* t) {
     if (t->up_stream) return TIDAL_OK;
     HIP_TRY(hipStreamCreateWithFlags(&t->up_stream, hipStreamNonBlocking));      // default priority
+    HIP_TRY(hipStreamCreateWithFlags(&t->pack_stream, hipStreamNonBlocking));    // default priority
     HIP_TRY(hipEventCreateWithFlags(&t->ev_up_begin, hipEventDisableTiming));
+    for (int g = 0; g < kMaxUploadGroups; ++g) HIP_TRY(hipEventCreateWithFlags(&t->ev_group_packed[g], hipEventDisableTiming));
     for (int k = 0; k < 4; ++k) HIP_TRY(hipEventCreate(&t->rates.ev[k]));
     return TIDAL_OK;
 }
@@ -450,7 +453,7 @@ struct Pipeline {
     bool kernel_copy = false;
     CopyBatch kbatch;
     int kruns = 0;
-    bool paced = true;              // the host stays at most two chunks ahead of the GPU (see acquire)
+    int64_t paced_chunks = 0;       // staged chunks still to come for which the host stays two ahead of the GPU (see acquire)
 
     int flush_kernel_copies() {
         if (kruns == 0) return TIDAL_OK;
@@ -517,12 +520,14 @@ struct Pipeline {
             if (t->bounce_used[b]) HIP_TRY(hipEventSynchronize(t->bounce_free[b]));
         }
         if (need_staging) {
-            // Host-side pacing: stay at most two chunks ahead of the GPU.  Hundreds of queued
-            // cross-stream waits slow every copy down (measured: 42 instead of 55 GB/s for 402
-            // chunks), a shallow queue does not.
-            if (paced && !(t->cfg.flags & TIDAL_FLAG_ASYNC_ENQUEUE) && t->staging_rec[b])
-                HIP_TRY(hipEventSynchronize(t->staging_free[b]));
-            HIP_TRY(hipStreamWaitEvent(copy, t->staging_free[b], 0));
+            // Host-side pacing.  Enqueued in one burst, a load of a few hundred chunks runs as fast
+            // as one whose caller stays two chunks ahead of the GPU; many more queued cross-stream
+            // waits, or a host that trails the GPU by more than a few chunks while it enqueues,
+            // slow every copy down (measured: 8 chunks ahead -5 %, 32 ahead -12 %).  So: two
+            // chunks ahead until at most chunks_ahead chunks remain, the rest in one burst.
+            if (paced_chunks > 0 && t->staging_rec[b]) HIP_TRY(hipEventSynchronize(t->staging_free[b]));
+            if (paced_chunks > 0) --paced_chunks;
+            if (t->staging_rec[b]) HIP_TRY(hipStreamWaitEvent(copy, t->staging_free[b], 0));
         }
         return TIDAL_OK;
     }
@@ -577,6 +582,16 @@ static int materialize_impl(tidal_template* t, std::vector<SourceInfo>& infos, b
     plan_copies(infos, t->cfg, kMaxConvertSeg, &plan);
 
     Pipeline pl{t, (hipStream_t)copy_stream, (hipStream_t)compute_stream};
+    if (!(t->cfg.flags & TIDAL_FLAG_ASYNC_ENQUEUE)) {
+        int64_t staged_chunks = 0;
+        int32_t last = -1;
+        for (const Piece& p : plan)
+            if (p.staged && p.chunk != last) {
+                ++staged_chunks;
+                last = p.chunk;
+            }
+        pl.paced_chunks = std::max<int64_t>(0, staged_chunks - t->cfg.chunks_ahead);
+    }
     // LoRA kernels of this template may have run on another stream: order after them
     rc = wait_marks(t, kMarkLora, pl.compute);
     if (rc) return rc;
@@ -807,7 +822,6 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
 
     Pipeline pl{t, copy, pack};
     pl.kernel_copy = true;
-    pl.paced = false;               // a handful of chunks: the host never waits for the GPU here
     size_t i = 0;
     int chunk = chunk_io ? *chunk_io : 0;
     while (i < jobs.size()) {
@@ -1067,7 +1081,7 @@ static void set_attached(tidal_template* t, const AdapterRec& rec, tidal_adapter
 
 // Rates the grouping of a pipelined attach is sized from.  They start at typical values and are
 // replaced by what the library measures with its own events on a pipelined call: the link rate from
-// the upload stream (first copy to last copy), the in-place pass rate from the last group's launches.
+// the first group's copies (alone on their stream), the in-place pass rate from the last group's launches.
 static void rates_update(tidal_template* t) {
     RateModel& r = t->rates;
     if (!r.pending) return;
@@ -1076,7 +1090,8 @@ static void rates_update(tidal_template* t) {
         return;
     }
     float up_ms = 0.f, rmw_ms = 0.f;
-    if (hipEventElapsedTime(&up_ms, r.ev[0], r.ev[1]) == hipSuccess && up_ms > 1e-3f && r.up_bytes > 0.0)
+    // copies of a few megabytes and more run at the link's rate; smaller ones measure latency: keep the estimate then
+    if (hipEventElapsedTime(&up_ms, r.ev[0], r.ev[1]) == hipSuccess && up_ms > 1e-3f && r.up_bytes >= 4.0e6)
         r.link_bytes_per_ms = r.up_bytes / up_ms;
     if (hipEventElapsedTime(&rmw_ms, r.ev[2], r.ev[3]) == hipSuccess && rmw_ms > 1e-3f && r.rmw_bytes > 0.0)
         r.rmw_bytes_per_ms = r.rmw_bytes / rmw_ms;
@@ -1093,7 +1108,7 @@ static void rates_update(tidal_template* t) {
 static void plan_upload_groups(const tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec,
                                const AdapterRec* old, std::vector<std::pair<size_t, size_t>>* groups) {
     constexpr size_t kPipelineFrom = (size_t)4 << 20;
-    constexpr double kLaunchMs = 0.012;            // bubble and tail of one more launch
+    constexpr double kLaunchMs = 0.03;             // what one more launch costs: its bubble, its ramp and tail, an event wait
     const size_t n = rec.targets.size();
     groups->clear();
     groups->push_back({0, n});
@@ -1130,25 +1145,46 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
     // a single group (serial) is the candidate to beat, unless grouping is forced
     double best = forced ? 1e300 : u_total + m_total + kLaunchMs * launches(0, n);
     std::vector<std::pair<size_t, size_t>> best_groups = *groups;
-    for (size_t first = 1; first < n; ++first) {
-        std::vector<std::pair<size_t, size_t>> cand;
-        size_t a = 0, b = first;
-        double up_done = 0.0, merge_done = 0.0;
-        while (a < n) {
-            if ((int)cand.size() == kMaxUploadGroups - 1) b = n;        // the last group takes the rest
-            double ug = 0.0, mg = 0.0;
-            for (size_t i = a; i < b; ++i) { ug += u[i]; mg += m[i]; }
-            up_done += ug;
-            merge_done = std::max(merge_done, up_done) + mg + kLaunchMs * (1 + launches(a, b));    // pack + merges
-            cand.push_back({a, b});
-            // next group: what crosses the link while this one is merged
-            a = b;
-            double budget = mg, acc = 0.0;
-            while (b < n && (acc + u[b] <= budget || b == a)) acc += u[b++];
-        }
-        if (merge_done < best) {
-            best = merge_done;
-            best_groups = cand;
+    // Candidates: G groups whose shares of the upload grow by a factor q from one to the next
+    // (q = 1: equal groups, what an upload-bound adapter wants; q > 1: a small first group, so that
+    // merging starts early, and large later ones that hide under the merges before them).  Each is
+    // simulated on three resources -- the link, the packing stream, the caller's stream -- and the
+    // one that ends first is taken.
+    const double pack_rate = 1.0e9;                                      // bytes per ms through the pack kernel
+    static const double kGrowth[] = {1.0, 1.5, 2.0, 3.0};
+    static const double kFirst[] = {1.0, 0.35};                           // the first group may be smaller still
+    for (int G = 2; G <= kMaxUploadGroups && (size_t)G <= n; ++G) {
+        for (int v = 0; v < 8; ++v) {
+            const double q = kGrowth[v & 3], f0 = kFirst[v >> 2];
+            double norm = 0.0, w = 1.0;
+            for (int g = 0; g < G; ++g) { norm += g ? w : f0; w *= q; }
+            std::vector<std::pair<size_t, size_t>> cand;
+            size_t a0 = 0;
+            double share = 0.0, acc = 0.0;
+            w = 1.0;
+            for (int g = 0; g < G; ++g) {
+                share += (g ? w : f0) / norm;
+                w *= q;
+                size_t b0 = a0;
+                while (b0 < n && (acc + u[b0] <= share * u_total + 1e-12 || b0 == a0)) acc += u[b0++];
+                if (g == G - 1) b0 = n;
+                if (b0 > a0) cand.push_back({a0, b0});
+                a0 = b0;
+                if (a0 >= n) break;
+            }
+            if (cand.size() < 2) continue;
+            double copy_done = 0.0, pack_done = 0.0, merge_done = 0.0;
+            for (const auto& gr : cand) {
+                double ug = 0.0, mg = 0.0;
+                for (size_t i = gr.first; i < gr.second; ++i) { ug += u[i]; mg += m[i]; }
+                copy_done += ug;
+                pack_done = std::max(pack_done, copy_done) + kLaunchMs + 2.0 * ug * t->rates.link_bytes_per_ms / pack_rate;
+                merge_done = std::max(merge_done, pack_done) + mg + kLaunchMs * launches(gr.first, gr.second);
+            }
+            if (merge_done < best) {
+                best = merge_done;
+                best_groups = cand;
+            }
         }
     }
     *groups = best_groups;
@@ -1188,15 +1224,30 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
         // the staging buffers and the region to be written were last used by work on the caller's stream
         HIP_TRY(hipEventRecord(t->ev_up_begin, (hipStream_t)stream));
         HIP_TRY(hipStreamWaitEvent(t->up_stream, t->ev_up_begin, 0));
+        HIP_TRY(hipStreamWaitEvent(t->pack_stream, t->ev_up_begin, 0));
         const bool calibrate = !t->rates.pending;
-        if (calibrate) HIP_TRY(hipEventRecord(t->rates.ev[0], t->up_stream));
         std::vector<char> in_new(t->slots.size(), 0);
         for (const PackedTarget& p : rec.targets) in_new[p.slot] = 1;
         int chunk = 0;
-        double up_bytes = 0.0;
         for (size_t g = 0; g < groups.size(); ++g) {
-            rc = upload_adapter(t, tg, rec, t->up_stream, (hipStream_t)stream, groups[g].first, groups[g].second, &chunk);
+            // copies on one stream, packing on a second, merges on the caller's: the copy engine never waits
+            // for a kernel, and the caller's stream carries nothing but the merges.  The first group's copies,
+            // bracketed by two events, give the link rate (nothing else is in flight on that stream then).
+            if (g == 0 && calibrate) HIP_TRY(hipEventRecord(t->rates.ev[0], t->up_stream));
+            rc = upload_adapter(t, tg, rec, t->up_stream, t->pack_stream, groups[g].first, groups[g].second, &chunk);
             if (rc) return rc;
+            if (g == 0 && calibrate) {
+                HIP_TRY(hipEventRecord(t->rates.ev[1], t->up_stream));
+                double up_bytes = 0.0;
+                for (size_t i = groups[0].first; i < groups[0].second; ++i) {
+                    const PackedTarget& p = rec.targets[i];
+                    const SlotState& sl = t->slots[p.slot];
+                    if (p.active() && sl.elems > 0) up_bytes += (double)p.r * (double)(sl.rows + sl.cols) * (double)dtype_size(tg[i].dtype);
+                }
+                t->rates.up_bytes = up_bytes;
+            }
+            HIP_TRY(hipEventRecord(t->ev_group_packed[g], t->pack_stream));
+            HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, t->ev_group_packed[g], 0));
             AdapterRec part_new, part_old;
             part_new.dev = rec.dev;
             part_new.targets.assign(rec.targets.begin() + groups[g].first, rec.targets.begin() + groups[g].second);
@@ -1208,21 +1259,12 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
                     if (here[p.slot] || (g + 1 == groups.size() && !in_new[p.slot])) part_old.targets.push_back(p);
             }
             const bool last = g + 1 == groups.size();
-            if (last && calibrate) {
-                HIP_TRY(hipEventRecord(t->rates.ev[1], t->up_stream));          // every copy has been issued by now
-                HIP_TRY(hipEventRecord(t->rates.ev[2], (hipStream_t)stream));   // after the last pack, before the last merge
-            }
+            if (last && calibrate) HIP_TRY(hipEventRecord(t->rates.ev[2], (hipStream_t)stream));   // behind the wait for the last pack
             const uint64_t before = t->stats.rmw_elems;
             rc = do_swap_launch(t, swap ? &part_old : nullptr, &part_new, (hipStream_t)stream);
             if (rc) return rc;
             if (last && calibrate) {
                 HIP_TRY(hipEventRecord(t->rates.ev[3], (hipStream_t)stream));
-                for (size_t i = 0; i < rec.targets.size(); ++i) {
-                    const PackedTarget& p = rec.targets[i];
-                    const SlotState& sl = t->slots[p.slot];
-                    if (p.active() && sl.elems > 0) up_bytes += (double)p.r * (double)(sl.rows + sl.cols) * (double)dtype_size(tg[i].dtype);
-                }
-                t->rates.up_bytes = up_bytes;
                 t->rates.rmw_bytes = 4.0 * (double)(t->stats.rmw_elems - before);
                 t->rates.pending = true;
             }
@@ -1877,6 +1919,9 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
         }
         if (t->up_stream) {
             (void)hipStreamSynchronize(t->up_stream);
+            (void)hipStreamSynchronize(t->pack_stream);
+            (void)hipStreamDestroy(t->pack_stream);
+            for (int g = 0; g < kMaxUploadGroups; ++g) (void)hipEventDestroy(t->ev_group_packed[g]);
             (void)hipEventDestroy(t->ev_up_begin);
             for (int k = 0; k < 4; ++k) (void)hipEventDestroy(t->rates.ev[k]);
             (void)hipStreamDestroy(t->up_stream);

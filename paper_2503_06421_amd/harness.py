@@ -103,12 +103,16 @@ def packed_adapter_bytes(wl: wl_mod.Workload, rank: int | None = None) -> int:
 class DeviceTemplate:
     """Template over a torch-allocated arena, with its two streams."""
 
-    def __init__(self, shapes, **cfg):
+    def __init__(self, shapes, arena=None, **cfg):
+        """arena: reuse another template's device memory (same shapes and sizes in cfg; one of the
+        two templates is in use at a time), else a new allocation."""
         self.cfg = tb.make_config(**cfg)
         self.need = tb.tidal_template_required_bytes(shapes, self.cfg)
         if self.need == 0:
             raise ValueError("invalid template configuration")
-        self.arena = torch.empty(self.need, dtype=torch.uint8, device="cuda:0")
+        if arena is not None and arena.numel() < self.need:
+            raise ValueError("shared arena too small")
+        self.arena = arena if arena is not None else torch.empty(self.need, dtype=torch.uint8, device="cuda:0")
         self.h = tb.tidal_template_create(shapes, self.arena, self.need, self.cfg)
         self.copy_stream = torch.cuda.Stream()
         self.compute_stream = torch.cuda.Stream()

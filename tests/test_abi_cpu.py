@@ -312,6 +312,14 @@ def test_gather_threads_default_and_range():
     assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(gather_threads=-1)) == 0
 
 
+def test_chunks_ahead_default_and_range():
+    assert tb.tidal_config_default().chunks_ahead == 256                      # 128 MiB chunks
+    for kw in (dict(chunks_ahead=1), dict(chunks_ahead=4096), dict(chunk_bytes=1 << 20)):
+        assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(**kw)) > 0
+    assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(chunks_ahead=4097)) == 0
+    assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(chunks_ahead=-1)) == 0
+
+
 def test_header_is_plain_c_and_links_from_c(tmp_path):
     """The boundary is a C ABI: the header must compile as C99 (and C++), and a C program must
     link against the library and call a host-only entry point."""

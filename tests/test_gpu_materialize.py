@@ -226,3 +226,39 @@ def test_lora_on_another_stream_waits_for_the_materialisation(orc, G):
                 want = merged[i].copy()
                 orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 16.0, -1)
             assert np.array_equal(T.slot(i), want), i
+
+
+@pytest.mark.parametrize("ahead", [1, 3, 7, 4096])
+def test_every_pacing_depth_gives_the_same_slots(orc, G, ahead):
+    """A load of a few dozen chunks with the host two chunks ahead for all of it, for part of it, and
+    enqueued in one burst: same bits as the oracle's conversion every time (twice in a row, so the
+    second load's copies meet the first one's staging events)."""
+    rng = np.random.default_rng(50 + ahead)
+    shapes = [(96, 1024), (33, 517), (256, 1024), (1, 7), (128, 2048)]
+    with G.Template(shapes, chunk_bytes=64 << 10, chunks_ahead=ahead) as T:
+        for rep in range(2):
+            arrays = {i: rng.normal(0, 1.0, s).astype(np.float32 if i % 2 else np.float16) for i, s in enumerate(shapes)}
+            T.arena.fill_(0x5A)
+            T.materialize(arrays, sync=False)
+            T.sync()
+            assert tb.tidal_get_stats(T.h)["chunks"] >= 20 * (rep + 1)
+            _compare_all_slots(orc, T, shapes, arrays)
+
+
+def test_a_load_within_the_burst_budget_returns_before_it_is_done(G):
+    """1.5 GiB of pinned fp16 in 128 MiB chunks (12 chunks, default budget 256): the call only
+    enqueues, so it is back long before the ~27 ms the link needs."""
+    import time
+    n = 3
+    shapes = [(8192, 32768)] * n
+    with G.Template(shapes) as T:
+        keep = [torch.zeros(shapes[0], dtype=torch.float16).pin_memory() for _ in range(n)]
+        srcs = [(i, tb.TIDAL_F16, k.data_ptr()) for i, k in enumerate(keep)]
+        tb.tidal_materialize(T.h, srcs, T.copy_stream, T.compute_stream)      # first call: buffers, events
+        T.sync()
+        t0 = time.perf_counter()
+        tb.tidal_materialize(T.h, srcs, T.copy_stream, T.compute_stream)
+        t1 = time.perf_counter()
+        T.sync()
+        t2 = time.perf_counter()
+        assert (t1 - t0) < 0.5 * (t2 - t0), "call %.2f ms of %.2f ms" % ((t1 - t0) * 1e3, (t2 - t0) * 1e3)
