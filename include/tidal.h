@@ -48,6 +48,9 @@ typedef struct tidal_template tidal_template;   /* opaque, freed by tidal_templa
 typedef struct tidal_adapter tidal_adapter;     /* opaque, freed by tidal_adapter_destroy  */
 typedef struct tidal_fork tidal_fork;           /* opaque, freed by tidal_fork_destroy     */
 
+/* Element types of host sources and LoRA factors.  Structs and calls carry the value in an int32_t
+ * field or argument: the width of a C enum is the compiler's choice, that of int32_t is not, and the
+ * records are filled in from other languages through this ABI. */
 typedef enum { TIDAL_F32 = 0, TIDAL_F16 = 1, TIDAL_BF16 = 2 } tidal_dtype;
 
 typedef enum {
@@ -63,7 +66,7 @@ typedef enum {
 typedef struct { int64_t rows, cols; } tidal_slot_desc;
 
 /* One tensor to materialise: rows*cols elements of `dtype` at `host`, row-major, dense. */
-typedef struct { int32_t slot; int32_t dtype; const void* host; /* [host] borrowed */ } tidal_src;
+typedef struct { int32_t slot; int32_t dtype /* a tidal_dtype value */; const void* host; /* [host] borrowed */ } tidal_src;
 
 /* One LoRA target: slot W (out x in) gets W + (alpha/r) * B * A with A (r x in) and
  * B (out x r), row-major, dense, both of `dtype`.  r == 0 or alpha == 0 is valid and
@@ -74,7 +77,7 @@ typedef struct {
     int32_t slot;
     int32_t r;
     float alpha;
-    int32_t dtype;
+    int32_t dtype;        /* a tidal_dtype value */
     const void* A;        /* [host] borrowed */
     const void* B;        /* [host] borrowed */
 } tidal_lora_target;
@@ -254,7 +257,9 @@ int tidal_lora_launch_info(const tidal_template* t, int64_t out, int64_t in, int
  * path of Sec. 5.2 run backwards, leaving only the static state. */
 int tidal_lora_detach(tidal_template* t, void* stream);
 
-/* Resident adapters: the packed bf16 device copy lives in caller-owned device memory, so
+/* Resident adapters (Sec. 5.2, adaptive template state reusing: a kept-alive function holds on to
+ * dynamic state that later invocations are likely to need again, so that only what differs is loaded):
+ * the packed bf16 device copy lives in caller-owned device memory, so
  * attach / swap move no host data (multi-tenant pools of adapters kept on the GPU).  A resident
  * adapter holds, per target, A transposed (in x rp) and B (out x rp), zero padded to
  * rp = 16, 32 or 64 ranks, plus A row-major (r x in) for tidal_lora_apply; the in-arena copy of
@@ -267,6 +272,8 @@ int tidal_adapter_upload(tidal_template* t, const tidal_lora_target* targets /* 
                          until tidal_adapter_destroy */, size_t dev_bytes, void* stream,
                          tidal_adapter** out /* [host] out */);
 int tidal_adapter_destroy(tidal_adapter* a);   /* must not be attached */
+/* tidal_lora_attach / tidal_lora_swap (Sec. 5.2: the invocation's dynamic weights replace the previous
+ * invocation's) with an adapter that is already on the device: the same passes over W, no host data. */
 int tidal_lora_attach_adapter(tidal_template* t, const tidal_adapter* a, void* stream);
 int tidal_lora_swap_adapter(tidal_template* t, const tidal_adapter* a_new, void* stream);
 
@@ -349,7 +356,8 @@ int tidal_fork_slot_ptr(const tidal_fork* f, int32_t slot, void** dev_ptr /* [ho
                         size_t* bytes /* [host] out, may be NULL */);
 int tidal_fork_destroy(tidal_fork* f);
 
-/* Device address and byte length (2*rows*cols) of a slot. */
+/* Device address and byte length (2*rows*cols) of a slot: where the inference kernels find the
+ * weight (Sec. 4.2: the template fixes each tensor's place in device memory ahead of the load). */
 int tidal_template_slot_ptr(const tidal_template* t, int32_t slot, void** dev_ptr /* [host] out */,
                             size_t* bytes /* [host] out, may be NULL */);
 
@@ -402,13 +410,14 @@ int tidal_hbm_rmw_peak(void* dev /* [device] in/out */, int64_t rows, int64_t co
 int tidal_get_stats(tidal_template* t, tidal_stats* out /* [host] out */);
 int tidal_reset_stats(tidal_template* t);
 
-/* Block until every materialisation, adapter upload, LoRA attach / swap / detach and fork apply
- * this template enqueued has completed.  tidal_lora_apply, tidal_slot_checksum and
+/* The host-side counterpart of the per-tensor synchronisation of Sec. 5.2, for callers that want the
+ * whole template rather than one slot: block until every materialisation, adapter upload, LoRA
+ * attach / swap / detach and fork apply this template enqueued has completed.  tidal_lora_apply, tidal_slot_checksum and
  * tidal_convert_device only enqueue kernels on the caller's stream and complete with it. */
 int tidal_template_sync(tidal_template* t);
 
-/* Waits for enqueued work, then frees the handle, pinned buffers and events.  Resident
- * adapters and the arena stay with the caller. */
+/* End of the keep-alive period (Sec. 5.2): waits for enqueued work, then frees the handle, pinned
+ * buffers and events.  Resident adapters and the arena stay with the caller. */
 int tidal_template_destroy(tidal_template* t);
 
 /* Message of the calling thread's last failed call ("" if none).  Never NULL. */

@@ -146,12 +146,11 @@ __device__ __forceinline__ void shrink_group(uint16_t* xs, uint16_t* as, int lan
 
 // A single workgroup sees one load latency per group unless several groups are in flight: three
 // groups' worth of registers rotate (two at 64 ranks, where a group is 12 vectors per lane).
-template <int XI, int AI>
+template <int XI, int AI, int W = kShrinkWaves>
 __device__ __forceinline__ void shrink_walk(const uint16_t* __restrict__ x, const uint16_t* __restrict__ Ar, int in,
                                             int rows, int r, int lane, int wave, uint16_t* stage, f32x16& c0,
                                             f32x16& c1) {
     constexpr bool DEEP = (XI + AI) <= 8;
-    constexpr int W = kShrinkWaves;
     const int groups = (in + 63) >> 6;
     const int sub = lane >> 3, piece = lane & 7;
     uint16_t* xs = stage;
@@ -242,6 +241,224 @@ hipError_t launch_apply_shrink(const ApplyLongBatch& b, int n_tiles, int in, hip
     if (n_tiles <= 0) return hipSuccess;
     if (b.n <= 0 || b.n > kMaxApplyLong || in <= 0 || in % 8) return hipErrorInvalidValue;
     hipLaunchKernelGGL(apply_shrink_kernel, dim3((unsigned)n_tiles), dim3(64 * kShrinkWaves), 0, stream, b, in);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// prompts in one launch: shrink and expand of a token tile in the same workgroup
+// ---------------------------------------------------------------------------------------
+// A workgroup of 8 waves owns one tile of 32 (or, NV = 8, 16) token rows of one entry.  The waves
+// split the input width for u = bf16(A x) exactly as in apply_shrink_kernel, the partial tiles meet
+// in LDS and are added in wave order, and u stays in LDS: each wave then takes every eighth strip
+// of 256 outputs and updates its piece of y with the register tiling of the in-place merge (y in
+// the place of W, u as the per-row factor, B's rows as the strip).  No intermediate reaches
+// memory and the two steps need no second launch -- for a prompt batch of a few thousand tokens a
+// launch's ramp-up and tail are as long as its data movement.  Small batches take 16-row tiles so
+// that every compute unit gets a workgroup; the upper half of the matrix-core tile then idles.
+constexpr int kFusedWaves = 8;
+constexpr int kFusedPartBytes = kFusedWaves * 2 * 32 * 32 * 4;    // 65,536
+constexpr int kFusedLds = kFusedWaves * kStageBytes;              // 110,592: the stages; later partial sums + u
+static_assert(kFusedPartBytes + 32 * 64 * 2 <= kFusedLds, "partial sums and u must fit where the stages were");
+
+// The lane's part of a tile of y for one strip of 256 outputs: rows 8*(v/4) + 4*h + v%4 (v < NV), 8
+// adjacent outputs each.  Interior pieces use one vector access per row, ragged ones go by element.
+template <int NV>
+__device__ __forceinline__ void y_fetch(const uint16_t* __restrict__ y, int out, int rows, int strip, int lane,
+                                        uint32_t (&w)[NV][4]) {
+    typedef typename RowVec<8>::type vec_t;
+    const int n = lane & 31, h = lane >> 5;
+    const int j0 = strip << 8, jl = j0 + 8 * n;
+    if (j0 + 256 <= out && rows == 2 * NV) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+            unpack_words<8>(load_w((const vec_t*)(y + (int64_t)row * out + jl)), w[v]);
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint32_t lo = 0, hi = 0;
+                if (row < rows && jl + 2 * p < out) lo = as_global(y)[(int64_t)row * out + jl + 2 * p];
+                if (row < rows && jl + 2 * p + 1 < out) hi = as_global(y)[(int64_t)row * out + jl + 2 * p + 1];
+                w[v][p] = lo | (hi << 16);
+            }
+        }
+    }
+}
+
+template <int NV>
+__device__ __forceinline__ void y_store(uint16_t* __restrict__ y, int out, int rows, int strip, int lane,
+                                        const uint32_t (&w)[NV][4]) {
+    typedef typename RowVec<8>::type vec_t;
+    const int n = lane & 31, h = lane >> 5;
+    const int j0 = strip << 8, jl = j0 + 8 * n;
+    if (j0 + 256 <= out && rows == 2 * NV) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+            store_w((vec_t*)(y + (int64_t)row * out + jl), pack_words<8>(w[v]));
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int row = 8 * (v >> 2) + 4 * h + (v & 3);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                if (row < rows && jl + 2 * p < out) as_global(y)[(int64_t)row * out + jl + 2 * p] = (uint16_t)(w[v][p] & 0xFFFFu);
+                if (row < rows && jl + 2 * p + 1 < out) as_global(y)[(int64_t)row * out + jl + 2 * p + 1] = (uint16_t)(w[v][p] >> 16);
+            }
+        }
+    }
+}
+
+// w += s * (u B^T) for one strip: u (token rows) is the matrix-core A operand, B's rows for the
+// lane's 8 outputs the B operand, TB of them at a time (all 8 would not fit the registers at 64 ranks).
+template <int KS, int NV>
+__device__ __forceinline__ void strip_update(const ApplyLongEntry& sg, const bf16x8 (&aop)[KS], int strip, int lane,
+                                             uint32_t (&w)[NV][4]) {
+    constexpr int NT = 8;
+    constexpr int TB = KS == 4 ? 4 : NT;
+    const int n = lane & 31, h = lane >> 5;
+    const int out = sg.out, jl = (strip << 8) + NT * n;
+    const TIDAL_GLOBAL bf16x8* g = as_global((const bf16x8*)sg.Bp);
+#pragma unroll
+    for (int tb = 0; tb < NT; tb += TB) {
+        bf16x8 bop[TB][KS];
+#pragma unroll
+        for (int T = 0; T < TB; ++T) {
+            int j = jl + tb + T;
+            j = j < out ? j : out - 1;                            // ragged strip: clamp, masked at the store
+            const int64_t base = bp_group(j, 0, h, KS);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bop[T][ks] = g[base + 64 * ks];
+        }
+#pragma unroll
+        for (int q = 0; q < TB / 2; ++q) {
+            f32x16 c0 = {0}, c1 = {0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], bop[2 * q][ks], c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[ks], bop[2 * q + 1][ks], c1, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < NV; ++v) w[v][tb / 2 + q] = rmw2(w[v][tb / 2 + q], c0[v], c1[v], sg.s);
+        }
+    }
+}
+
+// The wave's strips (every eighth), two at a time: the second one's y is on its way while the first
+// is updated, where the registers allow.  EARLY: w0 arrives holding the wave's first strip.
+template <int KS, int NV, bool EARLY>
+__device__ __forceinline__ void fused_expand(const ApplyLongEntry& sg, const uint16_t* u_lds, uint16_t* y, int rows,
+                                             int wave, int lane, uint32_t (&w0)[NV][4]) {
+    constexpr bool AHEAD = NV == 8 && KS <= 2;
+    const int out = sg.out;
+    const int strips = (out + 255) >> 8;
+    const int n = lane & 31, h = lane >> 5;
+    bf16x8 aop[KS];                                               // token row n, ranks 16 ks + 8 h + 0..7
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) aop[ks] = *(const bf16x8*)(u_lds + n * (16 * KS) + 16 * ks + 8 * h);
+    for (int strip = wave; strip < strips; strip += 2 * kFusedWaves) {
+        const int next = strip + kFusedWaves;
+        uint32_t w1[NV][4];
+        if (!EARLY || strip != wave) y_fetch<NV>(y, out, rows, strip, lane, w0);
+        if constexpr (AHEAD) {
+            if (next < strips) y_fetch<NV>(y, out, rows, next, lane, w1);
+        }
+        strip_update<KS, NV>(sg, aop, strip, lane, w0);
+        y_store<NV>(y, out, rows, strip, lane, w0);
+        if (next < strips) {
+            if constexpr (!AHEAD) y_fetch<NV>(y, out, rows, next, lane, w1);
+            strip_update<KS, NV>(sg, aop, next, lane, w1);
+            y_store<NV>(y, out, rows, next, lane, w1);
+        }
+    }
+}
+
+// NV = rows of a tile that a lane owns: 16 (32-token tiles) or 8 (16-token tiles)
+template <int NV>
+__global__ __launch_bounds__(64 * kFusedWaves) void apply_fused_kernel(const ApplyLongBatch batch, int in) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kFusedLds];
+    constexpr int TR = 2 * NV;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int si = find_entry(batch, blockIdx.x);
+    const ApplyLongEntry sg = batch.e[si];
+    const int tile0 = sg.t0 + TR * ((int)blockIdx.x - batch.first[si]);   // first token of this tile
+    const int rows = sg.t1 - tile0 < TR ? sg.t1 - tile0 : TR;
+    const uint16_t* x = batch.x + (int64_t)tile0 * in;
+    uint16_t* stage = (uint16_t*)(lds + wave * kStageBytes);
+
+    f32x16 c0 = {0}, c1 = {0};
+    const int xi = (rows + 7) >> 3;
+    // instantiations by the number of 8-row blocks to fetch: x 1, 2 or 4, A 2, 4 or 8
+    if (sg.rp == 16) {
+        if (xi == 1) shrink_walk<1, 2, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else if (xi == 2) shrink_walk<2, 2, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else shrink_walk<4, 2, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+    } else if (sg.rp == 32) {
+        if (xi == 1) shrink_walk<1, 4, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else if (xi == 2) shrink_walk<2, 4, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else shrink_walk<4, 4, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+    } else {
+        if (xi == 1) shrink_walk<1, 8, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else if (xi == 2) shrink_walk<2, 8, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+        else shrink_walk<4, 8, kFusedWaves>(x, sg.Ar, in, rows, sg.r, lane, wave, stage, c0, c1);
+    }
+
+    // y does not depend on u: the wave's first strip sets out now and arrives during the reduction
+    uint16_t* y = sg.y + (int64_t)tile0 * sg.out;
+    uint32_t w0[NV][4];
+    constexpr bool EARLY = NV == 8;                               // 32-token tiles: the registers do not allow it
+    if constexpr (EARLY) {
+        if (wave < ((sg.out + 255) >> 8)) y_fetch<NV>(y, sg.out, rows, wave, lane, w0);
+    }
+
+    // C layout: lane holds rank column n of token rows 8*(v/4) + 4*kg + v%4
+    const int n = lane & 31, kg = lane >> 5;
+    const bool two = sg.rp > 32;
+    __syncthreads();                                              // the stages become the partial sums
+    float* part = (float*)lds;                                    // [wave][rank tile][token][rank]
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = 8 * (v >> 2) + 4 * kg + (v & 3);
+        part[((wave * 2 + 0) * 32 + row) * 32 + n] = c0[v];
+        if (two) part[((wave * 2 + 1) * 32 + row) * 32 + n] = c1[v];
+    }
+    __syncthreads();
+    uint16_t* u_lds = (uint16_t*)(lds + kFusedPartBytes);         // 32 token rows x rp bf16; rows past `rows` are zeros
+    const int pairs_per_row = sg.rp >> 1;
+    for (int e = threadIdx.x; e < 32 * pairs_per_row; e += 64 * kFusedWaves) {
+        const int row = e / pairs_per_row;
+        const int k = 2 * (e - row * pairs_per_row);
+        float lo = 0.0f, hi = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kFusedWaves; ++w) {                   // fixed order: reproducible
+            lo += part[((w * 2 + (k >> 5)) * 32 + row) * 32 + (k & 31)];
+            hi += part[((w * 2 + (k >> 5)) * 32 + row) * 32 + (k & 31) + 1];
+        }
+        const f32x2 r2 = {lo, hi};
+        ((uint32_t*)u_lds)[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(r2, bf16x2));
+    }
+    __syncthreads();
+    if (sg.rp == 16) fused_expand<1, NV, EARLY>(sg, u_lds, y, rows, wave, lane, w0);
+    else if (sg.rp == 32) fused_expand<2, NV, EARLY>(sg, u_lds, y, rows, wave, lane, w0);
+    else fused_expand<4, NV, EARLY>(sg, u_lds, y, rows, wave, lane, w0);
+}
+
+// tile_rows: 32 or 16 (token rows per workgroup; first[] of the batch counts tiles of that height)
+hipError_t launch_apply_fused(const ApplyLongBatch& b, int n_tiles, int tile_rows, int in, hipStream_t stream) {
+    if (n_tiles <= 0) return hipSuccess;
+    if (b.n <= 0 || b.n > kMaxApplyLong || in <= 0 || in % 8) return hipErrorInvalidValue;
+    for (int k = 0; k < b.n; ++k)
+        if (b.e[k].out <= 0 || b.e[k].out % 8 || (b.e[k].rp != 16 && b.e[k].rp != 32 && b.e[k].rp != 64))
+            return hipErrorInvalidValue;
+    if (tile_rows == 32) hipLaunchKernelGGL(apply_fused_kernel<16>, dim3((unsigned)n_tiles), dim3(64 * kFusedWaves), 0, stream, b, in);
+    else if (tile_rows == 16) hipLaunchKernelGGL(apply_fused_kernel<8>, dim3((unsigned)n_tiles), dim3(64 * kFusedWaves), 0, stream, b, in);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

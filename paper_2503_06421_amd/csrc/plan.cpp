@@ -126,7 +126,7 @@ void plan_copies(const std::vector<SourceInfo>& srcs, const tidal_config& cfg, i
 // launch plan of a LoRA read-modify-write group
 // ---------------------------------------------------------------------------------------
 TuningKnobs tuning_knobs() {
-    TuningKnobs k = {-1, -1, -1, -1, -1, -1};
+    TuningKnobs k = {-1, -1, -1, -1, -1, -1, -1, -1};
 #ifdef TIDAL_TUNING_KNOBS
     auto read = [](const char* name, int lo, int hi) {
         const char* e = getenv(name);
@@ -140,6 +140,9 @@ TuningKnobs tuning_knobs() {
     k.mfma_order = read("TIDAL_MFMA_ORDER", 0, 3);
     k.mfma_dynlds = read("TIDAL_MFMA_DYNLDS", 0, 120 << 10);
     k.apply_ct = read("TIDAL_APPLY_CT", 1, kApplyChunkTiles);
+    k.apply_tile_rows = read("TIDAL_APPLY_TILE_ROWS", 16, 32);
+    if (k.apply_tile_rows != 16 && k.apply_tile_rows != 32) k.apply_tile_rows = -1;
+    k.apply_two_step = read("TIDAL_APPLY_TWO_STEP", 0, 1);
 #endif
     return k;
 }

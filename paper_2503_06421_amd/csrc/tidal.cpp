@@ -1540,6 +1540,32 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
         }
         return TIDAL_OK;
     };
+    // Default for prompts: both steps of a token tile in one workgroup, one launch per kMaxApplyLong
+    // entries.  Batches too small to give every compute unit a 32-token tile take 16-token tiles.
+    auto run_fused = [&]() -> int {
+        int64_t tiles32 = 0;
+        for (const ApplyLongEntry& e : long_entries) tiles32 += ((int64_t)e.t1 - e.t0 + 31) / 32;
+        int tr = tiles32 < 256 ? 16 : 32;
+        if (tuning_knobs().apply_tile_rows > 0) tr = tuning_knobs().apply_tile_rows;      // tuning builds only
+        for (size_t at = 0; at < long_entries.size(); at += kMaxApplyLong) {
+            const int n = (int)std::min(long_entries.size() - at, (size_t)kMaxApplyLong);
+            ApplyLongBatch b;
+            memset(&b, 0, sizeof b);
+            b.x = (const uint16_t*)x;
+            b.u = nullptr;                               // u never leaves the workgroup
+            b.n = n;
+            int64_t units = 0;
+            for (int k = 0; k < kMaxApplyLong; ++k) b.first[k] = 0x7FFFFFFF;
+            for (int k = 0; k < n; ++k) {
+                b.e[k] = long_entries[at + k];
+                b.first[k] = (int32_t)units;
+                units += ((int64_t)b.e[k].t1 - b.e[k].t0 + tr - 1) / tr;
+            }
+            if (units > 0x7FFFFFF0) return fail(TIDAL_E_INVAL, "batch too large");
+            HIP_TRY(launch_apply_fused(b, (int)units, tr, (int)in, stream));
+        }
+        return TIDAL_OK;
+    };
     // ---- decode steps: compact tables, up to kMaxApplyShort segments whose adapters' factor
     // entries (n_slots each) fit the factor table
     auto run_short = [&](bool shrink) -> int {
@@ -1574,14 +1600,16 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
         }
         return TIDAL_OK;
     };
-    rc = run_long(true, 0);
+    const bool two_step = ordered || tuning_knobs().apply_two_step == 1;      // the knob: tuning builds only
+    rc = two_step ? run_long(true, 0) : run_fused();
     if (rc) return rc;
     rc = run_short(true);
     if (rc) return rc;
-    for (int rp = 16; rp <= 64; rp *= 2) {
-        rc = run_long(false, rp);
-        if (rc) return rc;
-    }
+    if (two_step)
+        for (int rp = 16; rp <= 64; rp *= 2) {
+            rc = run_long(false, rp);
+            if (rc) return rc;
+        }
     return run_short(false);
 }
 

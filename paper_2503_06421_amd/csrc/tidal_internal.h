@@ -207,6 +207,9 @@ constexpr int kApplyShortRows = 4;     // segments up to this many tokens take t
 // (n_chunks = chunks over all entries; rp = the padded rank all entries of the launch have).
 hipError_t launch_apply_shrink(const ApplyLongBatch& b, int n_tiles, int in, hipStream_t stream);
 hipError_t launch_apply_expand(const ApplyLongBatch& b, int n_chunks, int chunk_tiles, int max_out, int rp, hipStream_t stream);
+// Both steps in one launch: a workgroup per tile of tile_rows (32 or 16) token rows keeps u in LDS
+// (n_tiles = tiles of that height over all entries, numbered by first[]; entries of any padded rank).
+hipError_t launch_apply_fused(const ApplyLongBatch& b, int n_tiles, int tile_rows, int in, hipStream_t stream);
 // Both steps with ordered accumulation (any segment length): u = bf16(A x) if shrink, else the expand.
 hipError_t launch_apply_ordered(const ApplyLongBatch& b, int in, bool shrink, hipStream_t stream);
 // Vector-ALU pair for the short segments.
@@ -224,6 +227,8 @@ struct TuningKnobs {
     int mfma_order;     // TIDAL_MFMA_ORDER: workgroup -> tile order of the LDS-strip kernel
     int mfma_dynlds;    // TIDAL_MFMA_DYNLDS: extra LDS bytes per workgroup (limits workgroups per CU)
     int apply_ct;       // TIDAL_APPLY_CT: 32-token tiles per wave of the expand kernel
+    int apply_tile_rows; // TIDAL_APPLY_TILE_ROWS: 16 or 32 token rows per workgroup of the fused prompt kernel
+    int apply_two_step; // TIDAL_APPLY_TWO_STEP: 1 = prompts as two launches (shrink, expand) instead of the fused one
 };
 TuningKnobs tuning_knobs();
 

@@ -14,6 +14,7 @@ hipError_t launch_lora_ordered(const LoraGroup&, hipStream_t) { return hipErrorN
 hipError_t launch_convert_merge(const FusedPiece&, bool, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_apply_shrink(const ApplyLongBatch&, int, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_apply_expand(const ApplyLongBatch&, int, int, int, int, hipStream_t) { return hipErrorNotSupported; }
+hipError_t launch_apply_fused(const ApplyLongBatch&, int, int, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_apply_ordered(const ApplyLongBatch&, int, bool, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_apply_shrink_short(const ApplyShortBatch&, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_apply_expand_short(const ApplyShortBatch&, int, hipStream_t) { return hipErrorNotSupported; }

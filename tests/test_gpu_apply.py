@@ -143,6 +143,23 @@ def test_segment_lengths_around_the_kernel_boundaries(orc, flags):
         check(orc, items, segs, X, Y, got, bool(flags))
 
 
+def test_batch_of_more_than_256_tiles_takes_32_token_tiles(orc):
+    """Prompt batches of 8192 tokens or more run one workgroup per 32 token rows (smaller ones per 16):
+    three ranks, a ragged last tile per segment, 1.03 strips of outputs, a ragged last 64-column group."""
+    rng = np.random.default_rng(16)
+    with Template([(264, 200)]) as T:
+        items, handles = make_adapters(T, rng, 0, [16, 64, 20], [32.0, 64.0, 40.0])
+        lens = [4999, 2500, 777, 33]
+        segs, t = [], 0
+        for i, n in enumerate(lens):
+            segs.append((i % 3, t, t + n))
+            t += n + 1
+        X = bf16_bits(rng, (t, 200), 1.0)
+        Y = bf16_bits(rng, (t, 264), 1.0)
+        got = run_apply(T, 0, handles, segs, X, Y)
+        check(orc, items, segs, X, Y, got)
+
+
 def test_long_prompt_one_adapter_and_merged_weights_untouched(orc):
     rng = np.random.default_rng(13)
     with Template([(256, 1024)]) as T:

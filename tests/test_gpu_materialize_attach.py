@@ -43,8 +43,10 @@ def run_case(orc, flags, dtype, shapes, targets, chunk_bytes, seed, one_stream=F
         tb.tidal_materialize_attach(T.h, srcs, tg, T.compute_stream if one_stream else T.copy_stream, T.compute_stream)
         T.sync()
         exact = bool(flags & ORDERED)
+        merged = {}
         for i in range(len(shapes)):
             got = T.slot(i)
+            merged[i] = got
             if i in ad and ad[i][1].shape[0] > 0 and ad[i][0] != 0.0:
                 al, A, B = ad[i]
                 want = orc.materialize_merge(src[i], orc.convert_to_bf16(A), orc.convert_to_bf16(B), al)
@@ -56,8 +58,17 @@ def run_case(orc, flags, dtype, shapes, targets, chunk_bytes, seed, one_stream=F
         tb.tidal_lora_detach(T.h, T.compute_stream)
         T.sync()
         for i in ad:
+            al, A, B = ad[i]
+            got = T.slot(i)
+            if A.shape[0] > 0 and al != 0.0:
+                # the oracle's unmerge of what the GPU held after the fused load
+                want = merged[i].copy()
+                orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), al, -1)
+                check_against_oracle(got, want, exact, "slot %d after detach" % i)
+            else:
+                assert np.array_equal(got, merged[i]), i
             base = orc.convert_to_bf16(src[i])
-            g, b = f32(T.slot(i)).astype(np.float64), f32(base).astype(np.float64)
+            g, b = f32(got).astype(np.float64), f32(base).astype(np.float64)
             assert np.max(np.abs(g - b)) <= 2.0 ** -6 * max(np.max(np.abs(b)), 1e-30), i
         return T.slot(0)
 
