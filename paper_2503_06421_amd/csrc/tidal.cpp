@@ -1601,9 +1601,14 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
         return TIDAL_OK;
     };
     const bool two_step = ordered || tuning_knobs().apply_two_step == 1;      // the knob: tuning builds only
-    rc = two_step ? run_long(true, 0) : run_fused();
-    if (rc) return rc;
+    // Decode segments stay two launches: one workgroup per (request, target) that computes all of u
+    // itself was tried and lost (35 instead of 20 us for 64 requests: a single compute unit cannot
+    // pull a 64-rank A through fast enough), and the shrink of a request must be spread over many
+    // compute units, which puts a grid-wide dependency in front of the expand.  The prompts' launch
+    // goes in between and covers the hand-over.
     rc = run_short(true);
+    if (rc) return rc;
+    rc = two_step ? run_long(true, 0) : run_fused();
     if (rc) return rc;
     if (two_step)
         for (int rp = 16; rp <= 64; rp *= 2) {
