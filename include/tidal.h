@@ -102,16 +102,15 @@ enum {
      * copy and tiny tensors are not gathered by the CPU.  For measuring what tensor merging
      * (Sec. 6) buys; results are identical.                                                    */
     TIDAL_FLAG_NO_COPY_MERGE = 32,
-    /* tidal_lora_attach / _swap upload and merge an adapter in groups of targets: while one group
-     * is packed and merged on the caller's stream, the next one's factors cross the link on a stream
-     * of the library's own, so most of the upload hides under the merge (or the other way round).
-     * By default the library does this for adapters of 4 MiB or more where its estimate says it
-     * pays, with groups sized from link and pass rates it measures with its own events; results are
-     * identical to a single pass either way.  PIPELINED_UPLOAD: always (two groups or more, whatever
-     * the size); SERIAL_UPLOAD: never -- everything on the caller's stream, upload first, then one
-     * launch per group of equal shapes.  (The extra stream shares the process's few hardware queues
-     * with the caller's streams: with four or more streams of the caller's in use, work on one of
-     * them may queue behind the uploads.)                                                         */
+    /* tidal_lora_attach / _swap upload and merge an adapter in groups of targets: the factors of
+     * all groups cross the link back to back on a stream of the library's own, and the caller's
+     * stream packs and merges each group as soon as it has arrived, so that most of the upload
+     * hides under the merges (or the other way round).  This needs factors in pinned host memory
+     * (pageable ones always take the single pass).  By default the library does it for adapters of
+     * 4 MiB or more where its estimate says it pays, with groups sized from link and pass rates it
+     * measures with its own events; results are identical to a single pass either way.
+     * PIPELINED_UPLOAD: always (two groups or more, whatever the size); SERIAL_UPLOAD: never --
+     * everything on the caller's stream, upload first, then one launch per group of equal shapes. */
     TIDAL_FLAG_PIPELINED_UPLOAD = 64,
     TIDAL_FLAG_SERIAL_UPLOAD = 128
 };

@@ -165,6 +165,34 @@ __host__ __device__ inline int64_t pack_lines_padded(const PackSegment& seg) {
     return seg.layout == kPackAt ? (seg.lines + 255) / 256 * 256 : (seg.layout == kPackBp ? (seg.lines + 31) / 32 * 32 : seg.lines);
 }
 
+// Eight consecutive source elements from element idx on (a 16-byte aligned address), narrowed to bf16.
+__device__ __forceinline__ u32x4 load8_narrow(const void* src, int dtype, int64_t idx) {
+    if (dtype == TIDAL_F32) {
+        const u32x4* p = (const u32x4*)((const uint32_t*)src + idx);
+        return narrow8_f32(p[0], p[1]);
+    }
+    const u32x4 v = *(const u32x4*)((const uint16_t*)src + idx);
+    return dtype == TIDAL_F16 ? narrow8_f16(v) : v;
+}
+
+// Half `T & 1` of word `T >> 1` of two vectors of 8 bf16, side by side in one word: element T of
+// `lo` in the low half, of `hi` in the high half.
+template <int T>
+__device__ __forceinline__ uint32_t pair_of(const u32x4& lo, const u32x4& hi) {
+    const uint32_t a = lo[T >> 1], b = hi[T >> 1];
+    return (T & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+}
+
+template <int T>
+__device__ __forceinline__ u32x4 column_of(const u32x4 (&row)[8]) {
+    u32x4 o;
+    o.x = pair_of<T>(row[0], row[1]);
+    o.y = pair_of<T>(row[2], row[3]);
+    o.z = pair_of<T>(row[4], row[5]);
+    o.w = pair_of<T>(row[6], row[7]);
+    return o;
+}
+
 __global__ __launch_bounds__(256) void pack_adapter_kernel(PackBatch batch) {
     const PackSegment seg = batch.seg[blockIdx.y];
     const int groups_per_line = seg.rp >> 3;                 // 16-byte groups per packed line
@@ -172,7 +200,51 @@ __global__ __launch_bounds__(256) void pack_adapter_kernel(PackBatch batch) {
     const int64_t lines_pad = pack_lines_padded(seg);
     const int64_t ngroups = lines_pad * groups_per_line;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < ngroups; g += stride) {
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool aligned = (uintptr_t)seg.src % 16 == 0;
+    u32x4* __restrict__ dst = (u32x4*)seg.dst;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    if (seg.layout == kPackAt && aligned && seg.lines % 8 == 0) {
+        // A lane takes 8 ranks x 8 columns: eight 16-byte reads along the rows of A (neighbouring lanes
+        // read neighbouring pieces: whole cache lines), an 8 x 8 transpose in registers, eight 16-byte
+        // groups out, each next to the one the neighbouring lane writes.
+        const int64_t nblk = lines_pad >> 3;
+        for (int64_t unit = first; unit < nblk * groups_per_line; unit += stride) {
+            const int64_t c = unit % nblk;                    // block of 8 columns
+            const int kg = (int)(unit / nblk);
+            u32x4 row[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = kg * 8 + e;
+                row[e] = (k < seg.r && 8 * c < seg.lines) ? load8_narrow(seg.src, seg.dtype, (int64_t)k * seg.lines + 8 * c) : zero;
+            }
+            const int64_t base = (c >> 5) * 8 * KS * 64 + (kg >> 1) * 64 + (kg & 1) * 32 + (c & 31);   // column T: + T * KS * 64
+            dst[base + 0 * KS * 64] = column_of<0>(row);
+            dst[base + 1 * KS * 64] = column_of<1>(row);
+            dst[base + 2 * KS * 64] = column_of<2>(row);
+            dst[base + 3 * KS * 64] = column_of<3>(row);
+            dst[base + 4 * KS * 64] = column_of<4>(row);
+            dst[base + 5 * KS * 64] = column_of<5>(row);
+            dst[base + 6 * KS * 64] = column_of<6>(row);
+            dst[base + 7 * KS * 64] = column_of<7>(row);
+        }
+        return;
+    }
+    if (seg.layout != kPackAt && aligned && seg.r % 8 == 0) {
+        // rows of B (or plain rows): a group is 8 consecutive source elements; neighbouring lanes take
+        // neighbouring groups of a row, so the reads are whole cache lines
+        for (int64_t g = first; g < ngroups; g += stride) {
+            const int64_t line = g / groups_per_line;
+            const int kg = (int)(g - line * groups_per_line);
+            const u32x4 o = (line < seg.lines && 8 * kg < seg.r) ? load8_narrow(seg.src, seg.dtype, line * seg.r + 8 * kg) : zero;
+            const int64_t at = seg.layout == kPackBp ? ((line >> 5) * KS + (kg >> 1)) * 64 + (kg & 1) * 32 + (line & 31)
+                                                     : line * groups_per_line + kg;
+            dst[at] = o;
+        }
+        return;
+    }
+    // any rank, width and alignment: element by element
+    for (int64_t g = first; g < ngroups; g += stride) {
         // consecutive lanes take consecutive lines so that the strided reads of a transposed
         // A are coalesced along j
         const int64_t line = g % lines_pad;
@@ -199,7 +271,7 @@ __global__ __launch_bounds__(256) void pack_adapter_kernel(PackBatch batch) {
         if (seg.layout == kPackAt) at = (((line >> 8) * 8 + (line & 7)) * KS + (kg >> 1)) * 64 + (kg & 1) * 32 + ((line & 255) >> 3);
         else if (seg.layout == kPackBp) at = ((line >> 5) * KS + (kg >> 1)) * 64 + (kg & 1) * 32 + (line & 31);
         else at = line * groups_per_line + kg;
-        ((u32x4*)seg.dst)[at] = o;
+        dst[at] = o;
     }
 }
 

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <chrono>
 #include <map>
 #include <mutex>
 #include <new>
@@ -33,9 +34,44 @@ static int fail(int code, const char* fmt, ...) {
     return code;
 }
 
+#ifdef TIDAL_TUNING_KNOBS
+// tuning builds: host time per kind of HIP call, printed by whoever asks (TIDAL_TRACE_HOST)
+struct HostCallStat { const char* what; double us; long n; };
+static HostCallStat g_call_stats[64];
+static int g_n_call_stats = 0;
+static void host_call_add(const char* what, double us) {
+    size_t len = 0;
+    while (what[len] && what[len] != '(') ++len;
+    for (int i = 0; i < g_n_call_stats; ++i)
+        if (!strncmp(g_call_stats[i].what, what, len) && g_call_stats[i].what[len] == '(') {
+            g_call_stats[i].us += us;
+            g_call_stats[i].n++;
+            return;
+        }
+    if (g_n_call_stats < 64) g_call_stats[g_n_call_stats++] = HostCallStat{what, us, 1};
+}
+static void host_call_report() {
+    for (int i = 0; i < g_n_call_stats; ++i) {
+        size_t len = 0;
+        while (g_call_stats[i].what[len] && g_call_stats[i].what[len] != '(') ++len;
+        fprintf(stderr, "[hostcalls] %-32.*s n=%5ld total %9.1f us\n", (int)len, g_call_stats[i].what, g_call_stats[i].n, g_call_stats[i].us);
+    }
+    g_n_call_stats = 0;
+}
+#define HIP_TIMED(expr)                                                                            \
+    [&]() {                                                                                        \
+        const auto t0_ = std::chrono::steady_clock::now();                                         \
+        hipError_t r_ = (expr);                                                                    \
+        host_call_add(#expr, std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0_).count()); \
+        return r_;                                                                                 \
+    }()
+#else
+#define HIP_TIMED(expr) (expr)
+#endif
+
 #define HIP_TRY(expr)                                                                              \
     do {                                                                                           \
-        hipError_t e_ = (expr);                                                                    \
+        hipError_t e_ = HIP_TIMED(expr);                                                           \
         if (e_ != hipSuccess)                                                                      \
             return fail(TIDAL_E_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
     } while (0)
@@ -147,8 +183,10 @@ struct tidal_template {
     hipEvent_t ev_start = nullptr, ev_copy_done = nullptr;
     std::vector<StreamMark> marks;
     hipStream_t up_stream = nullptr;                   // library-owned: adapter uploads that overlap the merge
-    hipStream_t pack_stream = nullptr;                 // library-owned: packs each uploaded group beside the merges
-    hipEvent_t ev_up_begin = nullptr, ev_group_packed[kMaxUploadGroups] = {};
+    hipEvent_t ev_up_begin = nullptr;
+    hipEvent_t ev_group_copied[kMaxUploadGroups] = {}; // up_stream: the group's factors are in the staging memory
+    hipEvent_t ev_group_packed[kMaxUploadGroups] = {}; // caller's stream: ... and have been read from there again
+    hipStream_t staging_stream[2] = {nullptr, nullptr};   // the stream staging_free[b] was last recorded on
     RateModel rates;
     char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
     bool bounce_used[2] = {false, false};
@@ -223,9 +261,11 @@ static int ensure_bounce(tidal_template* t, int b) {
 static int ensure_upload_stream(tidal_template* t) {
     if (t->up_stream) return TIDAL_OK;
     HIP_TRY(hipStreamCreateWithFlags(&t->up_stream, hipStreamNonBlocking));      // default priority
-    HIP_TRY(hipStreamCreateWithFlags(&t->pack_stream, hipStreamNonBlocking));    // default priority
     HIP_TRY(hipEventCreateWithFlags(&t->ev_up_begin, hipEventDisableTiming));
-    for (int g = 0; g < kMaxUploadGroups; ++g) HIP_TRY(hipEventCreateWithFlags(&t->ev_group_packed[g], hipEventDisableTiming));
+    for (int g = 0; g < kMaxUploadGroups; ++g) {
+        HIP_TRY(hipEventCreateWithFlags(&t->ev_group_copied[g], hipEventDisableTiming));
+        HIP_TRY(hipEventCreateWithFlags(&t->ev_group_packed[g], hipEventDisableTiming));
+    }
     for (int k = 0; k < 4; ++k) HIP_TRY(hipEventCreate(&t->rates.ev[k]));
     return TIDAL_OK;
 }
@@ -273,7 +313,7 @@ static int timing_drain(tidal_template* t) {
 
 static bool host_is_pinned(const void* p) {
     hipPointerAttribute_t attr;
-    hipError_t e = hipPointerGetAttributes(&attr, p);
+    hipError_t e = HIP_TIMED(hipPointerGetAttributes(&attr, p));
     if (e != hipSuccess) {
         (void)hipGetLastError();   // plain malloc'ed memory is reported as an error, not a type
         return false;
@@ -469,7 +509,7 @@ struct Pipeline {
         t->stats.h2d_copies++;
         if (kernel_copy && run_len <= kKernelCopyMax && (uintptr_t)run_src % 16 == 0 && (uintptr_t)run_dst % 16 == 0) {
             void* view = nullptr;            // the GPU's address for this pinned host memory
-            if (hipHostGetDevicePointer(&view, const_cast<char*>(run_src), 0) == hipSuccess && view &&
+            if (HIP_TIMED(hipHostGetDevicePointer(&view, const_cast<char*>(run_src), 0)) == hipSuccess && view &&
                 (uintptr_t)view % 16 == 0) {
                 kbatch.run[kruns++] = CopyRun{view, run_dst, (uint64_t)run_len};
                 return kruns == kMaxCopyRuns ? flush_kernel_copies() : TIDAL_OK;
@@ -553,6 +593,7 @@ struct Pipeline {
     int consumed(int b) {
         HIP_TRY(hipEventRecord(t->staging_free[b], compute));
         t->staging_rec[b] = true;
+        t->staging_stream[b] = compute;
         t->stats.chunks++;
         return TIDAL_OK;
     }
@@ -793,37 +834,58 @@ extern "C" size_t tidal_adapter_required_bytes(const tidal_template* t, const ti
 // `copy` and `pack` may differ: the copies of a later chunk then run while an earlier one is packed
 // (and, for a pipelined attach, merged) on `pack`.  `chunk_io` carries the staging-buffer parity from
 // one call to the next so that successive groups alternate between the two buffers.
-static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t copy,
-                          hipStream_t pack, size_t first = 0, size_t last = ~(size_t)0, int* chunk_io = nullptr) {
-    // A job is one factor staged once; A may be packed twice (transposed and, as a plain
-    // conversion written as lines of 8, row-major)
-    struct Job { const char* host; size_t bytes; PackSegment seg; bool pinned; bool has2; PackSegment seg2; };
-    std::vector<Job> jobs;
+// A job is one factor staged once; A may be packed twice (transposed and, as a plain conversion
+// written as lines of 8, row-major).
+struct UploadJob { const char* host; size_t bytes; PackSegment seg; bool pinned; bool has2; PackSegment seg2; };
+
+static int upload_jobs(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, size_t first, size_t last,
+                       std::vector<UploadJob>* jobs) {
     for (size_t i = first; i < std::min(last, rec.targets.size()); ++i) {
         const PackedTarget& p = rec.targets[i];
         const SlotState& s = t->slots[p.slot];
         if (!p.active() || s.elems == 0) continue;
         const size_t isz = dtype_size(tg[i].dtype);
-        Job a{(const char*)tg[i].A, (size_t)p.r * (size_t)s.cols * isz,
-              PackSegment{nullptr, rec.dev + p.at_off, s.cols, p.r, p.rp, tg[i].dtype, kPackAt}, false, false, {}};
+        UploadJob a{(const char*)tg[i].A, (size_t)p.r * (size_t)s.cols * isz,
+                    PackSegment{nullptr, rec.dev + p.at_off, s.cols, p.r, p.rp, tg[i].dtype, kPackAt}, false, false, {}};
         if (p.ar_off != kNoOffset) {
             a.has2 = true;
             a.seg2 = PackSegment{nullptr, rec.dev + p.ar_off, (int64_t)p.r * s.cols / 8, 8, 8, tg[i].dtype, kPackRows};
         }
-        Job b{(const char*)tg[i].B, (size_t)p.r * (size_t)s.rows * isz,
-              PackSegment{nullptr, rec.dev + p.bp_off, s.rows, p.r, p.rp, tg[i].dtype, kPackBp}, false, false, {}};
+        UploadJob b{(const char*)tg[i].B, (size_t)p.r * (size_t)s.rows * isz,
+                    PackSegment{nullptr, rec.dev + p.bp_off, s.rows, p.r, p.rp, tg[i].dtype, kPackBp}, false, false, {}};
         if (a.bytes > t->cfg.chunk_bytes || b.bytes > t->cfg.chunk_bytes)
             return fail(TIDAL_E_INVAL, "target %zu: a LoRA factor is larger than chunk_bytes", i);
-        jobs.push_back(a);
-        jobs.push_back(b);
+        jobs->push_back(a);
+        jobs->push_back(b);
     }
+    for (UploadJob& j : *jobs) j.pinned = host_is_pinned(j.host);
+    return TIDAL_OK;
+}
+
+static int launch_packs(const std::vector<PackSegment>& segs, hipStream_t stream) {
+    for (size_t k = 0; k < segs.size(); k += kMaxPackSeg) {
+        const int n = (int)std::min(segs.size() - k, (size_t)kMaxPackSeg);
+        PackBatch batch;
+        memcpy(batch.seg, segs.data() + k, (size_t)n * sizeof(PackSegment));
+        HIP_TRY(launch_pack(batch, n, stream));
+    }
+    return TIDAL_OK;
+}
+
+// Stage the factors of an adapter chunk by chunk through the two staging buffers and pack them into
+// rec.dev: copies on `copy`, pack kernels on `pack` (the same stream or two).
+static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec, hipStream_t copy,
+                          hipStream_t pack) {
+    typedef UploadJob Job;
+    std::vector<Job> jobs;
+    int rc0 = upload_jobs(t, tg, rec, 0, rec.targets.size(), &jobs);
+    if (rc0) return rc0;
     if (jobs.empty()) return TIDAL_OK;
-    for (Job& j : jobs) j.pinned = host_is_pinned(j.host);
 
     Pipeline pl{t, copy, pack};
     pl.kernel_copy = true;
     size_t i = 0;
-    int chunk = chunk_io ? *chunk_io : 0;
+    int chunk = 0;
     while (i < jobs.size()) {
         const int b = chunk & 1;
         // fill one staging buffer with whole factors: all copies first (neighbouring ones merge
@@ -857,18 +919,13 @@ static int upload_adapter(tidal_template* t, const tidal_lora_target* tg, const 
         }
         rc = pl.copies_done(b, need_bounce, true);
         if (rc) return rc;
-        for (size_t k = 0; k < segs.size(); k += kMaxPackSeg) {
-            const int n = (int)std::min(segs.size() - k, (size_t)kMaxPackSeg);
-            PackBatch batch;
-            memcpy(batch.seg, segs.data() + k, (size_t)n * sizeof(PackSegment));
-            HIP_TRY(launch_pack(batch, n, pack));
-        }
+        rc = launch_packs(segs, pack);
+        if (rc) return rc;
         rc = pl.consumed(b);
         if (rc) return rc;
         i = j;
         ++chunk;
     }
-    if (chunk_io) *chunk_io = chunk;
     return TIDAL_OK;
 }
 
@@ -1099,6 +1156,9 @@ static void rates_update(tidal_template* t) {
     r.pending = false;
 }
 
+// The two staging buffers lie back to back in the arena: one span for the grouped upload.
+static inline size_t staging_span(const tidal_template* t) { return 2 * t->cfg.chunk_bytes; }
+
 // Cut the targets of an adapter given by host pointers into groups that are uploaded and merged in
 // turn.  With upload time u and merge time m of each target known from the two rates, the end of
 // the call is simulated for every choice of the first group's size (each later group: as many
@@ -1108,7 +1168,8 @@ static void rates_update(tidal_template* t) {
 static void plan_upload_groups(const tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec,
                                const AdapterRec* old, std::vector<std::pair<size_t, size_t>>* groups) {
     constexpr size_t kPipelineFrom = (size_t)4 << 20;
-    constexpr double kLaunchMs = 0.03;             // what one more launch costs: its bubble, its ramp and tail, an event wait
+    constexpr double kLaunchMs = 0.02;             // what one more launch costs: its bubble, its ramp and tail
+    constexpr double kWaitMs = 0.04;               // what a cross-stream wait costs the calling thread
     const size_t n = rec.targets.size();
     groups->clear();
     groups->push_back({0, n});
@@ -1118,13 +1179,14 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
     if (old)
         for (const PackedTarget& p : old->targets)
             if (p.active()) in_old[p.slot] = 1;
-    std::vector<double> u(n, 0.0), m(n, 0.0);
+    std::vector<double> u(n, 0.0), m(n, 0.0), raw(n, 0.0);
     double u_total = 0.0, m_total = 0.0;
     for (size_t i = 0; i < n; ++i) {
         const PackedTarget& p = rec.targets[i];
         const SlotState& s = t->slots[p.slot];
         if (s.elems == 0) continue;
-        if (p.active()) u[i] = (double)p.r * (double)(s.rows + s.cols) * (double)dtype_size(tg[i].dtype) / t->rates.link_bytes_per_ms;
+        if (p.active()) raw[i] = (double)p.r * (double)(s.rows + s.cols) * (double)dtype_size(tg[i].dtype) + 2.0 * kSlotAlign;
+        u[i] = raw[i] / t->rates.link_bytes_per_ms;
         if (p.active() || in_old[p.slot]) m[i] = 4.0 * (double)s.elems / t->rates.rmw_bytes_per_ms;
         u_total += u[i];
         m_total += m[i];
@@ -1150,7 +1212,7 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
     // merging starts early, and large later ones that hide under the merges before them).  Each is
     // simulated on three resources -- the link, the packing stream, the caller's stream -- and the
     // one that ends first is taken.
-    const double pack_rate = 1.0e9;                                      // bytes per ms through the pack kernel
+    const double pack_rate = 2.0e9;                                      // bytes per ms through the pack kernel
     static const double kGrowth[] = {1.0, 1.5, 2.0, 3.0};
     static const double kFirst[] = {1.0, 0.35};                           // the first group may be smaller still
     for (int G = 2; G <= kMaxUploadGroups && (size_t)G <= n; ++G) {
@@ -1173,14 +1235,20 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
                 if (a0 >= n) break;
             }
             if (cand.size() < 2) continue;
-            double copy_done = 0.0, pack_done = 0.0, merge_done = 0.0;
+            // the link carries the groups back to back, as soon as the calling thread has got to them; the
+            // caller's stream takes each group when its copies are in: pack, then merge
+            double host = kWaitMs, copy_done = 0.0, merge_done = 0.0;
+            bool fits = true;
             for (const auto& gr : cand) {
-                double ug = 0.0, mg = 0.0;
-                for (size_t i = gr.first; i < gr.second; ++i) { ug += u[i]; mg += m[i]; }
-                copy_done += ug;
-                pack_done = std::max(pack_done, copy_done) + kLaunchMs + 2.0 * ug * t->rates.link_bytes_per_ms / pack_rate;
-                merge_done = std::max(merge_done, pack_done) + mg + kLaunchMs * launches(gr.first, gr.second);
+                double ug = 0.0, mg = 0.0, bytes = 0.0;
+                for (size_t i = gr.first; i < gr.second; ++i) { ug += u[i]; mg += m[i]; bytes += raw[i]; }
+                fits = fits && bytes <= 0.5 * (double)staging_span(t);
+                copy_done = std::max(copy_done, host) + ug;
+                host += kWaitMs + kLaunchMs;
+                merge_done = std::max(merge_done, copy_done + kLaunchMs) + 2.0 * bytes / pack_rate + mg +
+                             kLaunchMs * launches(gr.first, gr.second);
             }
+            if (!fits) continue;
             if (merge_done < best) {
                 best = merge_done;
                 best_groups = cand;
@@ -1212,6 +1280,24 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
     // stream, the copies of group g+1 cross the link on a stream of the library's own.
     std::vector<std::pair<size_t, size_t>> groups;
     plan_upload_groups(t, tg, rec, swap ? &old : nullptr, &groups);
+    // the grouped path copies straight from the caller's memory: pinned factors only, each group's share
+    // of the staging memory in one piece
+    std::vector<std::vector<UploadJob>> group_jobs;
+    if (groups.size() > 1) {
+        bool ok = true;
+        for (const auto& gr : groups) {
+            group_jobs.emplace_back();
+            rc = upload_jobs(t, tg, rec, gr.first, gr.second, &group_jobs.back());
+            if (rc) return rc;
+            size_t need = 0;
+            for (const UploadJob& j : group_jobs.back()) {
+                need = align_up(need, kSlotAlign) + j.bytes;
+                ok = ok && j.pinned;
+            }
+            ok = ok && need <= staging_span(t);
+        }
+        if (!ok) groups.assign(1, {0, rec.targets.size()});
+    }
     if (groups.size() <= 1) {
         rc = upload_adapter(t, tg, rec, (hipStream_t)stream, (hipStream_t)stream);
         if (rc) return rc;
@@ -1221,33 +1307,85 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
         rc = ensure_upload_stream(t);
         if (rc) return rc;
         rates_update(t);
-        // the staging buffers and the region to be written were last used by work on the caller's stream
-        HIP_TRY(hipEventRecord(t->ev_up_begin, (hipStream_t)stream));
+        // Two streams, and as few cross-stream waits as possible (each costs the calling thread tens of
+        // microseconds, more than a launch): the library's stream carries nothing but the copies, group
+        // after group without a pause, each group into its own piece of the staging memory; the caller's
+        // stream waits once per group for that group's copies, packs it and merges it.
+        hipStream_t cs = (hipStream_t)stream;
+        rc = wait_marks(t, kMarkLora, cs);                       // the region may still be read by a pass on another stream
+        if (rc) return rc;
+        HIP_TRY(hipEventRecord(t->ev_up_begin, cs));             // staging memory and region: last used on the caller's stream ...
         HIP_TRY(hipStreamWaitEvent(t->up_stream, t->ev_up_begin, 0));
-        HIP_TRY(hipStreamWaitEvent(t->pack_stream, t->ev_up_begin, 0));
+        for (int b = 0; b < 2; ++b)                              // ... or on some other one
+            if (t->staging_rec[b] && t->staging_stream[b] != cs) HIP_TRY(hipStreamWaitEvent(t->up_stream, t->staging_free[b], 0));
         const bool calibrate = !t->rates.pending;
         std::vector<char> in_new(t->slots.size(), 0);
         for (const PackedTarget& p : rec.targets) in_new[p.slot] = 1;
-        int chunk = 0;
+        const size_t cap = staging_span(t);
+        struct Span { size_t lo, hi; bool packed_recorded; };
+        std::vector<Span> spans;                                 // staging bytes of the groups so far
+        size_t pos = 0;
+#ifdef TIDAL_TUNING_KNOBS
+        const bool trace_host = getenv("TIDAL_TRACE_HOST") != nullptr;
+        const auto h0 = std::chrono::steady_clock::now();
+        auto hmark = [&](const char* what, size_t g) {
+            if (trace_host)
+                fprintf(stderr, "[host] g%zu %-10s %8.1f us\n", g, what,
+                        std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - h0).count());
+        };
+#else
+        auto hmark = [](const char*, size_t) {};
+#endif
         for (size_t g = 0; g < groups.size(); ++g) {
-            // copies on one stream, packing on a second, merges on the caller's: the copy engine never waits
-            // for a kernel, and the caller's stream carries nothing but the merges.  The first group's copies,
-            // bracketed by two events, give the link rate (nothing else is in flight on that stream then).
+            hmark("begin", g);
+            const auto& jobs = group_jobs[g];
+            size_t need = 0;
+            for (const UploadJob& j : jobs) need = align_up(need, kSlotAlign) + j.bytes;
+            if (pos + need > cap) pos = 0;                       // groups never straddle the end (each fits: the planner saw to it)
+            // a piece of staging memory that an earlier group of this call used must have been packed
+            for (size_t k = 0; k < spans.size(); ++k)
+                if (spans[k].lo < pos + need && pos < spans[k].hi) {
+                    HIP_TRY(hipStreamWaitEvent(t->up_stream, t->ev_group_packed[k], 0));
+                    spans[k].lo = spans[k].hi = 0;
+                }
             if (g == 0 && calibrate) HIP_TRY(hipEventRecord(t->rates.ev[0], t->up_stream));
-            rc = upload_adapter(t, tg, rec, t->up_stream, t->pack_stream, groups[g].first, groups[g].second, &chunk);
+            Pipeline pl{t, t->up_stream, t->up_stream};
+            pl.kernel_copy = true;
+            std::vector<PackSegment> segs;
+            size_t off = pos;
+            double up_bytes = 0.0;
+            for (const UploadJob& job : jobs) {
+                off = align_up(off, kSlotAlign);
+                char* dst = t->arena + t->lay.staging[0] + off;
+                rc = pl.put(false, 0, 0, job.host, job.bytes, dst);
+                if (rc) return rc;
+                PackSegment sg = job.seg;
+                sg.src = dst;
+                segs.push_back(sg);
+                if (job.has2) {
+                    sg = job.seg2;
+                    sg.src = dst;
+                    segs.push_back(sg);
+                }
+                off += job.bytes;
+                up_bytes += (double)job.bytes;
+            }
+            rc = pl.flush();
+            if (!rc) rc = pl.flush_kernel_copies();
             if (rc) return rc;
+            spans.push_back(Span{pos, pos + need, false});
+            pos += need;
             if (g == 0 && calibrate) {
                 HIP_TRY(hipEventRecord(t->rates.ev[1], t->up_stream));
-                double up_bytes = 0.0;
-                for (size_t i = groups[0].first; i < groups[0].second; ++i) {
-                    const PackedTarget& p = rec.targets[i];
-                    const SlotState& sl = t->slots[p.slot];
-                    if (p.active() && sl.elems > 0) up_bytes += (double)p.r * (double)(sl.rows + sl.cols) * (double)dtype_size(tg[i].dtype);
-                }
                 t->rates.up_bytes = up_bytes;
             }
-            HIP_TRY(hipEventRecord(t->ev_group_packed[g], t->pack_stream));
-            HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, t->ev_group_packed[g], 0));
+            HIP_TRY(hipEventRecord(t->ev_group_copied[g], t->up_stream));
+            hmark("uploaded", g);
+            HIP_TRY(hipStreamWaitEvent(cs, t->ev_group_copied[g], 0));
+            rc = launch_packs(segs, cs);
+            if (rc) return rc;
+            // whether a later group will reuse this piece is not known yet: the record costs next to nothing
+            if (g + 1 < groups.size()) HIP_TRY(hipEventRecord(t->ev_group_packed[g], cs));
             AdapterRec part_new, part_old;
             part_new.dev = rec.dev;
             part_new.targets.assign(rec.targets.begin() + groups[g].first, rec.targets.begin() + groups[g].second);
@@ -1259,17 +1397,29 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
                     if (here[p.slot] || (g + 1 == groups.size() && !in_new[p.slot])) part_old.targets.push_back(p);
             }
             const bool last = g + 1 == groups.size();
-            if (last && calibrate) HIP_TRY(hipEventRecord(t->rates.ev[2], (hipStream_t)stream));   // behind the wait for the last pack
+            if (last) {
+                // later users of the staging buffers, on whatever stream, order themselves behind the packs
+                for (int b = 0; b < 2; ++b) {
+                    HIP_TRY(hipEventRecord(t->staging_free[b], cs));
+                    t->staging_rec[b] = true;
+                    t->staging_stream[b] = cs;
+                }
+            }
+            if (last && calibrate) HIP_TRY(hipEventRecord(t->rates.ev[2], cs));
             const uint64_t before = t->stats.rmw_elems;
-            rc = do_swap_launch(t, swap ? &part_old : nullptr, &part_new, (hipStream_t)stream);
+            rc = do_swap_launch(t, swap ? &part_old : nullptr, &part_new, cs);
             if (rc) return rc;
+            hmark("launched", g);
             if (last && calibrate) {
-                HIP_TRY(hipEventRecord(t->rates.ev[3], (hipStream_t)stream));
+                HIP_TRY(hipEventRecord(t->rates.ev[3], cs));
                 t->rates.rmw_bytes = 4.0 * (double)(t->stats.rmw_elems - before);
                 t->rates.pending = true;
             }
         }
     }
+#ifdef TIDAL_TUNING_KNOBS
+    if (getenv("TIDAL_TRACE_HOST")) host_call_report();
+#endif
     set_attached(t, rec, nullptr, region);
     return TIDAL_OK;
 }
@@ -1952,9 +2102,10 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
         }
         if (t->up_stream) {
             (void)hipStreamSynchronize(t->up_stream);
-            (void)hipStreamSynchronize(t->pack_stream);
-            (void)hipStreamDestroy(t->pack_stream);
-            for (int g = 0; g < kMaxUploadGroups; ++g) (void)hipEventDestroy(t->ev_group_packed[g]);
+            for (int g = 0; g < kMaxUploadGroups; ++g) {
+                (void)hipEventDestroy(t->ev_group_copied[g]);
+                (void)hipEventDestroy(t->ev_group_packed[g]);
+            }
             (void)hipEventDestroy(t->ev_up_begin);
             for (int k = 0; k < 4; ++k) (void)hipEventDestroy(t->rates.ev[k]);
             (void)hipStreamDestroy(t->up_stream);

@@ -333,15 +333,25 @@ def test_pipelined_upload_gives_the_same_bits(G, flags):
     shapes = [(512, 1024)] * 26 + [(100, 130)]
     arrays = {i: rng.uniform(-0.05, 0.05, s).astype(np.float16) for i, s in enumerate(shapes)}
 
-    def adapter(seed, slots, r):
-        g = np.random.default_rng(seed)
-        return [(s, 2.0 * r, g.normal(0, 0.05, (r, shapes[s][1])).astype(np.float32),
-                 g.normal(0, 0.05, (shapes[s][0], r)).astype(np.float32)) for s in slots]
+    keep = []
 
-    a0 = adapter(1, range(0, 27), 64)                      # 5.1 MB packed: enough to be pipelined
-    a1 = adapter(2, range(3, 26), 64)                      # leaves slots 0-2 and 26 to the old adapter only
+    def pinned(a):                                         # the grouped path takes pinned factors only
+        k, v = G.pinned_like(a)
+        keep.append(k)
+        return v
+
+    def adapter(seed, slots, r, pin):
+        g = np.random.default_rng(seed)
+        stage = pinned if pin else (lambda a: a)
+        return [(s, 2.0 * r, stage(g.normal(0, 0.05, (r, shapes[s][1])).astype(np.float32)),
+                 stage(g.normal(0, 0.05, (shapes[s][0], r)).astype(np.float32))) for s in slots]
+
     res = []
-    for extra in (tb.TIDAL_FLAG_SERIAL_UPLOAD, tb.TIDAL_FLAG_PIPELINED_UPLOAD):
+    # serial; grouped; grouped asked for with pageable factors (which then take the single pass after all)
+    for extra, pin in ((tb.TIDAL_FLAG_SERIAL_UPLOAD, True), (tb.TIDAL_FLAG_PIPELINED_UPLOAD, True),
+                       (tb.TIDAL_FLAG_PIPELINED_UPLOAD, False)):
+        a0 = adapter(1, range(0, 27), 64, pin)             # 5.1 MB packed: enough to be pipelined
+        a1 = adapter(2, range(3, 26), 64, pin)             # leaves slots 0-2 and 26 to the old adapter only
         with G.Template(shapes, max_adapter_bytes=8 << 20, flags=flags | extra) as T:
             T.materialize(arrays)
             T.attach(a0)
@@ -352,9 +362,11 @@ def test_pipelined_upload_gives_the_same_bits(G, flags):
             T.detach()
             res.append((s_att, s_swp, [T.slot(i) for i in range(len(shapes))], n_att))
     assert res[1][3] > res[0][3]                           # it did take several launches
-    for k in range(3):
-        for i in range(len(shapes)):
-            assert np.array_equal(res[0][k][i], res[1][k][i]), (k, i)
+    assert res[2][3] == res[0][3]
+    for other in (1, 2):
+        for k in range(3):
+            for i in range(len(shapes)):
+                assert np.array_equal(res[0][k][i], res[other][k][i]), (other, k, i)
 
 
 @pytest.mark.parametrize("out,inn,r", [(203, 331, 5), (77, 8203, 5)], ids=["gathered", "pinned-direct"])
