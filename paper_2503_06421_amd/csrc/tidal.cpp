@@ -491,6 +491,7 @@ struct Pipeline {
     // kernel on the same stream follows and the copy -> kernel hand-over would dominate).  They
     // collect here and go out in one launch per kMaxCopyRuns, at the latest in copies_done().
     bool kernel_copy = false;
+    size_t kernel_copy_max = kKernelCopyMax;
     CopyBatch kbatch;
     int kruns = 0;
     int64_t paced_chunks = 0;       // staged chunks still to come for which the host stays two ahead of the GPU (see acquire)
@@ -507,7 +508,7 @@ struct Pipeline {
         if (!run) return TIDAL_OK;
         run = false;
         t->stats.h2d_copies++;
-        if (kernel_copy && run_len <= kKernelCopyMax && (uintptr_t)run_src % 16 == 0 && (uintptr_t)run_dst % 16 == 0) {
+        if (kernel_copy && run_len <= kernel_copy_max && (uintptr_t)run_src % 16 == 0 && (uintptr_t)run_dst % 16 == 0) {
             void* view = nullptr;            // the GPU's address for this pinned host memory
             if (HIP_TIMED(hipHostGetDevicePointer(&view, const_cast<char*>(run_src), 0)) == hipSuccess && view &&
                 (uintptr_t)view % 16 == 0) {
@@ -1148,8 +1149,9 @@ static void rates_update(tidal_template* t) {
     }
     float up_ms = 0.f, rmw_ms = 0.f;
     // copies of a few megabytes and more run at the link's rate; smaller ones measure latency: keep the estimate then
-    if (hipEventElapsedTime(&up_ms, r.ev[0], r.ev[1]) == hipSuccess && up_ms > 1e-3f && r.up_bytes >= 4.0e6)
-        r.link_bytes_per_ms = r.up_bytes / up_ms;
+    // (and a copy that shared the link or waited for its turn reads low: the estimate only drifts down slowly)
+    if (hipEventElapsedTime(&up_ms, r.ev[0], r.ev[1]) == hipSuccess && up_ms > 1e-3f && r.up_bytes >= 8.0e6)
+        r.link_bytes_per_ms = std::max(0.9 * r.link_bytes_per_ms, r.up_bytes / up_ms);
     if (hipEventElapsedTime(&rmw_ms, r.ev[2], r.ev[3]) == hipSuccess && rmw_ms > 1e-3f && r.rmw_bytes > 0.0)
         r.rmw_bytes_per_ms = r.rmw_bytes / rmw_ms;
     (void)hipGetLastError();
@@ -1170,6 +1172,8 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
     constexpr size_t kPipelineFrom = (size_t)4 << 20;
     constexpr double kLaunchMs = 0.02;             // what one more launch costs: its bubble, its ramp and tail
     constexpr double kWaitMs = 0.04;               // what a cross-stream wait costs the calling thread
+    constexpr double kHandoverMs = 0.03;           // from the end of a group's copies to the start of its pack on the other stream
+    constexpr double kGroupMs = 0.035;             // what one more group costs the caller's stream (measured on 64 targets of 4096 x 4096)
     const size_t n = rec.targets.size();
     groups->clear();
     groups->push_back({0, n});
@@ -1237,16 +1241,18 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
             if (cand.size() < 2) continue;
             // the link carries the groups back to back, as soon as the calling thread has got to them; the
             // caller's stream takes each group when its copies are in: pack, then merge
-            double host = kWaitMs, copy_done = 0.0, merge_done = 0.0;
-            bool fits = true;
+            // (the first group's copies run on the caller's stream and share the link with the second's)
+            double link_done = kWaitMs, merge_done = 0.0;
+            bool fits = true, first_group = true;
             for (const auto& gr : cand) {
                 double ug = 0.0, mg = 0.0, bytes = 0.0;
                 for (size_t i = gr.first; i < gr.second; ++i) { ug += u[i]; mg += m[i]; bytes += raw[i]; }
                 fits = fits && bytes <= 0.5 * (double)staging_span(t);
-                copy_done = std::max(copy_done, host) + ug;
-                host += kWaitMs + kLaunchMs;
-                merge_done = std::max(merge_done, copy_done + kLaunchMs) + 2.0 * bytes / pack_rate + mg +
-                             kLaunchMs * launches(gr.first, gr.second);
+                link_done += ug;                                 // the link's total does not depend on who shares it
+                const double here = first_group ? 1.5 * ug : link_done + kHandoverMs;
+                merge_done = std::max(merge_done, here) + 2.0 * bytes / pack_rate + mg + kGroupMs +
+                             kLaunchMs * (launches(gr.first, gr.second) - 1);
+                first_group = false;
             }
             if (!fits) continue;
             if (merge_done < best) {
@@ -1256,6 +1262,26 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
         }
     }
     *groups = best_groups;
+#ifdef TIDAL_TUNING_KNOBS
+    if (const char* e = getenv("TIDAL_UP_GROUPS")) {           // tuning builds only: "4,12,48" = targets per group
+        std::vector<std::pair<size_t, size_t>> forced_groups;
+        size_t a0 = 0;
+        while (*e && a0 < n) {
+            const size_t cnt = (size_t)strtol(e, const_cast<char**>(&e), 10);
+            if (*e == ',') ++e;
+            if (cnt == 0) break;
+            forced_groups.push_back({a0, std::min(n, a0 + cnt)});
+            a0 = std::min(n, a0 + cnt);
+        }
+        if (a0 < n) forced_groups.push_back({a0, n});
+        if (forced_groups.size() >= 1 && forced_groups.size() <= (size_t)kMaxUploadGroups) *groups = forced_groups;
+    }
+    if (getenv("TIDAL_TRACE_HOST")) {
+        fprintf(stderr, "[groups]");
+        for (const auto& gr : *groups) fprintf(stderr, " %zu", gr.second - gr.first);
+        fprintf(stderr, "  (link %.1f GB/s, pass %.2f TB/s)\n", t->rates.link_bytes_per_ms / 1e6, t->rates.rmw_bytes_per_ms / 1e9);
+    }
+#endif
 }
 
 // attach (swap = false) or swap (swap = true) an adapter given by host pointers
@@ -1308,22 +1334,28 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
         if (rc) return rc;
         rates_update(t);
         // Two streams, and as few cross-stream waits as possible (each costs the calling thread tens of
-        // microseconds, more than a launch): the library's stream carries nothing but the copies, group
-        // after group without a pause, each group into its own piece of the staging memory; the caller's
+        // microseconds, more than a launch).  The first group stays on the caller's stream altogether:
+        // copy, pack, merge, no event.  The copies of all later groups go to the library's stream at once,
+        // back to back from the start, each group into its own piece of the staging memory; the caller's
         // stream waits once per group for that group's copies, packs it and merges it.
         hipStream_t cs = (hipStream_t)stream;
+        const size_t G = groups.size();
         rc = wait_marks(t, kMarkLora, cs);                       // the region may still be read by a pass on another stream
         if (rc) return rc;
-        HIP_TRY(hipEventRecord(t->ev_up_begin, cs));             // staging memory and region: last used on the caller's stream ...
+        HIP_TRY(hipEventRecord(t->ev_up_begin, cs));             // staging memory: last used on the caller's stream ...
         HIP_TRY(hipStreamWaitEvent(t->up_stream, t->ev_up_begin, 0));
         for (int b = 0; b < 2; ++b)                              // ... or on some other one
-            if (t->staging_rec[b] && t->staging_stream[b] != cs) HIP_TRY(hipStreamWaitEvent(t->up_stream, t->staging_free[b], 0));
+            if (t->staging_rec[b] && t->staging_stream[b] != cs) {
+                HIP_TRY(hipStreamWaitEvent(t->up_stream, t->staging_free[b], 0));
+                HIP_TRY(hipStreamWaitEvent(cs, t->staging_free[b], 0));
+            }
         const bool calibrate = !t->rates.pending;
         std::vector<char> in_new(t->slots.size(), 0);
         for (const PackedTarget& p : rec.targets) in_new[p.slot] = 1;
         const size_t cap = staging_span(t);
-        struct Span { size_t lo, hi; bool packed_recorded; };
-        std::vector<Span> spans;                                 // staging bytes of the groups so far
+        struct Span { size_t lo, hi; };
+        std::vector<Span> spans;                                 // staging bytes of the groups whose copies are enqueued
+        std::vector<std::vector<PackSegment>> group_segs(G);
         size_t pos = 0;
 #ifdef TIDAL_TUNING_KNOBS
         const bool trace_host = getenv("TIDAL_TRACE_HOST") != nullptr;
@@ -1336,56 +1368,72 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
 #else
         auto hmark = [](const char*, size_t) {};
 #endif
-        for (size_t g = 0; g < groups.size(); ++g) {
-            hmark("begin", g);
-            const auto& jobs = group_jobs[g];
-            size_t need = 0;
-            for (const UploadJob& j : jobs) need = align_up(need, kSlotAlign) + j.bytes;
-            if (pos + need > cap) pos = 0;                       // groups never straddle the end (each fits: the planner saw to it)
-            // a piece of staging memory that an earlier group of this call used must have been packed
-            for (size_t k = 0; k < spans.size(); ++k)
-                if (spans[k].lo < pos + need && pos < spans[k].hi) {
-                    HIP_TRY(hipStreamWaitEvent(t->up_stream, t->ev_group_packed[k], 0));
-                    spans[k].lo = spans[k].hi = 0;
-                }
-            if (g == 0 && calibrate) HIP_TRY(hipEventRecord(t->rates.ev[0], t->up_stream));
-            Pipeline pl{t, t->up_stream, t->up_stream};
-            pl.kernel_copy = true;
-            std::vector<PackSegment> segs;
-            size_t off = pos;
-            double up_bytes = 0.0;
-            for (const UploadJob& job : jobs) {
-                off = align_up(off, kSlotAlign);
-                char* dst = t->arena + t->lay.staging[0] + off;
-                rc = pl.put(false, 0, 0, job.host, job.bytes, dst);
-                if (rc) return rc;
-                PackSegment sg = job.seg;
-                sg.src = dst;
-                segs.push_back(sg);
-                if (job.has2) {
-                    sg = job.seg2;
+        // Enqueue the copies of the next groups, as far as their pieces of staging memory are free or
+        // become free behind packs that are enqueued already (those of groups < packed_upto).
+        size_t copied_upto = 0;
+        auto enqueue_copies = [&](size_t packed_upto) -> int {
+            while (copied_upto < G) {
+                const size_t g = copied_upto;
+                hipStream_t on = g == 0 ? cs : t->up_stream;
+                const auto& jobs = group_jobs[g];
+                size_t need = 0;
+                for (const UploadJob& j : jobs) need = align_up(need, kSlotAlign) + j.bytes;
+                size_t at = pos + need > cap ? 0 : pos;          // groups never straddle the end (each fits: checked above)
+                for (size_t k = 0; k < spans.size(); ++k)
+                    if (spans[k].lo < at + need && at < spans[k].hi && k >= packed_upto) return TIDAL_OK;   // not yet
+                for (size_t k = 0; k < spans.size(); ++k)
+                    if (spans[k].lo < at + need && at < spans[k].hi) {
+                        HIP_TRY(hipStreamWaitEvent(on, t->ev_group_packed[k], 0));
+                        spans[k].lo = spans[k].hi = 0;
+                    }
+                const bool timed = calibrate && g + 1 == G;      // the last group has the link to itself
+                if (timed) HIP_TRY(hipEventRecord(t->rates.ev[0], on));
+                Pipeline pl{t, on, on};
+                pl.kernel_copy = true;
+                // the first group's pack follows on the same stream: a kernel that fetches the factors spares the
+                // hand-over from the copy engine, which costs more than a few megabytes take to cross the link
+                if (g == 0) pl.kernel_copy_max = (size_t)8 << 20;
+                size_t off = at;
+                double up_bytes = 0.0;
+                for (const UploadJob& job : jobs) {
+                    off = align_up(off, kSlotAlign);
+                    char* dst = t->arena + t->lay.staging[0] + off;
+                    int prc = pl.put(false, 0, 0, job.host, job.bytes, dst);
+                    if (prc) return prc;
+                    PackSegment sg = job.seg;
                     sg.src = dst;
-                    segs.push_back(sg);
+                    group_segs[g].push_back(sg);
+                    if (job.has2) {
+                        sg = job.seg2;
+                        sg.src = dst;
+                        group_segs[g].push_back(sg);
+                    }
+                    off += job.bytes;
+                    up_bytes += (double)job.bytes;
                 }
-                off += job.bytes;
-                up_bytes += (double)job.bytes;
+                int prc = pl.flush();
+                if (!prc) prc = pl.flush_kernel_copies();
+                if (prc) return prc;
+                spans.push_back(Span{at, at + need});
+                pos = at + need;
+                if (timed) {
+                    HIP_TRY(hipEventRecord(t->rates.ev[1], on));
+                    t->rates.up_bytes = up_bytes;
+                }
+                if (g > 0) HIP_TRY(hipEventRecord(t->ev_group_copied[g], on));
+                hmark("copies", g);
+                ++copied_upto;
             }
-            rc = pl.flush();
-            if (!rc) rc = pl.flush_kernel_copies();
+            return TIDAL_OK;
+        };
+        for (size_t g = 0; g < G; ++g) {
+            rc = enqueue_copies(g);                              // at least group g's, as a rule all that are left
             if (rc) return rc;
-            spans.push_back(Span{pos, pos + need, false});
-            pos += need;
-            if (g == 0 && calibrate) {
-                HIP_TRY(hipEventRecord(t->rates.ev[1], t->up_stream));
-                t->rates.up_bytes = up_bytes;
-            }
-            HIP_TRY(hipEventRecord(t->ev_group_copied[g], t->up_stream));
-            hmark("uploaded", g);
-            HIP_TRY(hipStreamWaitEvent(cs, t->ev_group_copied[g], 0));
-            rc = launch_packs(segs, cs);
+            if (copied_upto <= g) return fail(TIDAL_E_STATE, "internal: group %zu has no staging memory", g);
+            if (g > 0) HIP_TRY(hipStreamWaitEvent(cs, t->ev_group_copied[g], 0));
+            rc = launch_packs(group_segs[g], cs);
             if (rc) return rc;
-            // whether a later group will reuse this piece is not known yet: the record costs next to nothing
-            if (g + 1 < groups.size()) HIP_TRY(hipEventRecord(t->ev_group_packed[g], cs));
+            if (g + 1 < G) HIP_TRY(hipEventRecord(t->ev_group_packed[g], cs));   // a later group may want this piece
             AdapterRec part_new, part_old;
             part_new.dev = rec.dev;
             part_new.targets.assign(rec.targets.begin() + groups[g].first, rec.targets.begin() + groups[g].second);
@@ -1394,9 +1442,9 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
                 for (const PackedTarget& p : part_new.targets) here[p.slot] = 1;
                 part_old.dev = old.dev;
                 for (const PackedTarget& p : old.targets)       // slots only the old adapter touches go last
-                    if (here[p.slot] || (g + 1 == groups.size() && !in_new[p.slot])) part_old.targets.push_back(p);
+                    if (here[p.slot] || (g + 1 == G && !in_new[p.slot])) part_old.targets.push_back(p);
             }
-            const bool last = g + 1 == groups.size();
+            const bool last = g + 1 == G;
             if (last) {
                 // later users of the staging buffers, on whatever stream, order themselves behind the packs
                 for (int b = 0; b < 2; ++b) {
