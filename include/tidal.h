@@ -129,7 +129,8 @@ typedef struct {
                                   (pieces of 8 MiB or more are split among them); 0 = 4, at most
                                   16.  One thread moves about half of what the link carries.     */
     int32_t chunks_ahead;      /* tidal_materialize enqueues a load of up to this many staged chunks
-                                  in one burst and returns; in a longer load the calling thread
+                                  in one burst and returns (chunks of earlier loads that are still
+                                  in flight count against it); in a longer load the calling thread
                                   stays two chunks ahead of the GPU until only this many remain
                                   (many hundreds of queued cross-stream waits slow every copy
                                   down, small chunks sooner than large ones).  0 = chunk_bytes /

@@ -187,6 +187,10 @@ struct tidal_template {
     hipEvent_t ev_group_copied[kMaxUploadGroups] = {}; // up_stream: the group's factors are in the staging memory
     hipEvent_t ev_group_packed[kMaxUploadGroups] = {}; // caller's stream: ... and have been read from there again
     hipStream_t staging_stream[2] = {nullptr, nullptr};   // the stream staging_free[b] was last recorded on
+    // staged chunks of earlier loads that may still be queued: one record per load that staged any
+    struct LoadMark { hipEvent_t done; int64_t chunks; };
+    std::vector<LoadMark> load_marks;                  // oldest first
+    std::vector<hipEvent_t> load_mark_pool;
     RateModel rates;
     char* bounce[2] = {nullptr, nullptr};              // pinned host, chunk_bytes each
     bool bounce_used[2] = {false, false};
@@ -495,6 +499,7 @@ struct Pipeline {
     CopyBatch kbatch;
     int kruns = 0;
     int64_t paced_chunks = 0;       // staged chunks still to come for which the host stays two ahead of the GPU (see acquire)
+    int64_t staged_total = 0;       // staged chunks of this load
 
     int flush_kernel_copies() {
         if (kruns == 0) return TIDAL_OK;
@@ -632,7 +637,17 @@ static int materialize_impl(tidal_template* t, std::vector<SourceInfo>& infos, b
                 ++staged_chunks;
                 last = p.chunk;
             }
-        pl.paced_chunks = std::max<int64_t>(0, staged_chunks - t->cfg.chunks_ahead);
+        // the burst budget is what earlier loads, as far as they are still in flight, have left of it
+        int64_t queued = 0;
+        while (!t->load_marks.empty() && hipEventQuery(t->load_marks.front().done) == hipSuccess) {
+            t->load_mark_pool.push_back(t->load_marks.front().done);
+            t->load_marks.erase(t->load_marks.begin());
+        }
+        (void)hipGetLastError();                           // hipErrorNotReady is no error here
+        for (const auto& m : t->load_marks) queued += m.chunks;
+        const int64_t budget = std::max<int64_t>(0, (int64_t)t->cfg.chunks_ahead - queued);
+        pl.paced_chunks = std::max<int64_t>(0, staged_chunks - budget);
+        pl.staged_total = staged_chunks;
     }
     // LoRA kernels of this template may have run on another stream: order after them
     rc = wait_marks(t, kMarkLora, pl.compute);
@@ -720,6 +735,17 @@ static int materialize_impl(tidal_template* t, std::vector<SourceInfo>& infos, b
     }
     rc = mark_done(t, kMarkLoad, pl.compute);
     if (rc) return rc;
+    if (pl.staged_total > 0 && !(t->cfg.flags & TIDAL_FLAG_ASYNC_ENQUEUE)) {
+        hipEvent_t e = nullptr;
+        if (!t->load_mark_pool.empty()) {
+            e = t->load_mark_pool.back();
+            t->load_mark_pool.pop_back();
+        } else {
+            HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        }
+        HIP_TRY(hipEventRecord(e, pl.compute));
+        t->load_marks.push_back({e, pl.staged_total});
+    }
     for (const SourceInfo& s : infos) t->slots[s.slot].materialised = true;
     if (!direct.targets.empty()) {
         // bf16 sources are exact in the slot already: the in-place merge is the same single rounding
@@ -2141,6 +2167,8 @@ extern "C" int tidal_template_destroy(tidal_template* t) {
     if (!t) return TIDAL_OK;
     int rc = tidal_template_sync(t);
     if (t->dev_ready) {
+        for (const auto& m : t->load_marks) (void)hipEventDestroy(m.done);
+        for (hipEvent_t e : t->load_mark_pool) (void)hipEventDestroy(e);
         for (int b = 0; b < 2; ++b) {
             if (t->bounce_used[b]) (void)hipEventSynchronize(t->bounce_free[b]);
             (void)hipEventDestroy(t->staged_ready[b]);
