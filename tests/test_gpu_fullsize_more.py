@@ -53,14 +53,27 @@ def test_llama2_13b_shaped_materialize_attach(orc):
     assert len(sampled) == 28
     # adapters: every target gets factors; the sampled ones are drawn per slot, the rest share
     # one pair per shape (their result is covered by the launch being the same kernel and table)
+    # (factors in pinned memory: the library then uploads and merges in groups of targets, through
+    # staging memory smaller than the adapter -- the path the 13B-shaped benchmark takes)
     shared, items, keep = {}, [], []
+
+    def pinned(pair):
+        out = []
+        for a in pair:
+            tns = torch.empty(a.nbytes, dtype=torch.uint8, pin_memory=True)
+            v = tns.numpy().view(a.dtype).reshape(a.shape)
+            v[...] = a
+            keep.append(tns)
+            out.append(v)
+        return tuple(out)
+
     for s in wl.lora_slots:
         t = wl.tensors[s]
         if s in sampled:
-            A, B = wl_mod.draw_adapter(wl, 0, s)
+            A, B = pinned(wl_mod.draw_adapter(wl, 0, s))
         else:
             if (t.rows, t.cols) not in shared:
-                shared[(t.rows, t.cols)] = wl_mod.draw_adapter(wl, 0, s)
+                shared[(t.rows, t.cols)] = pinned(wl_mod.draw_adapter(wl, 0, s))
             A, B = shared[(t.rows, t.cols)]
         items.append((s, wl.alpha, A, B))
     adapter_bytes = sum(2 * 64 * (wl.tensors[s].rows + wl.tensors[s].cols) for s in wl.lora_slots)
@@ -124,7 +137,7 @@ def test_llama2_13b_shaped_materialize_attach(orc):
         st = tb.tidal_get_stats(T)
         assert st["rmw_elems"] == wl.lora_w_elements
         # uploaded and merged in groups of targets, each group one launch per shape (5120^2, 13824x5120, 5120x13824)
-        assert 3 <= st["lora_launches"] <= 3 * 8 + 1
+        assert 2 * 3 <= st["lora_launches"] <= 3 * 8 + 1, st["lora_launches"]
     finally:
         torch.cuda.synchronize()
         tb.tidal_template_destroy(T)

@@ -347,12 +347,13 @@ def test_pipelined_upload_gives_the_same_bits(G, flags):
                  stage(g.normal(0, 0.05, (shapes[s][0], r)).astype(np.float32))) for s in slots]
 
     res = []
-    # serial; grouped; grouped asked for with pageable factors (which then take the single pass after all)
-    for extra, pin in ((tb.TIDAL_FLAG_SERIAL_UPLOAD, True), (tb.TIDAL_FLAG_PIPELINED_UPLOAD, True),
-                       (tb.TIDAL_FLAG_PIPELINED_UPLOAD, False)):
+    # serial; grouped; grouped asked for with pageable factors (which then take the single pass after all);
+    # grouped through 4 MiB of staging memory for 10.6 MB of factors (groups reuse it behind the packs)
+    for extra, pin, chunk in ((tb.TIDAL_FLAG_SERIAL_UPLOAD, True, 0), (tb.TIDAL_FLAG_PIPELINED_UPLOAD, True, 0),
+                              (tb.TIDAL_FLAG_PIPELINED_UPLOAD, False, 0), (tb.TIDAL_FLAG_PIPELINED_UPLOAD, True, 2 << 20)):
         a0 = adapter(1, range(0, 27), 64, pin)             # 5.1 MB packed: enough to be pipelined
         a1 = adapter(2, range(3, 26), 64, pin)             # leaves slots 0-2 and 26 to the old adapter only
-        with G.Template(shapes, max_adapter_bytes=8 << 20, flags=flags | extra) as T:
+        with G.Template(shapes, max_adapter_bytes=8 << 20, flags=flags | extra, chunk_bytes=chunk) as T:
             T.materialize(arrays)
             T.attach(a0)
             s_att = [T.slot(i) for i in range(len(shapes))]
@@ -363,7 +364,8 @@ def test_pipelined_upload_gives_the_same_bits(G, flags):
             res.append((s_att, s_swp, [T.slot(i) for i in range(len(shapes))], n_att))
     assert res[1][3] > res[0][3]                           # it did take several launches
     assert res[2][3] == res[0][3]
-    for other in (1, 2):
+    assert res[3][3] >= 5                                  # groups of at most half the staging memory: at least six
+    for other in (1, 2, 3):
         for k in range(3):
             for i in range(len(shapes)):
                 assert np.array_equal(res[0][k][i], res[other][k][i]), (other, k, i)
