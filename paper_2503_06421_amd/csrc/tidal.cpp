@@ -167,6 +167,9 @@ struct tidal_adapter {
     tidal_template* owner;
     AdapterRec rec;
     bool attached;
+    // host-side shortcuts of the unmerged apply, which runs once per layer and decode step
+    mutable bool upload_seen_done = false;          // rec.ready was found complete once: no more stream waits on it
+    mutable std::vector<int32_t> target_of_slot;    // slot -> index into rec.targets, -1: not a target (built on first use)
 };
 
 struct tidal_template {
@@ -1608,11 +1611,15 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
     for (int32_t a = 0; a < n_adapters; ++a) {
         if (!adapters[a]) return fail(TIDAL_E_INVAL, "adapter %d is NULL", a);
         if (adapters[a]->owner != t) return fail(TIDAL_E_INVAL, "adapter %d belongs to another template", a);
+        const tidal_adapter* ad = adapters[a];
+        if (ad->target_of_slot.empty()) {
+            ad->target_of_slot.assign(t->slots.size(), -1);
+            for (size_t i = 0; i < ad->rec.targets.size(); ++i) ad->target_of_slot[ad->rec.targets[i].slot] = (int32_t)i;
+        }
         for (int32_t k = 0; k < n_slots; ++k) {
-            for (const PackedTarget& p : adapters[a]->rec.targets)
-                if (p.slot == slots[k]) entry[(size_t)a * n_slots + k] = &p;
-            if (!entry[(size_t)a * n_slots + k])
-                return fail(TIDAL_E_INVAL, "adapter %d does not target slot %d", a, slots[k]);
+            const int32_t at = ad->target_of_slot[slots[k]];
+            if (at < 0) return fail(TIDAL_E_INVAL, "adapter %d does not target slot %d", a, slots[k]);
+            entry[(size_t)a * n_slots + k] = &ad->rec.targets[at];
         }
     }
     // segments: in range, disjoint
@@ -1695,8 +1702,15 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
     int rc = no_alloc ? TIDAL_OK : ensure_device(t);
     if (rc) return rc;
     hipStream_t stream = (hipStream_t)stream_;
-    for (int32_t a = 0; a < n_adapters; ++a)                                         // the uploads of the adapters in use
-        if (used[a] && adapters[a]->rec.ready) HIP_TRY(hipStreamWaitEvent(stream, adapters[a]->rec.ready, 0));
+    for (int32_t a = 0; a < n_adapters; ++a) {                                       // the uploads of the adapters in use
+        if (!used[a] || !adapters[a]->rec.ready || adapters[a]->upload_seen_done) continue;
+        if (hipEventQuery(adapters[a]->rec.ready) == hipSuccess) {
+            adapters[a]->upload_seen_done = true;                                    // finished uploads need no wait, now or later
+            continue;
+        }
+        (void)hipGetLastError();                                                     // hipErrorNotReady is no error here
+        HIP_TRY(hipStreamWaitEvent(stream, adapters[a]->rec.ready, 0));
+    }
 
     // with ordered accumulation every segment takes the (slow, bit-reproducible) ordered kernels
     const bool ordered = (t->cfg.flags & TIDAL_FLAG_ORDERED_ACCUM) != 0;
@@ -1802,11 +1816,11 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
             b.adapter_base = lowest;
             b.n_slots = n_slots;
             memcpy(b.slot, slot_tab, sizeof slot_tab);
-            std::map<int32_t, int> fac_of;
+            std::vector<int> fac_of((size_t)std::max(n_adapters, 1), -1);      // adapter -> its first factor entry of this launch
             int n = 0, nfac = 0;
             while (at + n < shorts.size() && n < kMaxApplyShort) {
                 const HostSeg& g = shorts[at + n];
-                if (!fac_of.count(g.adapter)) {
+                if (fac_of[g.adapter] < 0) {
                     if (nfac + n_slots > kMaxApplyFactors) break;
                     fac_of[g.adapter] = nfac;
                     for (int32_t k = 0; k < n_slots; ++k) b.fac[nfac + k] = facs[(size_t)g.adapter * n_slots + k];
@@ -1839,7 +1853,14 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
             rc = run_long(false, rp);
             if (rc) return rc;
         }
-    return run_short(false);
+    rc = run_short(false);
+#ifdef TIDAL_TUNING_KNOBS
+    if (getenv("TIDAL_TRACE_HOST")) {
+        static int calls = 0;
+        if (++calls % 64 == 0) host_call_report();
+    }
+#endif
+    return rc;
 }
 
 extern "C" int tidal_lora_apply(tidal_template* t, int32_t slot, const tidal_adapter* const* adapters,
