@@ -273,10 +273,10 @@ def run_stack(tag, wl, args, pcie_peak, pool_limit, steps, warmup, with_swap, cp
             by_shape = {}
             for idx, s in enumerate(wl.lora_slots):
                 by_shape.setdefault((wl.tensors[s].rows, wl.tensors[s].cols), []).append(idx)
-            order = []                       # first, last, middle target of every shape, round robin over shapes
-            for pick in (0, -1, 1):
+            order = []                       # first, last, middle, then further targets of every shape, round robin over shapes,
+            for frac in (0.0, 1.0, 0.5, 0.25, 0.75, 0.125, 0.875, 0.375, 0.625, 0.0625, 0.9375):   # until the time budget is spent
                 for shape, idxs in by_shape.items():
-                    order.append(idxs[pick if pick <= 0 else len(idxs) // 2])
+                    order.append(idxs[min(len(idxs) - 1, int(frac * (len(idxs) - 1) + 0.5))])
             seen = set()
             for k, idx in enumerate(order):
                 if idx in seen:
