@@ -407,6 +407,14 @@ int tidal_h2d_peak(void* dev /* [device] */, size_t bytes, int32_t reps, void* s
 int tidal_hbm_rmw_peak(void* dev /* [device] in/out */, int64_t rows, int64_t cols, int64_t n, int32_t blocks_per_walk,
                        int32_t reps, void* stream, double* gbytes_per_s /* [host] out */);
 
+/* The same walk with only its loads (TIDAL_PROBE_READ) or only its stores (TIDAL_PROBE_WRITE: fills the
+ * memory with an address pattern, the previous contents are lost), 2 bytes per element; TIDAL_PROBE_RMW is
+ * tidal_hbm_rmw_peak.  Separates what the read side and the write side of the memory system make of a
+ * row pitch and a walk length.  Arguments and errors as above; unknown mode: TIDAL_E_INVAL. */
+enum { TIDAL_PROBE_RMW = 0, TIDAL_PROBE_READ = 1, TIDAL_PROBE_WRITE = 2 };
+int tidal_hbm_probe(void* dev /* [device] in/out */, int64_t rows, int64_t cols, int64_t n, int32_t blocks_per_walk,
+                    int32_t mode, int32_t reps, void* stream, double* gbytes_per_s /* [host] out */);
+
 int tidal_get_stats(tidal_template* t, tidal_stats* out /* [host] out */);
 int tidal_reset_stats(tidal_template* t);
 

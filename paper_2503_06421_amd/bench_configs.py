@@ -1,7 +1,7 @@
 """Measurements of the other workload configurations (bench.py at the repository root times the
 Llama2-7B-shaped headline workload).
 
-    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging|apply|coldstart|pitch
+    python -m paper_2503_06421_amd.bench_configs --config single|13b|churn|70b|overlap|merging|apply|coldstart|pitch|probe
 
 Each prints one JSON line.  Kernel times come from the library's HIP events around each launch
 (TIDAL_FLAG_KERNEL_TIMING); call-level times from events on the compute stream.
@@ -241,6 +241,27 @@ def bench_pitch(args):
         finally:
             T.close()
         del T
+        torch.cuda.empty_cache()
+    return out
+
+
+def bench_probe(args):
+    """What this memory system makes of a row pitch and a walk length, with the LoRA kernels' tiling and no arithmetic:
+    about 4 GiB of matrices per width, each 256-column strip walked down in runs of 1, 4 or 16 blocks of 32 rows, as
+    loads only, stores only and read-modify-write (tidal_hbm_probe)."""
+    widths = [4096, 5120, 8192, 11008, 13824, 28672]
+    out = {"config": "hbm_probe_by_row_pitch", "widths": []}
+    for cols in widths:
+        rows = 4096
+        n = max(1, (4 << 30) // (rows * cols * 2))
+        mem = torch.zeros(n * rows * cols, dtype=torch.int16, device="cuda:0")
+        rec = {"cols": cols, "row_pitch_bytes": 2 * cols, "matrices": n, "GiB": round(n * rows * cols * 2 / 2 ** 30, 2)}
+        for mode, name in ((tb.TIDAL_PROBE_READ, "read"), (tb.TIDAL_PROBE_WRITE, "write"), (tb.TIDAL_PROBE_RMW, "rmw")):
+            for walk in (1, 4, 16):
+                rec["%s_walk%d_GBps" % (name, walk)] = round(tb.tidal_hbm_probe(mem, rows, cols, n, walk, mode, 4), 1)
+        out["widths"].append(rec)
+        log(json.dumps(rec))
+        del mem
         torch.cuda.empty_cache()
     return out
 
@@ -571,7 +592,7 @@ def bench_apply(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply", "coldstart", "pitch"])
+    ap.add_argument("--config", required=True, choices=["single", "13b", "churn", "70b", "overlap", "merging", "apply", "coldstart", "pitch", "probe"])
     ap.add_argument("--rank", type=int, default=64, help="pitch: rank of the merged adapter")
     ap.add_argument("--reps", type=int, default=2)
     ap.add_argument("--pool-gib", type=float, default=0.0, help="wrap the host pool into this many GiB (70b default: 24)")
@@ -587,6 +608,8 @@ def main():
         out = bench_stack(args, wl_mod.llama2_13b(), int(args.pool_gib * 2**30) if args.pool_gib else None)
     elif args.config == "70b":
         out = bench_stack(args, wl_mod.llama3_70b(), int((args.pool_gib or 24.0) * 2**30))
+    elif args.config == "probe":
+        out = bench_probe(args)
     elif args.config == "overlap":
         out = bench_overlap(args)
     elif args.config == "merging":

@@ -35,7 +35,7 @@ EXPORTS = [
     "tidal_fork_required_bytes", "tidal_fork_create",
     "tidal_fork_apply", "tidal_fork_slot_ptr", "tidal_fork_destroy", "tidal_template_slot_ptr",
     "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
-    "tidal_convert_device", "tidal_h2d_peak", "tidal_hbm_rmw_peak", "tidal_get_stats",
+    "tidal_convert_device", "tidal_h2d_peak", "tidal_hbm_rmw_peak", "tidal_hbm_probe", "tidal_get_stats",
     "tidal_reset_stats", "tidal_template_sync", "tidal_template_destroy", "tidal_last_error",
 ]
 
@@ -153,6 +153,7 @@ def lib() -> ctypes.CDLL:
     L.tidal_convert_device.argtypes = [vp, vp, c_int32, c_int64, vp]
     L.tidal_h2d_peak.argtypes = [vp, c_size_t, c_int32, vp, POINTER(c_double)]
     L.tidal_hbm_rmw_peak.argtypes = [vp, c_int64, c_int64, c_int64, c_int32, c_int32, vp, POINTER(c_double)]
+    L.tidal_hbm_probe.argtypes = [vp, c_int64, c_int64, c_int64, c_int32, c_int32, c_int32, vp, POINTER(c_double)]
     L.tidal_get_stats.argtypes = [vp, POINTER(tidal_stats)]
     L.tidal_reset_stats.argtypes = [vp]
     L.tidal_template_sync.argtypes = [vp]
@@ -457,6 +458,16 @@ def tidal_convert_device(dst, src, dtype: int, n: int, stream=None) -> None:
 def tidal_h2d_peak(dev, nbytes: int, reps: int = 5, stream=None) -> float:
     out = c_double()
     _check(lib().tidal_h2d_peak(device_ptr(dev), nbytes, reps, stream_ptr(stream), byref(out)))
+    return out.value
+
+
+TIDAL_PROBE_RMW, TIDAL_PROBE_READ, TIDAL_PROBE_WRITE = 0, 1, 2
+
+
+def tidal_hbm_probe(dev, rows: int, cols: int, n: int, blocks_per_walk: int = 4, mode: int = TIDAL_PROBE_RMW, reps: int = 4,
+                    stream=None) -> float:
+    out = c_double(0.0)
+    _check(lib().tidal_hbm_probe(device_ptr(dev), rows, cols, n, blocks_per_walk, mode, reps, stream_ptr(stream), byref(out)))
     return out.value
 
 

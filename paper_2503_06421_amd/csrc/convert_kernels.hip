@@ -345,6 +345,10 @@ hipError_t launch_slot_checksum(const void* slot, int64_t elems, int passes, voi
 // one bit of every word and stores them back: the memory traffic of a LoRA pass (4 bytes per
 // element) and nothing else.  What this runs at is the ceiling of the in-place pass for that
 // row pitch and walk length.  rows % 32 == 0 and cols % 256 == 0 (checked by the launcher).
+// MODE 0: read-modify-write (above); 1: the loads alone (what is read is folded into one word that is
+// stored only if it has a value no input produces, so the loads cannot be dropped); 2: the stores alone
+// (a pattern of the address: the memory's previous contents are lost).
+template <int MODE>
 __global__ __launch_bounds__(256) void rmw_probe_kernel(uint16_t* base, int rows, int cols, int strips, int rowblocks,
                                                         int rc, long long total_items) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -361,32 +365,47 @@ __global__ __launch_bounds__(256) void rmw_probe_kernel(uint16_t* base, int rows
     uint16_t* W = base + mat * (long long)rows * cols;
     const int rb_end = (rowchunk + 1) * rc < rowblocks ? (rowchunk + 1) * rc : rowblocks;
     const int n = lane & 31, h = lane >> 5;
+    uint32_t fold = 0;
     for (int rb = rowchunk * rc; rb < rb_end; ++rb) {
         u32x4 w[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            w[v] = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4*)(W + (long long)row * cols + strip * 256 + n * 8));
+            if constexpr (MODE != 2)
+                w[v] = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4*)(W + (long long)row * cols + strip * 256 + n * 8));
+            else
+                w[v] = u32x4{(uint32_t)row, (uint32_t)strip, (uint32_t)n, 0u};
         }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) w[v] ^= 1u;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            __builtin_nontemporal_store(w[v], (__attribute__((address_space(1))) u32x4*)(W + (long long)row * cols + strip * 256 + n * 8));
+            if constexpr (MODE == 0) w[v] ^= 1u;
+            if constexpr (MODE == 1) fold |= (w[v].x & w[v].y & w[v].z & w[v].w);
         }
+        if constexpr (MODE != 1) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rb * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                __builtin_nontemporal_store(w[v], (__attribute__((address_space(1))) u32x4*)(W + (long long)row * cols + strip * 256 + n * 8));
+            }
+        }
+    }
+    if constexpr (MODE == 1) {
+        // bf16 data never has all bits set in four words of the same position of every row: practically never taken
+        if (fold == 0xFFFFFFFFu && rows < 0) ((__attribute__((address_space(1))) uint32_t*)W)[0] = fold;
     }
 }
 
-hipError_t launch_rmw_probe(void* base, int64_t rows, int64_t cols, int64_t n, int rc, hipStream_t stream) {
-    if (!base || rows <= 0 || cols <= 0 || n <= 0 || rc < 1) return hipErrorInvalidValue;
+hipError_t launch_rmw_probe(void* base, int64_t rows, int64_t cols, int64_t n, int rc, int mode, hipStream_t stream) {
+    if (!base || rows <= 0 || cols <= 0 || n <= 0 || rc < 1 || mode < 0 || mode > 2) return hipErrorInvalidValue;
     if (rows % 32 || cols % 256 || rows > 0x7FFFFFFF || cols > 0x7FFFFFFF || (uintptr_t)base % 16) return hipErrorInvalidValue;
     const int strips = (int)(cols / 256), rowblocks = (int)(rows / 32);
     const int64_t total = (int64_t)strips * ((rowblocks + rc - 1) / rc) * n;
     const int64_t blocks = ((total + 3) / 4 + 7) / 8 * 8;
     if (blocks > 0x7FFFFFF0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(rmw_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (uint16_t*)base, (int)rows, (int)cols,
-                       strips, rowblocks, rc, (long long)total);
+    const dim3 grid((unsigned)blocks);
+    if (mode == 0) hipLaunchKernelGGL(rmw_probe_kernel<0>, grid, dim3(256), 0, stream, (uint16_t*)base, (int)rows, (int)cols, strips, rowblocks, rc, (long long)total);
+    else if (mode == 1) hipLaunchKernelGGL(rmw_probe_kernel<1>, grid, dim3(256), 0, stream, (uint16_t*)base, (int)rows, (int)cols, strips, rowblocks, rc, (long long)total);
+    else hipLaunchKernelGGL(rmw_probe_kernel<2>, grid, dim3(256), 0, stream, (uint16_t*)base, (int)rows, (int)cols, strips, rowblocks, rc, (long long)total);
     return hipGetLastError();
 }
 

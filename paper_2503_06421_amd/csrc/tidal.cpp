@@ -2129,13 +2129,15 @@ extern "C" int tidal_h2d_peak(void* dev, size_t bytes, int32_t reps, void* strea
     return TIDAL_OK;
 }
 
-extern "C" int tidal_hbm_rmw_peak(void* dev, int64_t rows, int64_t cols, int64_t n, int32_t blocks_per_walk, int32_t reps,
-                                  void* stream, double* gbytes_per_s) {
+extern "C" int tidal_hbm_probe(void* dev, int64_t rows, int64_t cols, int64_t n, int32_t blocks_per_walk, int32_t mode,
+                               int32_t reps, void* stream, double* gbytes_per_s) {
     if (!dev || !gbytes_per_s || reps <= 0) return fail(TIDAL_E_INVAL, "bad argument");
     if (rows <= 0 || cols <= 0 || n <= 0 || rows % 32 || cols % 256 || rows > 0x7FFFFFFF || cols > 0x7FFFFFFF)
         return fail(TIDAL_E_INVAL, "rows must be a positive multiple of 32 and cols of 256");
     if (blocks_per_walk < 1 || blocks_per_walk > 1024) return fail(TIDAL_E_INVAL, "blocks_per_walk outside 1..1024");
+    if (mode < TIDAL_PROBE_RMW || mode > TIDAL_PROBE_WRITE) return fail(TIDAL_E_INVAL, "unknown probe mode %d", mode);
     if ((uintptr_t)dev % 16) return fail(TIDAL_E_INVAL, "dev is not 16-byte aligned");
+    const double bytes_per_elem = mode == TIDAL_PROBE_RMW ? 4.0 : 2.0;
     hipEvent_t a = nullptr, b = nullptr;
     hipError_t e = hipEventCreate(&a);
     if (e == hipSuccess) e = hipEventCreate(&b);
@@ -2143,18 +2145,24 @@ extern "C" int tidal_hbm_rmw_peak(void* dev, int64_t rows, int64_t cols, int64_t
     double best = 0.0;
     for (int i = 0; i < reps + 1 && e == hipSuccess; ++i) {     // first pass is a warm-up
         e = hipEventRecord(a, s);
-        if (e == hipSuccess) e = launch_rmw_probe(dev, rows, cols, n, blocks_per_walk, s);
+        if (e == hipSuccess) e = launch_rmw_probe(dev, rows, cols, n, blocks_per_walk, mode, s);
         if (e == hipSuccess) e = hipEventRecord(b, s);
         if (e == hipSuccess) e = hipEventSynchronize(b);
         float ms = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
-        if (e == hipSuccess && i > 0 && ms > 0.f) best = std::max(best, 4.0 * (double)rows * (double)cols * (double)n / (ms * 1e-3) / 1e9);
+        if (e == hipSuccess && i > 0 && ms > 0.f)
+            best = std::max(best, bytes_per_elem * (double)rows * (double)cols * (double)n / (ms * 1e-3) / 1e9);
     }
     if (a) (void)hipEventDestroy(a);
     if (b) (void)hipEventDestroy(b);
-    if (e != hipSuccess) return fail(TIDAL_E_HIP, "read-modify-write probe failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return fail(TIDAL_E_HIP, "memory probe failed: %s", hipGetErrorString(e));
     *gbytes_per_s = best;
     return TIDAL_OK;
+}
+
+extern "C" int tidal_hbm_rmw_peak(void* dev, int64_t rows, int64_t cols, int64_t n, int32_t blocks_per_walk, int32_t reps,
+                                  void* stream, double* gbytes_per_s) {
+    return tidal_hbm_probe(dev, rows, cols, n, blocks_per_walk, TIDAL_PROBE_RMW, reps, stream, gbytes_per_s);
 }
 
 extern "C" int tidal_get_stats(tidal_template* t, tidal_stats* out) {

@@ -26,7 +26,7 @@ hipError_t launch_convert(const ConvertBatch& batch, int nseg, hipStream_t strea
 hipError_t launch_slot_checksum(const void* slot, int64_t elems, int passes, void* dev_sum, hipStream_t stream);
 // Bare in-place read-modify-write over n matrices of rows x cols 16-bit elements in the LoRA kernels'
 // tiling (256-column strips, rc blocks of 32 rows per wave); rows % 32 == 0, cols % 256 == 0.
-hipError_t launch_rmw_probe(void* base, int64_t rows, int64_t cols, int64_t n, int rc, hipStream_t stream);
+hipError_t launch_rmw_probe(void* base, int64_t rows, int64_t cols, int64_t n, int rc, int mode, hipStream_t stream);
 
 // ---- packing of LoRA factors ------------------------------------------------------------
 enum PackLayout {

@@ -5,7 +5,7 @@
 namespace tidal {
 hipError_t launch_convert(const ConvertBatch&, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_slot_checksum(const void*, int64_t, int, void*, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_rmw_probe(void*, int64_t, int64_t, int64_t, int, hipStream_t) { return hipErrorNotSupported; }
+hipError_t launch_rmw_probe(void*, int64_t, int64_t, int64_t, int, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_pack(const PackBatch&, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_copy_from_host(const CopyBatch&, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_lora_mfma(const LoraGroup&, const LoraLaunchPlan&, hipStream_t) { return hipErrorNotSupported; }
