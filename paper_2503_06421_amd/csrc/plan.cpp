@@ -126,7 +126,7 @@ void plan_copies(const std::vector<SourceInfo>& srcs, const tidal_config& cfg, i
 // launch plan of a LoRA read-modify-write group
 // ---------------------------------------------------------------------------------------
 TuningKnobs tuning_knobs() {
-    TuningKnobs k = {-1, -1, -1, -1, -1, -1, -1, -1};
+    TuningKnobs k = {-1, -1, -1, -1, -1, -1, -1, -1, 0, {0, 0, 0, 0, 0, 0, 0, 0}, -1};
 #ifdef TIDAL_TUNING_KNOBS
     auto read = [](const char* name, int lo, int hi) {
         const char* e = getenv(name);
@@ -142,6 +142,16 @@ TuningKnobs tuning_knobs() {
     k.apply_ct = read("TIDAL_APPLY_CT", 1, kApplyChunkTiles);
     k.apply_tile_rows = read("TIDAL_APPLY_TILE_ROWS", 16, 32);
     if (k.apply_tile_rows != 16 && k.apply_tile_rows != 32) k.apply_tile_rows = -1;
+    k.trace_host = read("TIDAL_TRACE_HOST", 0, 1);
+    if (const char* e = getenv("TIDAL_UP_GROUPS")) {
+        while (*e && k.n_up_groups < 8) {
+            char* end = nullptr;
+            const long cnt = strtol(e, &end, 10);
+            if (end == e || cnt <= 0) break;
+            k.up_groups[k.n_up_groups++] = (int)cnt;
+            e = *end == ',' ? end + 1 : end;
+        }
+    }
     k.apply_two_step = read("TIDAL_APPLY_TWO_STEP", 0, 1);
 #endif
     return k;

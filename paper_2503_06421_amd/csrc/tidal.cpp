@@ -7,7 +7,6 @@
 #include <string.h>
 
 #include <algorithm>
-#include <chrono>
 #include <map>
 #include <mutex>
 #include <new>
@@ -16,6 +15,7 @@
 #include <tuple>
 #include <vector>
 
+#include "host_trace.h"
 #include "plan.h"
 #include "tidal_internal.h"
 
@@ -33,41 +33,6 @@ static int fail(int code, const char* fmt, ...) {
     va_end(ap);
     return code;
 }
-
-#ifdef TIDAL_TUNING_KNOBS
-// tuning builds: host time per kind of HIP call, printed by whoever asks (TIDAL_TRACE_HOST)
-struct HostCallStat { const char* what; double us; long n; };
-static HostCallStat g_call_stats[64];
-static int g_n_call_stats = 0;
-static void host_call_add(const char* what, double us) {
-    size_t len = 0;
-    while (what[len] && what[len] != '(') ++len;
-    for (int i = 0; i < g_n_call_stats; ++i)
-        if (!strncmp(g_call_stats[i].what, what, len) && g_call_stats[i].what[len] == '(') {
-            g_call_stats[i].us += us;
-            g_call_stats[i].n++;
-            return;
-        }
-    if (g_n_call_stats < 64) g_call_stats[g_n_call_stats++] = HostCallStat{what, us, 1};
-}
-static void host_call_report() {
-    for (int i = 0; i < g_n_call_stats; ++i) {
-        size_t len = 0;
-        while (g_call_stats[i].what[len] && g_call_stats[i].what[len] != '(') ++len;
-        fprintf(stderr, "[hostcalls] %-32.*s n=%5ld total %9.1f us\n", (int)len, g_call_stats[i].what, g_call_stats[i].n, g_call_stats[i].us);
-    }
-    g_n_call_stats = 0;
-}
-#define HIP_TIMED(expr)                                                                            \
-    [&]() {                                                                                        \
-        const auto t0_ = std::chrono::steady_clock::now();                                         \
-        hipError_t r_ = (expr);                                                                    \
-        host_call_add(#expr, std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0_).count()); \
-        return r_;                                                                                 \
-    }()
-#else
-#define HIP_TIMED(expr) (expr)
-#endif
 
 #define HIP_TRY(expr)                                                                              \
     do {                                                                                           \
@@ -1291,26 +1256,22 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
         }
     }
     *groups = best_groups;
-#ifdef TIDAL_TUNING_KNOBS
-    if (const char* e = getenv("TIDAL_UP_GROUPS")) {           // tuning builds only: "4,12,48" = targets per group
+    const TuningKnobs knobs = tuning_knobs();                 // tuning builds only: targets per group, given outright
+    if (knobs.n_up_groups > 0) {
         std::vector<std::pair<size_t, size_t>> forced_groups;
         size_t a0 = 0;
-        while (*e && a0 < n) {
-            const size_t cnt = (size_t)strtol(e, const_cast<char**>(&e), 10);
-            if (*e == ',') ++e;
-            if (cnt == 0) break;
-            forced_groups.push_back({a0, std::min(n, a0 + cnt)});
-            a0 = std::min(n, a0 + cnt);
+        for (int k = 0; k < knobs.n_up_groups && a0 < n; ++k) {
+            forced_groups.push_back({a0, std::min(n, a0 + (size_t)knobs.up_groups[k])});
+            a0 = forced_groups.back().second;
         }
         if (a0 < n) forced_groups.push_back({a0, n});
-        if (forced_groups.size() >= 1 && forced_groups.size() <= (size_t)kMaxUploadGroups) *groups = forced_groups;
+        if (forced_groups.size() <= (size_t)kMaxUploadGroups) *groups = forced_groups;
     }
-    if (getenv("TIDAL_TRACE_HOST")) {
+    if (host_trace_on()) {
         fprintf(stderr, "[groups]");
         for (const auto& gr : *groups) fprintf(stderr, " %zu", gr.second - gr.first);
         fprintf(stderr, "  (link %.1f GB/s, pass %.2f TB/s)\n", t->rates.link_bytes_per_ms / 1e6, t->rates.rmw_bytes_per_ms / 1e9);
     }
-#endif
 }
 
 // attach (swap = false) or swap (swap = true) an adapter given by host pointers
@@ -1386,17 +1347,8 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
         std::vector<Span> spans;                                 // staging bytes of the groups whose copies are enqueued
         std::vector<std::vector<PackSegment>> group_segs(G);
         size_t pos = 0;
-#ifdef TIDAL_TUNING_KNOBS
-        const bool trace_host = getenv("TIDAL_TRACE_HOST") != nullptr;
-        const auto h0 = std::chrono::steady_clock::now();
-        auto hmark = [&](const char* what, size_t g) {
-            if (trace_host)
-                fprintf(stderr, "[host] g%zu %-10s %8.1f us\n", g, what,
-                        std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - h0).count());
-        };
-#else
-        auto hmark = [](const char*, size_t) {};
-#endif
+        HostTrace trace;                                         // tuning builds: host time of each step; nothing otherwise
+        auto hmark = [&](const char* what, size_t g) { trace.mark(what, g); };
         // Enqueue the copies of the next groups, as far as their pieces of staging memory are free or
         // become free behind packs that are enqueued already (those of groups < packed_upto).
         size_t copied_upto = 0;
@@ -1494,9 +1446,7 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
             }
         }
     }
-#ifdef TIDAL_TUNING_KNOBS
-    if (getenv("TIDAL_TRACE_HOST")) host_call_report();
-#endif
+    host_call_report();
     set_attached(t, rec, nullptr, region);
     return TIDAL_OK;
 }
@@ -1854,12 +1804,7 @@ static int lora_apply_impl(tidal_template* t, const int32_t* slots, int32_t n_sl
             if (rc) return rc;
         }
     rc = run_short(false);
-#ifdef TIDAL_TUNING_KNOBS
-    if (getenv("TIDAL_TRACE_HOST")) {
-        static int calls = 0;
-        if (++calls % 64 == 0) host_call_report();
-    }
-#endif
+    host_call_report(64);
     return rc;
 }
 

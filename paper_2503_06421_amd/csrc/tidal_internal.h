@@ -228,6 +228,9 @@ struct TuningKnobs {
     int mfma_dynlds;    // TIDAL_MFMA_DYNLDS: extra LDS bytes per workgroup (limits workgroups per CU)
     int apply_ct;       // TIDAL_APPLY_CT: 32-token tiles per wave of the expand kernel
     int apply_tile_rows; // TIDAL_APPLY_TILE_ROWS: 16 or 32 token rows per workgroup of the fused prompt kernel
+    int trace_host;     // TIDAL_TRACE_HOST: 1 = print the calling thread's time per HIP call and per step (host_trace.h)
+    int n_up_groups;    // TIDAL_UP_GROUPS: "4,12,48" = targets per group of the grouped adapter upload, given outright
+    int up_groups[8];
     int apply_two_step; // TIDAL_APPLY_TWO_STEP: 1 = prompts as two launches (shrink, expand) instead of the fused one
 };
 TuningKnobs tuning_knobs();
