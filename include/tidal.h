@@ -24,7 +24,8 @@
  *     streams; in addition every LoRA / fork call waits (on the GPU) for the template's
  *     last materialisation and every materialisation for its last LoRA call, whatever
  *     streams those used.  LoRA calls among themselves are ordered only by their streams:
- *     issue them on one stream or order them yourself.  One thread at a time per template.
+ *     issue them on one stream or order them yourself.  One thread at a time per template;
+ *     different templates may be driven from different threads at the same time.
  *   - Adapters and forks refer to their template: destroy them before it.
  *   - Every int-returning call returns TIDAL_OK (0) or a negative tidal_status;
  *     tidal_last_error() then holds a message (thread-local).  Arguments are validated

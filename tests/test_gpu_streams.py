@@ -148,3 +148,49 @@ def test_apply_and_fork_wait_for_the_upload(orc):
             assert np.array_equal(T.slot(0), base)
         finally:
             tb.tidal_fork_destroy(F)
+
+
+def test_two_threads_each_with_a_template_of_its_own(orc):
+    """One thread at a time per template, but templates are independent: two host threads load,
+    attach, swap and detach on their own templates at the same time (ordered accumulation: every
+    state is compared with the oracle bit for bit)."""
+    import threading
+    assert torch.cuda.is_available()
+    errors = []
+
+    def worker(seed):
+        try:
+            rng = np.random.default_rng(seed)
+            shapes = [(256, 384), (96, 520)]
+            with Template(shapes, flags=tb.TIDAL_FLAG_ORDERED_ACCUM, max_adapter_bytes=1 << 20) as T:
+                for rep in range(4):
+                    Ws = {i: rng.normal(0, 0.02, sh).astype(np.float16) for i, sh in enumerate(shapes)}
+                    T.materialize(Ws)
+                    want = {i: orc.convert_to_bf16(w) for i, w in Ws.items()}
+                    ads = []
+                    for r in (8, 24):
+                        ads.append([(i, 2.0 * r, rng.normal(0, 0.05, (r, sh[1])).astype(np.float16),
+                                     rng.normal(0, 0.05, (sh[0], r)).astype(np.float16)) for i, sh in enumerate(shapes)])
+                    T.attach(ads[0])
+                    for i, al, A, B in ads[0]:
+                        orc.lora_merge(want[i], orc.convert_to_bf16(A), orc.convert_to_bf16(B), al, +1)
+                        assert np.array_equal(T.slot(i), want[i]), (seed, rep, "attach", i)
+                    T.swap(ads[1])
+                    for (i, al0, A0, B0), (_, al1, A1, B1) in zip(ads[0], ads[1]):
+                        orc.lora_swap(want[i], orc.convert_to_bf16(A0), orc.convert_to_bf16(B0), al0,
+                                      orc.convert_to_bf16(A1), orc.convert_to_bf16(B1), al1)
+                        assert np.array_equal(T.slot(i), want[i]), (seed, rep, "swap", i)
+                    T.detach()
+                    for i, al, A, B in ads[1]:
+                        orc.lora_merge(want[i], orc.convert_to_bf16(A), orc.convert_to_bf16(B), al, -1)
+                        assert np.array_equal(T.slot(i), want[i]), (seed, rep, "detach", i)
+        except Exception as exc:                                  # noqa: BLE001 -- reported by the main thread
+            errors.append(repr(exc))
+
+    threads = [threading.Thread(target=worker, args=(s,)) for s in (11, 12)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not any(th.is_alive() for th in threads), "a worker did not finish"
+    assert not errors, errors
