@@ -27,7 +27,7 @@ SOURCES = ["tidal.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip", "
 # per-file extras: the LDS swap kernel wants its MFMA results in VGPRs (see the file's header)
 EXTRA_FLAGS = {"lora_lds_kernel.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 HEADERS = [os.path.join(ROOT, "include", "tidal.h"), os.path.join(CSRC, "tidal_internal.h"),
-           os.path.join(CSRC, "plan.h"), os.path.join(CSRC, "lora_device.h")]
+           os.path.join(CSRC, "plan.h"), os.path.join(CSRC, "lora_device.h"), os.path.join(CSRC, "host_trace.h")]
 
 # -packed-fp32-ops off: packed fp32 VALU forms are not to be generated on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
