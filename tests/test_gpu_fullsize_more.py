@@ -108,6 +108,11 @@ def test_llama2_13b_shaped_materialize_attach(orc):
         print("conversion and placement bit-exact on all %d slots" % len(views), flush=True)
 
         prev = {(s, b): host_rows(s, *b) for s in sampled for b in bands_for(wl.tensors[s].rows)}
+        # and one band (a different one each) of targets that share their factors with others of their shape
+        others = [s for s in wl.lora_slots if s not in set(sampled)][3::23]
+        for k, s in enumerate(others):
+            b = bands_for(wl.tensors[s].rows)[k % 3]
+            prev[(s, b)] = host_rows(s, *b)
         untargeted = [i for i in range(len(views)) if i not in set(wl.lora_slots)]
         before = {i: dev_slot(i).clone() for i in untargeted}
         tb.tidal_lora_attach(T, tb.targets_from_arrays(items), comp_s)
@@ -274,6 +279,11 @@ def test_llama3_70b_shaped_materialize_attach(orc):
         del scratch
 
         prev = {(s, b): host_rows(s, *b) for s in sampled for b in bands_for(wl.tensors[s].rows)}
+        # and one band (a different one each) of targets that share their factors with others of their shape
+        others = [s for s in wl.lora_slots if s not in set(sampled)][5::41]
+        for k, s in enumerate(others):
+            b = bands_for(wl.tensors[s].rows)[k % 3]
+            prev[(s, b)] = host_rows(s, *b)
         untargeted = [i for i in range(len(wl.tensors)) if i not in set(wl.lora_slots)]
         before = {i: dev_slot(i).clone() for i in untargeted}
         tb.tidal_lora_attach(T, tb.targets_from_arrays(items), comp_s)
