@@ -397,3 +397,50 @@ def test_small_factors_at_any_host_alignment(orc, G, offset, out, inn, r):
         orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 10.0, +1)
         assert np.array_equal(T.slot(0), want)
     del buf
+
+
+def test_grouped_upload_with_idle_targets_on_the_null_stream(G):
+    """The grouped path with targets that have nothing to upload (rank 0, alpha 0) spread over the
+    groups, a group that consists of such targets only, and the null stream as the caller's stream:
+    the same bits as the single pass."""
+    rng = np.random.default_rng(61)
+    shapes = [(256, 512)] * 14
+    arrays = {i: rng.uniform(-0.05, 0.05, s).astype(np.float16) for i, s in enumerate(shapes)}
+    keep = []
+
+    def pinned(a):
+        k, v = G.pinned_like(a)
+        keep.append(k)
+        return v
+
+    def adapter(seed):
+        g = np.random.default_rng(seed)
+        items = []
+        for s in range(14):
+            r = 0 if s in (0, 1, 7) else 48                 # the first group may hold nothing but idle targets
+            al = 0.0 if s == 5 else 96.0
+            items.append((s, al, pinned(g.normal(0, 0.05, (r, 512)).astype(np.float32)),
+                          pinned(g.normal(0, 0.05, (256, r)).astype(np.float32))))
+        return items
+
+    res = []
+    for extra in (tb.TIDAL_FLAG_SERIAL_UPLOAD, tb.TIDAL_FLAG_PIPELINED_UPLOAD):
+        with G.Template(shapes, max_adapter_bytes=4 << 20, flags=extra) as T:
+            T.materialize(arrays)
+            tb.tidal_lora_attach(T.h, T._targets(adapter(3)), None)
+            tb.tidal_template_sync(T.h)
+            a = [T.slot(i) for i in range(14)]
+            tb.tidal_lora_swap(T.h, T._targets(adapter(4)), None)
+            tb.tidal_template_sync(T.h)
+            b = [T.slot(i) for i in range(14)]
+            tb.tidal_lora_detach(T.h, None)
+            tb.tidal_template_sync(T.h)
+            res.append((a, b, [T.slot(i) for i in range(14)], tb.tidal_get_stats(T.h)["lora_launches"]))
+    assert res[1][3] > res[0][3]
+    base = [res[0][2][i] for i in range(14)]
+    for k in range(3):
+        for i in range(14):
+            assert np.array_equal(res[0][k][i], res[1][k][i]), (k, i)
+    for i in (0, 1, 5, 7):                                   # idle targets: untouched by attach and swap
+        assert np.array_equal(res[1][0][i], base[i]) and np.array_equal(res[1][1][i], base[i])
+    assert not np.array_equal(res[1][0][2], base[2])
