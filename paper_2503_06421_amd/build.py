@@ -22,11 +22,11 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtidal.so")
 
-SOURCES = ["tidal.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip", "lora_lds_kernel.hip",
+SOURCES = ["tidal.cpp", "tidal_lora.cpp", "tidal_apply.cpp", "plan.cpp", "convert_kernels.hip", "lora_kernels.hip", "lora_lds_kernel.hip",
            "lora_apply_kernels.hip", "convert_merge_kernel.hip"]
 # per-file extras: the LDS swap kernel wants its MFMA results in VGPRs (see the file's header)
 EXTRA_FLAGS = {"lora_lds_kernel.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
-HEADERS = [os.path.join(ROOT, "include", "tidal.h"), os.path.join(CSRC, "tidal_internal.h"),
+HEADERS = [os.path.join(ROOT, "include", "tidal.h"), os.path.join(CSRC, "tidal_internal.h"), os.path.join(CSRC, "tidal_host.h"),
            os.path.join(CSRC, "plan.h"), os.path.join(CSRC, "lora_device.h"), os.path.join(CSRC, "host_trace.h")]
 
 # -packed-fp32-ops off: packed fp32 VALU forms are not to be generated on this target.
@@ -65,7 +65,7 @@ def _compile(src: str, force: bool, tuning: bool = False) -> str:
 def build(force: bool = False, verbose: bool = False, tuning: bool = False) -> str:
     LIB = TUNING_LIB if tuning else globals()["LIB"]
     os.makedirs(OBJ + ("_tuning" if tuning else ""), exist_ok=True)
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(lambda s: _compile(s, force, tuning), SOURCES))
     if force or _stale(LIB, objs):
         tmp = LIB + ".tmp%d" % os.getpid()

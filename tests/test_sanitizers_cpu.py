@@ -49,7 +49,8 @@ def test_host_paths_of_libtidal_under_asan_ubsan(tmp_path):
     p = run(["hipcc", "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-x", "hip",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", *host_san,
              "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-             os.path.join(CSRC, "tidal.cpp"), os.path.join(CSRC, "plan.cpp"),
+             os.path.join(CSRC, "tidal.cpp"), os.path.join(CSRC, "tidal_lora.cpp"), os.path.join(CSRC, "tidal_apply.cpp"),
+             os.path.join(CSRC, "plan.cpp"),
              os.path.join(SAN, "launch_stubs.cpp"), os.path.join(SAN, "host_driver.cpp"),
              "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize", "-pthread", "-o", exe])
     assert p.returncode == 0, p.stderr[-4000:]
