@@ -490,7 +490,7 @@ def run_churn(args, cpu_seconds):
                      "first_attach_ms": round(per_step[0][2], 4),
                      "by_rank_pair_GBps": {"%d->%d" % k: round(byte_of(*k) / float(np.median(v)) / 1e6, 0) for k, v in sorted(by.items())}},
             "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(gbps / HBM_PEAK_GBPS, 4),
-                         "traffic": None, "kernel": "lora_mfma_kernel / lora_mfma_lds_kernel (by rank pair)", "avg_launch_ms": round(float(kern.mean()), 4),
+                         "traffic": measured_traffic("adapter_churn"), "kernel": "lora_mfma_kernel / lora_mfma_lds_kernel (by rank pair)", "avg_launch_ms": round(float(kern.mean()), 4),
                          "launches": len(swaps), "algorithmic_bytes_per_launch": total_bytes / len(swaps)},
             "value": round(gbps, 1)})
         log("churn: %.3f ms per swap (p95 %.3f), kernels %.1f GB/s (%.1f%% of peak)" % (float(call.mean()), float(np.percentile(call, 95)), gbps, gbps / 80))
