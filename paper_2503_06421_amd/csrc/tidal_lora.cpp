@@ -418,7 +418,7 @@ static inline size_t staging_span(const tidal_template* t) { return 2 * t->cfg.c
 static void plan_upload_groups(const tidal_template* t, const tidal_lora_target* tg, const AdapterRec& rec,
                                const AdapterRec* old, std::vector<std::pair<size_t, size_t>>* groups) {
     constexpr size_t kPipelineFrom = (size_t)4 << 20;
-    constexpr double kLaunchMs = 0.02;             // what one more launch costs: its bubble, its ramp and tail
+    constexpr double kLaunchMs = 0.045;            // what one more launch costs: its bubble, its ramp and tail (70B-shaped adapter, 16 to 28 launches)
     constexpr double kWaitMs = 0.04;               // what a cross-stream wait costs the calling thread
     constexpr double kHandoverMs = 0.03;           // from the end of a group's copies to the start of its pack on the other stream
     constexpr double kGroupMs = 0.035;             // what one more group costs the caller's stream (measured on 64 targets of 4096 x 4096)
@@ -459,14 +459,37 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
     // a single group (serial) is the candidate to beat, unless grouping is forced
     double best = forced ? 1e300 : u_total + m_total + kLaunchMs * launches(0, n);
     std::vector<std::pair<size_t, size_t>> best_groups = *groups;
-    // Candidates: G groups whose shares of the upload grow by a factor q from one to the next
-    // (q = 1: equal groups, what an upload-bound adapter wants; q > 1: a small first group, so that
-    // merging starts early, and large later ones that hide under the merges before them).  Each is
-    // simulated on three resources -- the link, the packing stream, the caller's stream -- and the
-    // one that ends first is taken.
     const double pack_rate = 2.0e9;                                      // bytes per ms through the pack kernel
+    const double group_cap = 0.5 * (double)staging_span(t);              // a group's factors: half the staging memory, so that
+                                                                         // the next group's copies need not wait for its packs
     static const double kGrowth[] = {1.0, 1.5, 2.0, 3.0};
     static const double kFirst[] = {1.0, 0.35};                           // the first group may be smaller still
+    // Simulate a candidate on three resources -- the link, the packing stream, the caller's stream -- and keep
+    // it if it ends first.  The link carries the groups back to back, as soon as the calling thread has got to
+    // them; the caller's stream takes each group when its copies are in: pack, then merge (the first group's
+    // copies run on the caller's stream and share the link with the second's).
+    auto consider = [&](const std::vector<std::pair<size_t, size_t>>& cand) {
+        if (cand.size() < 2 || cand.size() > (size_t)kMaxUploadGroups) return;
+        double link_done = kWaitMs, merge_done = 0.0;
+        bool fits = true, first_group = true;
+        for (const auto& gr : cand) {
+            double ug = 0.0, mg = 0.0, bytes = 0.0;
+            for (size_t i = gr.first; i < gr.second; ++i) { ug += u[i]; mg += m[i]; bytes += raw[i]; }
+            fits = fits && bytes <= group_cap;
+            link_done += ug;                                 // the link's total does not depend on who shares it
+            const double here = first_group ? 1.5 * ug : link_done + kHandoverMs;
+            merge_done = std::max(merge_done, here) + 2.0 * bytes / pack_rate + mg + kGroupMs +
+                         kLaunchMs * (launches(gr.first, gr.second) - 1);
+            first_group = false;
+        }
+        if (fits && merge_done < best) {
+            best = merge_done;
+            best_groups = cand;
+        }
+    };
+    // Family one: G groups whose shares of the upload grow by a factor q from one to the next (q = 1: equal
+    // groups, what an upload-bound adapter wants; q > 1: a small first group, so that merging starts early,
+    // and large later ones that hide under the merges before them).
     for (int G = 2; G <= kMaxUploadGroups && (size_t)G <= n; ++G) {
         for (int v = 0; v < 8; ++v) {
             const double q = kGrowth[v & 3], f0 = kFirst[v >> 2];
@@ -486,29 +509,33 @@ static void plan_upload_groups(const tidal_template* t, const tidal_lora_target*
                 a0 = b0;
                 if (a0 >= n) break;
             }
-            if (cand.size() < 2) continue;
-            // the link carries the groups back to back, as soon as the calling thread has got to them; the
-            // caller's stream takes each group when its copies are in: pack, then merge
-            // (the first group's copies run on the caller's stream and share the link with the second's)
-            double link_done = kWaitMs, merge_done = 0.0;
-            bool fits = true, first_group = true;
-            for (const auto& gr : cand) {
-                double ug = 0.0, mg = 0.0, bytes = 0.0;
-                for (size_t i = gr.first; i < gr.second; ++i) { ug += u[i]; mg += m[i]; bytes += raw[i]; }
-                fits = fits && bytes <= 0.5 * (double)staging_span(t);
-                link_done += ug;                                 // the link's total does not depend on who shares it
-                const double here = first_group ? 1.5 * ug : link_done + kHandoverMs;
-                merge_done = std::max(merge_done, here) + 2.0 * bytes / pack_rate + mg + kGroupMs +
-                             kLaunchMs * (launches(gr.first, gr.second) - 1);
-                first_group = false;
-            }
-            if (!fits) continue;
-            if (merge_done < best) {
-                best = merge_done;
-                best_groups = cand;
-            }
+            consider(cand);
         }
     }
+    // Family two, for adapters of several times the staging memory whose merges outlast their upload: a small
+    // first group, growth by q until a group reaches what the staging memory takes at a time, groups of that
+    // size from there on (on the 70B-shaped adapter 8 / 40 / 160 / 176 / 176 targets measure 43.4 ms per
+    // attach, seven near-equal groups 44.6).
+    static const double kStart[] = {1.0 / 128, 1.0 / 64, 1.0 / 32, 1.0 / 16};
+    static const double kSteep[] = {3.0, 4.0, 5.0};
+    double raw_total = 0.0;
+    for (size_t i = 0; i < n; ++i) raw_total += raw[i];
+    for (double start : kStart)
+        for (double q : kSteep) {
+            std::vector<std::pair<size_t, size_t>> cand;
+            size_t a0 = 0;
+            double want = start * raw_total;
+            while (a0 < n && cand.size() <= (size_t)kMaxUploadGroups) {
+                const double lim = std::min(want, group_cap);
+                size_t b0 = a0;
+                double acc = 0.0;
+                while (b0 < n && (acc + raw[b0] <= lim || b0 == a0)) acc += raw[b0++];
+                cand.push_back({a0, b0});
+                a0 = b0;
+                want *= q;
+            }
+            if (a0 == n) consider(cand);
+        }
     *groups = best_groups;
     const TuningKnobs knobs = tuning_knobs();                 // tuning builds only: targets per group, given outright
     if (knobs.n_up_groups > 0) {
