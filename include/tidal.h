@@ -133,9 +133,9 @@ typedef struct {
                                   in one burst and returns (chunks of earlier loads that are still
                                   in flight count against it); in a longer load the calling thread
                                   stays two chunks ahead of the GPU until only this many remain
-                                  (many hundreds of queued cross-stream waits slow every copy
+                                  (a few hundred queued cross-stream waits slow every copy
                                   down, small chunks sooner than large ones).  0 = chunk_bytes /
-                                  512 KiB, within 16..256 (256 for 128 MiB chunks); at most 4096. */
+                                  800 KiB, within 16..160 (160 for 128 MiB chunks); at most 4096. */
 } tidal_config;
 
 /* One planned host->device copy unit, as tidal_materialize would issue it (introspection). */

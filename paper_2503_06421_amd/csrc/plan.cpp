@@ -27,8 +27,10 @@ bool normalise_config(const tidal_config* in, tidal_config* out, const char** ms
     if (c.coalesce_bytes == 0) c.coalesce_bytes = (size_t)64 << 10;
     if (c.gather_threads == 0) c.gather_threads = 4;
     c.chunk_bytes = align_up(c.chunk_bytes, 4096);
-    // the smaller the chunks, the fewer of them may queue up before the transfer rate suffers
-    if (c.chunks_ahead == 0) c.chunks_ahead = (int32_t)std::min<size_t>(256, std::max<size_t>(16, c.chunk_bytes >> 19));
+    // the smaller the chunks, the fewer of them may queue up before the transfer rate suffers; and whatever
+    // their size, from about 200 staged chunks in flight on every copy runs 6 % slower (two loads of 101
+    // chunks of 128 MiB queued back to back: 254 ms each against 239)
+    if (c.chunks_ahead == 0) c.chunks_ahead = (int32_t)std::min<size_t>(160, std::max<size_t>(16, c.chunk_bytes / ((size_t)800 << 10)));
     c.max_adapter_bytes = align_up(c.max_adapter_bytes, kSlotAlign);
     if (c.chunk_bytes < ((size_t)64 << 10)) { *msg = "chunk_bytes below 64 KiB"; return false; }
     if (c.chunk_bytes > ((size_t)1 << 32)) { *msg = "chunk_bytes above 4 GiB"; return false; }

@@ -313,7 +313,7 @@ def test_gather_threads_default_and_range():
 
 
 def test_chunks_ahead_default_and_range():
-    assert tb.tidal_config_default().chunks_ahead == 256                      # 128 MiB chunks
+    assert tb.tidal_config_default().chunks_ahead == 160                      # 128 MiB chunks
     for kw in (dict(chunks_ahead=1), dict(chunks_ahead=4096), dict(chunk_bytes=1 << 20)):
         assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(**kw)) > 0
     assert tb.tidal_template_required_bytes([(4, 4)], tb.make_config(chunks_ahead=4097)) == 0

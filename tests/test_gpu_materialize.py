@@ -246,7 +246,7 @@ def test_every_pacing_depth_gives_the_same_slots(orc, G, ahead):
 
 
 def test_a_load_within_the_burst_budget_returns_before_it_is_done(G):
-    """1.5 GiB of pinned fp16 in 128 MiB chunks (12 chunks, default budget 256): the call only
+    """1.5 GiB of pinned fp16 in 128 MiB chunks (12 chunks, default budget 160): the call only
     enqueues, so it is back long before the ~27 ms the link needs."""
     import time
     n = 3
