@@ -254,6 +254,20 @@ typedef struct {
 int tidal_lora_launch_info(const tidal_template* t, int64_t out, int64_t in, int32_t n_targets, int32_t r_old,
                            int32_t r_new, int32_t fork, tidal_lora_launch* info /* [host] out */);
 
+/* In how many groups of targets tidal_lora_attach (swap = 0) or tidal_lora_swap (swap != 0) would
+ * carry out the dynamic initialisation of Sec. 5.2 for this adapter: one group means upload, pack,
+ * one pass; several mean that each group's factors cross the link while the group before it is
+ * merged.  Writes the number of targets of each group, in the order given, to group_targets (at most
+ * cap entries) and returns the number of groups, or a negative tidal_status (the checks of
+ * tidal_lora_attach on the target list; the attach state is not looked at, a swap with nothing
+ * attached is planned like an attach).  Host-only introspection, like tidal_materialize_plan: it
+ * uses the link and pass rates the template has measured on its grouped calls so far (fixed
+ * defaults before the first), and does not ask whether the factors are pinned (pageable factors
+ * always go in one group). */
+int32_t tidal_lora_upload_plan(tidal_template* t, const tidal_lora_target* targets /* [host] */,
+                               int32_t n_targets, int32_t swap, int32_t* group_targets /* [host] out */,
+                               int32_t cap);
+
 /* Subtract the attached adapter's delta (same packed bf16 copy that was merged): the keep-alive
  * path of Sec. 5.2 run backwards, leaving only the static state. */
 int tidal_lora_detach(tidal_template* t, void* stream);

@@ -31,7 +31,7 @@ EXPORTS = [
     "tidal_materialize_plan", "tidal_materialize_attach", "tidal_lora_attach", "tidal_lora_swap", "tidal_lora_detach",
     "tidal_adapter_required_bytes", "tidal_adapter_upload", "tidal_adapter_destroy",
     "tidal_lora_attach_adapter", "tidal_lora_swap_adapter", "tidal_lora_apply_workspace_bytes", "tidal_lora_apply", "tidal_lora_apply_multi",
-    "tidal_lora_apply_static", "tidal_lora_apply_static_max_tokens", "tidal_lora_launch_info",
+    "tidal_lora_apply_static", "tidal_lora_apply_static_max_tokens", "tidal_lora_launch_info", "tidal_lora_upload_plan",
     "tidal_fork_required_bytes", "tidal_fork_create",
     "tidal_fork_apply", "tidal_fork_slot_ptr", "tidal_fork_destroy", "tidal_template_slot_ptr",
     "tidal_template_slot_wait", "tidal_prefetch_bytes", "tidal_template_resident_prefix", "tidal_slot_checksum",
@@ -121,6 +121,8 @@ def lib() -> ctypes.CDLL:
     for name in ("tidal_lora_attach", "tidal_lora_swap"):
         getattr(L, name).argtypes = [vp, POINTER(tidal_lora_target), c_int32, vp]
     L.tidal_lora_detach.argtypes = [vp, vp]
+    L.tidal_lora_upload_plan.argtypes = [vp, POINTER(tidal_lora_target), c_int32, c_int32, POINTER(c_int32), c_int32]
+    L.tidal_lora_upload_plan.restype = c_int32
     L.tidal_lora_launch_info.argtypes = [vp, c_int64, c_int64, c_int32, c_int32, c_int32, c_int32, POINTER(tidal_lora_launch)]
     L.tidal_adapter_required_bytes.restype = c_size_t
     L.tidal_adapter_required_bytes.argtypes = [vp, POINTER(tidal_lora_target), c_int32]
@@ -318,6 +320,16 @@ def tidal_lora_launch_info(t, out: int, inn: int, n_targets: int, r_old: int, r_
     d = {k: getattr(info, k) for k, _ in tidal_lora_launch._fields_}
     d["kernel"] = d["kernel"].decode()
     return d
+
+
+def tidal_lora_upload_plan(t, targets, swap: bool = False) -> list:
+    """Targets per group, in order, as tidal_lora_attach / _swap would upload and merge them."""
+    arr, n = _target_array(targets)
+    out = (c_int32 * 64)()
+    g = lib().tidal_lora_upload_plan(t, arr, n, int(swap), out, 64)
+    if g < 0:
+        _check(g)
+    return [out[i] for i in range(min(g, 64))]
 
 
 def tidal_adapter_required_bytes(t, targets) -> int:

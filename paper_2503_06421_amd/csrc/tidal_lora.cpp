@@ -732,6 +732,20 @@ static int attach_host(tidal_template* t, const tidal_lora_target* tg, int32_t n
     return TIDAL_OK;
 }
 
+extern "C" int32_t tidal_lora_upload_plan(tidal_template* t, const tidal_lora_target* targets, int32_t n_targets,
+                                          int32_t swap, int32_t* group_targets, int32_t cap) {
+    AdapterRec rec;
+    int rc = validate_targets(t, targets, n_targets, true, &rec);
+    if (rc) return rc;
+    if (cap < 0 || (!group_targets && cap > 0)) return fail(TIDAL_E_INVAL, "bad output buffer");
+    std::vector<std::pair<size_t, size_t>> groups;
+    const AdapterRec old = t->cur;
+    plan_upload_groups(t, targets, rec, (swap && t->attached) ? &old : nullptr, &groups);
+    for (size_t g = 0; g < groups.size() && (int32_t)g < cap; ++g)
+        group_targets[g] = (int32_t)(groups[g].second - groups[g].first);
+    return (int32_t)groups.size();
+}
+
 extern "C" int tidal_materialize_attach(tidal_template* t, const tidal_src* srcs, int32_t n_src,
                                         const tidal_lora_target* targets, int32_t n_targets, void* copy_stream,
                                         void* compute_stream) {

@@ -172,9 +172,44 @@ static int validation() {
     return 0;
 }
 
+// Groups of the adapter upload over stacks of mixed shapes, ranks and chunk sizes: every target in exactly one
+// group, at most eight groups, and the planner's arithmetic under the sanitizers.
+static int upload_plans() {
+    static float fake[4];
+    for (int round = 0; round < 60; ++round) {
+        const int n = 2 + (int)(rnd() % 300);
+        const int64_t dims[] = {1024, 4096, 5120, 8192, 13824, 28672};
+        std::vector<tidal_slot_desc> slots((size_t)n);
+        for (int i = 0; i < n; ++i) slots[(size_t)i] = {dims[rnd() % 6], dims[rnd() % 6]};
+        tidal_config cfg;
+        tidal_config_default(&cfg);
+        cfg.chunk_bytes = (size_t)(1u << (24 + rnd() % 4));       // 16 to 128 MiB: the largest factor here is 7 MiB
+        if (round % 7 == 3) cfg.flags |= TIDAL_FLAG_PIPELINED_UPLOAD;
+        tidal_template* t = nullptr;
+        REQUIRE(tidal_template_create(slots.data(), n, (void*)(uintptr_t)0x700000000000ull, (size_t)1 << 46, &cfg, &t) == TIDAL_OK);
+        const int ranks[] = {0, 1, 8, 16, 32, 64};
+        std::vector<tidal_lora_target> tg;
+        for (int i = 0; i < n; ++i) {
+            if (rnd() % 5 == 0) continue;                       // not every slot is a target
+            const int r = ranks[rnd() % 6];
+            tg.push_back(tidal_lora_target{i, r, r ? 2.0f * (float)r : 0.0f, (rnd() & 1) ? TIDAL_F16 : TIDAL_F32, r ? fake : nullptr, r ? fake : nullptr});
+        }
+        int32_t groups[16];
+        const int32_t g = tidal_lora_upload_plan(t, tg.data(), (int32_t)tg.size(), round & 1, groups, 16);
+        REQUIRE(g >= 1 && g <= 8);
+        int64_t total = 0;
+        for (int k = 0; k < g; ++k) { REQUIRE(groups[k] > 0 || tg.empty()); total += groups[k]; }
+        REQUIRE(total == (int64_t)tg.size());
+        REQUIRE(tidal_lora_upload_plan(t, tg.data(), (int32_t)tg.size(), 0, nullptr, 4) == TIDAL_E_INVAL);
+        REQUIRE(tidal_template_destroy(t) == TIDAL_OK);
+    }
+    return 0;
+}
+
 int main() {
     if (fuzz_copy_plan()) return 1;
     if (launch_plans()) return 1;
+    if (upload_plans()) return 1;
     if (validation()) return 1;
     puts("host sanitizer run ok");
     return 0;

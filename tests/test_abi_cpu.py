@@ -348,3 +348,98 @@ def test_header_is_plain_c_and_links_from_c(tmp_path):
                    check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
     assert int(out[0]) == tb.tidal_template_required_bytes([(4, 8), (3, 5)])
+
+
+# ---- groups of the adapter upload (tidal_lora_attach / _swap with host pointers) ---------------------
+
+def _fake_targets(wl, r, dtype):
+    """Targets with host addresses that are never read (the plan only looks at sizes)."""
+    return [(s, r, 2.0 * r, dtype, 0x10000 + 64 * k, 0x20000 + 64 * k) for k, s in enumerate(wl.lora_slots)]
+
+
+def _raw_bytes(wl, slots, r, itemsize):
+    return sum(r * (wl.tensors[s].rows + wl.tensors[s].cols) * itemsize for s in slots)
+
+
+def test_upload_plan_of_the_listed_workloads():
+    """Default rates (55 GB/s link, 6 TB/s pass).  A merge-bound adapter gets a small first group and
+    growing later ones; an upload-bound one many near-equal groups; no group exceeds half the staging span."""
+    half_span = 128 << 20
+    seen = {}
+    for name, dt, isz in (("llama2_7b", tb.TIDAL_F16, 2), ("llama2_13b", tb.TIDAL_F16, 2), ("llama3_70b", tb.TIDAL_BF16, 2)):
+        wl = getattr(wl_mod, name)()
+        t = tb.tidal_template_create(wl.shapes, FAKE_ARENA, 1 << 40, tb.make_config())
+        try:
+            g = tb.tidal_lora_upload_plan(t, _fake_targets(wl, wl.rank, dt))
+            assert g == tb.tidal_lora_upload_plan(t, _fake_targets(wl, wl.rank, dt), swap=True)   # nothing attached
+        finally:
+            tb.tidal_template_destroy(t)
+        assert sum(g) == len(wl.lora_slots) and all(x > 0 for x in g) and 2 <= len(g) <= 8, (name, g)
+        a = 0
+        for x in g:
+            assert _raw_bytes(wl, wl.lora_slots[a:a + x], wl.rank, isz) <= half_span, (name, g)
+            a += x
+        seen[name] = g
+    # 7B: merges take twice the upload -> three groups, each about twice the one before
+    assert len(seen["llama2_7b"]) == 3 and seen["llama2_7b"][0] <= 12 and seen["llama2_7b"] == sorted(seen["llama2_7b"])
+    # 13B: upload and merges take the same time -> as many groups as there may be, equal but for a smaller first
+    g = seen["llama2_13b"]
+    assert len(g) == 8 and max(g[1:]) - min(g[1:]) <= 4 and g[0] <= g[1]
+    # 70B: merges take six times the upload -> a first group of a few megabytes, steep growth, capped by the span
+    g = seen["llama3_70b"]
+    assert len(g) <= 6 and g[0] <= 16 and g[1] >= 3 * g[0] and max(g) >= 150
+
+
+def test_upload_plan_single_group_cases_and_flags():
+    wl = wl_mod.llama2_7b()
+    tg = _fake_targets(wl, 16, tb.TIDAL_F16)
+    n = len(tg)
+    cases = [
+        (tb.make_config(flags=tb.TIDAL_FLAG_SERIAL_UPLOAD), tg, [n]),            # grouping forbidden
+        (tb.make_config(), tg[:1], [1]),                                          # one target
+        (tb.make_config(), tg[:8], [8]),                                          # 2 MiB of factors: below 4 MiB
+        (tb.make_config(chunk_bytes=1 << 20), tg, [n]),                           # no split into <= 8 groups fits 1 MiB each
+    ]
+    for cfg, targets, want in cases:
+        t = tb.tidal_template_create(wl.shapes, FAKE_ARENA, 1 << 40, cfg)
+        try:
+            assert tb.tidal_lora_upload_plan(t, targets) == want
+        finally:
+            tb.tidal_template_destroy(t)
+    # forced grouping of a small adapter; idle targets (rank 0) ride along in whatever group they fall into
+    t = tb.tidal_template_create(wl.shapes, FAKE_ARENA, 1 << 40, tb.make_config(flags=tb.TIDAL_FLAG_PIPELINED_UPLOAD))
+    try:
+        g = tb.tidal_lora_upload_plan(t, tg[:8])
+        assert len(g) >= 2 and sum(g) == 8
+        mixed = [(s, 0, 1.0, tb.TIDAL_F32, None, None) if k % 3 == 0 else x for k, (x, s) in enumerate(zip(tg, wl.lora_slots))]
+        g = tb.tidal_lora_upload_plan(t, mixed)
+        assert sum(g) == n and all(x > 0 for x in g)
+        # argument checks are those of the attach
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_upload_plan, t, [(wl.lora_slots[0], 65, 1.0, tb.TIDAL_F16, 0x1000, 0x2000)])
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_upload_plan, t, [tg[0], tg[0]])
+        _expect(tb.TIDAL_E_INVAL, tb.tidal_lora_upload_plan, t, [(10 ** 6, 8, 1.0, tb.TIDAL_F16, 0x1000, 0x2000)])
+    finally:
+        tb.tidal_template_destroy(t)
+
+
+def test_upload_plan_properties_on_random_stacks():
+    rng = np.random.default_rng(5)
+    for case in range(40):
+        n = int(rng.integers(2, 200))
+        dims = [int(rng.choice([1024, 2048, 4096, 5120, 8192, 11008])) for _ in range(2)]
+        shapes = [(dims[k % 2], dims[(k + 1) % 2]) for k in range(n)]
+        r = int(rng.choice([4, 8, 16, 32, 64]))
+        chunk = int(rng.choice([8, 32, 128])) << 20
+        t = tb.tidal_template_create(shapes, FAKE_ARENA, 1 << 42, tb.make_config(chunk_bytes=chunk))
+        try:
+            tg = [(k, r, 1.0, tb.TIDAL_F16, 0x1000, 0x2000) for k in range(n)]
+            g = tb.tidal_lora_upload_plan(t, tg)
+        finally:
+            tb.tidal_template_destroy(t)
+        assert sum(g) == n and all(x > 0 for x in g) and len(g) <= 8, (case, g)
+        if len(g) > 1:
+            a = 0
+            for x in g:
+                raw = sum(r * (shapes[k][0] + shapes[k][1]) * 2 + 512 for k in range(a, a + x))
+                assert raw <= chunk, (case, g)                           # half the span of two staging buffers
+                a += x
