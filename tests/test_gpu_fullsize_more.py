@@ -126,6 +126,7 @@ def test_llama2_13b_shaped_materialize_attach(orc):
                 prev[(s, b)] = None
         untargeted = [i for i in range(len(views)) if i not in set(wl.lora_slots)]
         before = {i: dev_slot(i).clone() for i in untargeted}
+        plan = tb.tidal_lora_upload_plan(T, tb.targets_from_arrays(items))     # the groups the attach will use
         tb.tidal_lora_attach(T, tb.targets_from_arrays(items), comp_s)
         tb.tidal_template_sync(T)
         torch.cuda.synchronize()
@@ -155,6 +156,8 @@ def test_llama2_13b_shaped_materialize_attach(orc):
         assert st["rmw_elems"] == wl.lora_w_elements
         # uploaded and merged in groups of targets, each group one launch per shape (5120^2, 13824x5120, 5120x13824)
         assert 2 * 3 <= st["lora_launches"] <= 3 * 8 + 1, st["lora_launches"]
+        assert sum(plan) == len(items) and 2 <= len(plan) <= 8
+        assert len(plan) <= st["lora_launches"] <= 3 * len(plan), (plan, st["lora_launches"])
     finally:
         torch.cuda.synchronize()
         tb.tidal_template_destroy(T)
