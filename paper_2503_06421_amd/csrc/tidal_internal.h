@@ -35,7 +35,7 @@ enum PackLayout {
     kPackBp = 2          // src: B, lines x r; dst: B in MFMA operand order, lines rounded up to 32
 };
 struct PackSegment {
-    const void* src;     // device staging
+    const void* src;     // device staging, or the GPU's view of pinned host memory
     void* dst;           // device: packed bf16, ranks zero padded to rp
     int64_t lines;       // in (for A) or out (for B)
     int32_t r, rp, dtype, layout;
