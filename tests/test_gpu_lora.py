@@ -399,6 +399,49 @@ def test_small_factors_at_any_host_alignment(orc, G, offset, out, inn, r):
     del buf
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float16], ids=["fp32", "fp16"])
+@pytest.mark.parametrize("out,inn,r", [(203, 328, 8), (96, 1000, 24), (257, 4096, 64)])
+def test_small_pinned_adapter_is_packed_straight_from_host_memory(orc, G, out, inn, r, dtype):
+    """Pinned, 16-byte aligned factors with ranks and widths that are multiples of 8, at most 2 MiB in all:
+    the pack kernel reads them from the caller's memory (no staging copy is made: the copy and chunk
+    counters stand still).  Attach by host pointers and through a resident adapter, bit for bit against
+    the oracle; then the same factors from pageable memory (staged) give the same bits."""
+    W, A, B = make_problem(300 + r, out, inn, r, dtype=dtype)
+    keep_a, a_pin = G.pinned_like(A)
+    keep_b, b_pin = G.pinned_like(B)
+    res = []
+    for a_arr, b_arr, direct in ((a_pin, b_pin, True), (A, B, False)):
+        with G.Template([(out, inn)], flags=ORDERED, max_adapter_bytes=1 << 20) as T:
+            T.materialize({0: W})
+            want = orc.convert_to_bf16(W)
+            st0 = tb.tidal_get_stats(T.h)
+            tb.tidal_lora_attach(T.h, tb.targets_from_arrays([(0, 12.0, a_arr, b_arr)]), T.compute_stream)
+            T.sync()
+            st1 = tb.tidal_get_stats(T.h)
+            assert st1["h2d_bytes"] - st0["h2d_bytes"] == A.nbytes + B.nbytes
+            assert (st1["chunks"] == st0["chunks"] and st1["h2d_copies"] == st0["h2d_copies"]) == direct
+            orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 12.0, +1)
+            assert np.array_equal(T.slot(0), want)
+            tb.tidal_lora_detach(T.h, T.compute_stream)
+            # a resident adapter (A is packed twice: transposed and row-major) from the same memory
+            tg = tb.targets_from_arrays([(0, 12.0, a_arr, b_arr)])
+            nb = tb.tidal_adapter_required_bytes(T.h, tg)
+            mem = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+            h = tb.tidal_adapter_upload(T.h, tg, mem, nb, T.compute_stream)
+            tb.tidal_lora_attach_adapter(T.h, h, T.compute_stream)
+            T.sync()
+            orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 12.0, -1)
+            orc.lora_merge(want, orc.convert_to_bf16(A), orc.convert_to_bf16(B), 12.0, +1)
+            got = T.slot(0)
+            assert np.array_equal(got, want)
+            res.append(got)
+            tb.tidal_lora_detach(T.h, T.compute_stream)
+            T.sync()
+            tb.tidal_adapter_destroy(h)
+    assert np.array_equal(res[0], res[1])
+    del keep_a, keep_b
+
+
 def test_grouped_upload_with_idle_targets_on_the_null_stream(G):
     """The grouped path with targets that have nothing to upload (rank 0, alpha 0) spread over the
     groups, a group that consists of such targets only, and the null stream as the caller's stream:
