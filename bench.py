@@ -253,6 +253,7 @@ def run_stack(tag, wl, args, pcie_peak, pool_limit, steps, warmup, with_swap, cp
                      "note": "tidal_lora_attach / _swap with host pointers: per-invocation times include the adapter's upload over PCIe "
                              "and its packing, overlapped with the merge in groups of targets (launches_per_invocation)",
                      "launches_per_invocation": launches_per_call,
+                     "upload_groups_targets": tb.tidal_lora_upload_plan(Tp.h, targets[0]),
                      "kernel_ms_per_invocation_alone": round(st["lora_kernel_ms"] / (steps * (2 if with_swap else 1)), 4),
                      "keep_alive_kernel_GBps": round(warm_gbps, 1), "keep_alive_frac_of_hbm_peak": round(warm_gbps / HBM_PEAK_GBPS, 4),
                      "keep_alive_note": "the same adapter resident in HBM, detach / attach issued back to back after the steps (the kept-alive "
